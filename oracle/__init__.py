@@ -1,0 +1,14 @@
+"""CPU fp64 oracle of the VideoScan streaming attention path (TEST INFRASTRUCTURE).
+
+Only tests, the smoke check and the CPU-baseline leg of the benchmark import this
+package.  It shares no code with the GPU library and never imports it.
+"""
+from .vs_oracle import (  # noqa: F401
+    attention,
+    compact_append,
+    decode,
+    frame_prefill,
+    mean_pool,
+    num_threads,
+    OracleError,
+)

@@ -1,0 +1,215 @@
+/*
+ * vs_oracle.c -- TEST INFRASTRUCTURE, not product code.
+ *
+ * A plain, slow CPU implementation in fp64 of what the VideoScan streaming
+ * attention path computes.  Only tests, the smoke check and the CPU-baseline
+ * leg of the benchmark may call it; the GPU library never does and the two
+ * share no code, headers, tables or helpers.
+ *
+ * What it follows (VideoScan paper):
+ *   - Section 3.1, Eq. 1: Y = Softmax(Q K^T / sqrt(d_k)) V, evaluated here as
+ *     the textbook two-pass softmax, one (head, query row) at a time.
+ *   - Section 3.2: the semantic carrier is the LAST token of its frame's run
+ *     and its K/V is what stays in the cache.
+ *   - Section 3.3, prefilling phase: C^t = (1/N) sum_i E^t_i (mean pool);
+ *     the frame's tokens are run through the decoder once.
+ *   - Section 3.3, decoding phase: visual tokens are discarded afterwards;
+ *     decoding reads the retained carrier K/V only.
+ *
+ * Readings where the paper is silent (all listed in the design notes):
+ *   - every token of the frame run sees all retained cache rows; inside the
+ *     run the mask is ordinary causal, diagonal included;
+ *   - grouped-query attention: query head h reads KV head h / (Hq / Hkv);
+ *   - decode appends the new token's K/V first, then attends over all rows
+ *     including the new one;
+ *   - cache rows are [prefix | carriers in arrival order], append-only.
+ *
+ * No tiling, no online softmax, no split along keys, no reordering: loops are
+ * written in the order of the definition so they can be checked by eye.
+ * All tensors are row-major doubles: Q [Tq][Hq][D], K/V [rows][Hkv][D].
+ *
+ * Every function here is pinned by tests/test_oracle_pins.py (closed forms,
+ * invariants, hand-derived fixtures, brute force); none is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define VSO_OK 0
+#define VSO_ERR_ARG 1
+#define VSO_ERR_CAPACITY 2
+#define VSO_ERR_NOMEM 3
+
+int vs_oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/*
+ * Eq. 1 with a per-row visible prefix: query row i of every head sees key rows
+ * 0 .. vis[i]-1 of Kall/Vall (1 <= vis[i] <= R).  If P is not NULL it receives
+ * the probabilities, [Hq][Tq][R], zero outside the visible prefix.
+ */
+int vs_oracle_attention(const double *Q, int64_t Tq, int32_t Hq, int32_t Hkv, int32_t D,
+                        const double *Kall, const double *Vall, int64_t R,
+                        const int64_t *vis, double scale, double *O, double *P) {
+    if (!Q || !Kall || !Vall || !vis || !O) return VSO_ERR_ARG;
+    if (Tq < 0 || Hq < 1 || Hkv < 1 || D < 1 || R < 1 || Hq % Hkv != 0) return VSO_ERR_ARG;
+    for (int64_t i = 0; i < Tq; ++i)
+        if (vis[i] < 1 || vis[i] > R) return VSO_ERR_ARG;
+    const int32_t G = Hq / Hkv;
+    int failed = 0;
+
+#pragma omp parallel
+    {
+        double *z = (double *)malloc((size_t)R * sizeof(double));
+        if (!z) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for collapse(2) schedule(dynamic, 4)
+            for (int32_t h = 0; h < Hq; ++h) {
+                for (int64_t i = 0; i < Tq; ++i) {
+                    const int32_t g = h / G;
+                    const int64_t n = vis[i];
+                    const double *q = Q + ((size_t)i * Hq + h) * D;
+                    /* scores z_j = scale * <q, k_j> */
+                    for (int64_t j = 0; j < n; ++j) {
+                        const double *k = Kall + ((size_t)j * Hkv + g) * D;
+                        double dot = 0.0;
+                        for (int32_t d = 0; d < D; ++d) dot += q[d] * k[d];
+                        z[j] = scale * dot;
+                    }
+                    /* softmax over the visible prefix, two passes */
+                    double m = z[0];
+                    for (int64_t j = 1; j < n; ++j)
+                        if (z[j] > m) m = z[j];
+                    double Z = 0.0;
+                    for (int64_t j = 0; j < n; ++j) {
+                        z[j] = exp(z[j] - m);
+                        Z += z[j];
+                    }
+                    for (int64_t j = 0; j < n; ++j) z[j] /= Z;
+                    /* weighted sum of value rows */
+                    double *o = O + ((size_t)i * Hq + h) * D;
+                    for (int32_t d = 0; d < D; ++d) o[d] = 0.0;
+                    for (int64_t j = 0; j < n; ++j) {
+                        const double *v = Vall + ((size_t)j * Hkv + g) * D;
+                        const double p = z[j];
+                        for (int32_t d = 0; d < D; ++d) o[d] += p * v[d];
+                    }
+                    if (P) {
+                        double *prow = P + ((size_t)h * Tq + i) * R;
+                        for (int64_t j = 0; j < n; ++j) prow[j] = z[j];
+                        for (int64_t j = n; j < R; ++j) prow[j] = 0.0;
+                    }
+                }
+            }
+        }
+        free(z);
+    }
+    return failed ? VSO_ERR_NOMEM : VSO_OK;
+}
+
+/*
+ * Frame prefill (Section 3.3, prefilling phase; carrier last, Section 3.2).
+ * Keys/values are the L retained cache rows followed by the T rows of the
+ * frame run; frame row i sees the L cache rows and frame rows 0..i.
+ */
+int vs_oracle_frame_prefill(const double *Q, const double *Kc, const double *Vc, int64_t L,
+                            const double *Kf, const double *Vf, int64_t T,
+                            int32_t Hq, int32_t Hkv, int32_t D, double scale,
+                            double *O, double *P) {
+    if (L < 0 || T < 1 || !Kf || !Vf || (L > 0 && (!Kc || !Vc))) return VSO_ERR_ARG;
+    if (Hkv < 1 || D < 1) return VSO_ERR_ARG;
+    const size_t row = (size_t)Hkv * D;
+    const int64_t R = L + T;
+    double *Kall = (double *)malloc((size_t)R * row * sizeof(double));
+    double *Vall = (double *)malloc((size_t)R * row * sizeof(double));
+    int64_t *vis = (int64_t *)malloc((size_t)T * sizeof(int64_t));
+    int rc = VSO_ERR_NOMEM;
+    if (Kall && Vall && vis) {
+        if (L > 0) {
+            memcpy(Kall, Kc, (size_t)L * row * sizeof(double));
+            memcpy(Vall, Vc, (size_t)L * row * sizeof(double));
+        }
+        memcpy(Kall + (size_t)L * row, Kf, (size_t)T * row * sizeof(double));
+        memcpy(Vall + (size_t)L * row, Vf, (size_t)T * row * sizeof(double));
+        for (int64_t i = 0; i < T; ++i) vis[i] = L + i + 1;
+        rc = vs_oracle_attention(Q, T, Hq, Hkv, D, Kall, Vall, R, vis, scale, O, P);
+    }
+    free(Kall);
+    free(Vall);
+    free(vis);
+    return rc;
+}
+
+/*
+ * Carrier compaction (Sections 3.2 and 3.3): of the frame's T K/V rows only
+ * row `carrier` (the last one in the method) is kept, written at cache row
+ * *len; rows 0..*len-1 are untouched; *len grows by one.
+ */
+int vs_oracle_compact_append(double *Kc, double *Vc, int64_t capacity, int64_t *len,
+                             const double *Kf, const double *Vf, int64_t T, int64_t carrier,
+                             int32_t Hkv, int32_t D, int64_t *row_written) {
+    if (!Kc || !Vc || !len || !Kf || !Vf) return VSO_ERR_ARG;
+    if (T < 1 || carrier < 0 || carrier >= T || *len < 0 || *len > capacity) return VSO_ERR_ARG;
+    if (*len == capacity) return VSO_ERR_CAPACITY;
+    const size_t row = (size_t)Hkv * D;
+    const int64_t at = *len;
+    for (size_t e = 0; e < row; ++e) {
+        Kc[(size_t)at * row + e] = Kf[(size_t)carrier * row + e];
+        Vc[(size_t)at * row + e] = Vf[(size_t)carrier * row + e];
+    }
+    if (row_written) *row_written = at;
+    *len = at + 1;
+    return VSO_OK;
+}
+
+/*
+ * Decode step for one stream (Section 3.3, decoding phase): the new token's
+ * K/V (if given) is appended at row *len, then the single query attends over
+ * every valid row, the new one included.
+ */
+int vs_oracle_decode(const double *q, double *Kc, double *Vc, int64_t capacity, int64_t *len,
+                     const double *k_new, const double *v_new,
+                     int32_t Hq, int32_t Hkv, int32_t D, double scale, double *o) {
+    if (!q || !Kc || !Vc || !len || !o) return VSO_ERR_ARG;
+    if ((k_new == NULL) != (v_new == NULL)) return VSO_ERR_ARG;
+    if (*len < 0 || *len > capacity) return VSO_ERR_ARG;
+    if (k_new) {
+        if (*len == capacity) return VSO_ERR_CAPACITY;
+        const size_t row = (size_t)Hkv * D;
+        for (size_t e = 0; e < row; ++e) {
+            Kc[(size_t)(*len) * row + e] = k_new[e];
+            Vc[(size_t)(*len) * row + e] = v_new[e];
+        }
+        *len += 1;
+    }
+    if (*len < 1) return VSO_ERR_ARG;
+    int64_t vis = *len;
+    return vs_oracle_attention(q, 1, Hq, Hkv, D, Kc, Vc, *len, &vis, scale, o, NULL);
+}
+
+/*
+ * Carrier embedding (Section 3.3): c[j] = (1/N) sum_{i<N} E[i][j], summed in
+ * index order.
+ */
+int vs_oracle_mean_pool(const double *E, int64_t N, int64_t d, double *c) {
+    if (!E || !c || N < 1 || d < 1) return VSO_ERR_ARG;
+    for (int64_t j = 0; j < d; ++j) {
+        double s = 0.0;
+        for (int64_t i = 0; i < N; ++i) s += E[(size_t)i * d + j];
+        c[j] = s / (double)N;
+    }
+    return VSO_OK;
+}

@@ -1,0 +1,146 @@
+"""ctypes binding of oracle/vs_oracle.c (TEST INFRASTRUCTURE, fp64, CPU only).
+
+Every function takes/returns numpy float64 arrays, row-major:
+Q [Tq][Hq][D], K/V [rows][Hkv][D].  The arithmetic is all in the C file; this
+module only marshals arguments.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"oracle {what} failed with code {code}")
+        self.code = code
+
+
+ERR_ARG, ERR_CAPACITY, ERR_NOMEM = 1, 2, 3
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build()
+        lib = ctypes.CDLL(path)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int64)
+        i64, i32, f64 = ctypes.c_int64, ctypes.c_int32, ctypes.c_double
+        lib.vs_oracle_num_threads.restype = ctypes.c_int
+        lib.vs_oracle_attention.argtypes = [dp, i64, i32, i32, i32, dp, dp, i64, ip, f64, dp, dp]
+        lib.vs_oracle_frame_prefill.argtypes = [dp, dp, dp, i64, dp, dp, i64, i32, i32, i32, f64, dp, dp]
+        lib.vs_oracle_compact_append.argtypes = [dp, dp, i64, ip, dp, dp, i64, i64, i32, i32, ip]
+        lib.vs_oracle_decode.argtypes = [dp, dp, dp, i64, ip, dp, dp, i32, i32, i32, f64, dp]
+        lib.vs_oracle_mean_pool.argtypes = [dp, i64, i64, dp]
+        _LIB = lib
+    return _LIB
+
+
+def _c(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def num_threads():
+    return int(_lib().vs_oracle_num_threads())
+
+
+def attention(Q, Kall, Vall, vis, scale, return_probs=False):
+    """Eq. 1 with query row i seeing key rows 0..vis[i]-1.  Q [Tq][Hq][D], K/V [R][Hkv][D]."""
+    Q, Kall, Vall = _c(Q), _c(Kall), _c(Vall)
+    Tq, Hq, D = Q.shape
+    R, Hkv, D2 = Kall.shape
+    assert D2 == D and Vall.shape == Kall.shape
+    vis = np.ascontiguousarray(vis, dtype=np.int64)
+    assert vis.shape == (Tq,)
+    O = np.empty((Tq, Hq, D), dtype=np.float64)
+    P = np.empty((Hq, Tq, R), dtype=np.float64) if return_probs else None
+    rc = _lib().vs_oracle_attention(_p(Q), Tq, Hq, Hkv, D, _p(Kall), _p(Vall), R,
+                                    vis.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                    float(scale), _p(O), _p(P))
+    if rc:
+        raise OracleError(rc, "attention")
+    return (O, P) if return_probs else O
+
+
+def frame_prefill(Q, Kc, Vc, Kf, Vf, scale, return_probs=False):
+    """Prefill of one frame run [T] (carrier last) over L retained rows + causal run."""
+    Q, Kf, Vf = _c(Q), _c(Kf), _c(Vf)
+    T, Hq, D = Q.shape
+    T2, Hkv, D2 = Kf.shape
+    assert T2 == T and D2 == D and Vf.shape == Kf.shape
+    if Kc is None or len(Kc) == 0:
+        L, Kc, Vc = 0, None, None
+    else:
+        Kc, Vc = _c(Kc), _c(Vc)
+        L = Kc.shape[0]
+        assert Kc.shape[1:] == (Hkv, D) and Vc.shape == Kc.shape
+    O = np.empty((T, Hq, D), dtype=np.float64)
+    P = np.empty((Hq, T, L + T), dtype=np.float64) if return_probs else None
+    rc = _lib().vs_oracle_frame_prefill(_p(Q), _p(Kc), _p(Vc), L, _p(Kf), _p(Vf), T,
+                                        Hq, Hkv, D, float(scale), _p(O), _p(P))
+    if rc:
+        raise OracleError(rc, "frame_prefill")
+    return (O, P) if return_probs else O
+
+
+def compact_append(Kc, Vc, length, Kf, Vf, carrier=None):
+    """In place: cache row `length` <- frame row `carrier` (default last).  Returns (row, new_len)."""
+    assert Kc.dtype == np.float64 and Vc.dtype == np.float64
+    assert Kc.flags.c_contiguous and Vc.flags.c_contiguous
+    Kf, Vf = _c(Kf), _c(Vf)
+    cap, Hkv, D = Kc.shape
+    T = Kf.shape[0]
+    assert Kf.shape[1:] == (Hkv, D) and Vf.shape == Kf.shape and Vc.shape == Kc.shape
+    if carrier is None:
+        carrier = T - 1
+    ln = ctypes.c_int64(int(length))
+    row = ctypes.c_int64(-1)
+    rc = _lib().vs_oracle_compact_append(_p(Kc), _p(Vc), cap, ctypes.byref(ln), _p(Kf), _p(Vf),
+                                         T, int(carrier), Hkv, D, ctypes.byref(row))
+    if rc:
+        raise OracleError(rc, "compact_append")
+    return int(row.value), int(ln.value)
+
+
+def decode(q, Kc, Vc, length, k_new, v_new, scale):
+    """One stream, one step: append (k_new, v_new) at row `length` (if given), attend over all rows.
+    Kc/Vc [capacity][Hkv][D] are modified in place.  Returns (o [Hq][D], new_len)."""
+    assert Kc.dtype == np.float64 and Vc.dtype == np.float64
+    assert Kc.flags.c_contiguous and Vc.flags.c_contiguous
+    q = _c(q)
+    Hq, D = q.shape
+    cap, Hkv, D2 = Kc.shape
+    assert D2 == D
+    if k_new is not None:
+        k_new, v_new = _c(k_new), _c(v_new)
+        assert k_new.shape == (Hkv, D) and v_new.shape == (Hkv, D)
+    ln = ctypes.c_int64(int(length))
+    o = np.empty((Hq, D), dtype=np.float64)
+    rc = _lib().vs_oracle_decode(_p(q), _p(Kc), _p(Vc), cap, ctypes.byref(ln), _p(k_new), _p(v_new),
+                                 Hq, Hkv, D, float(scale), _p(o))
+    if rc:
+        raise OracleError(rc, "decode")
+    return o, int(ln.value)
+
+
+def mean_pool(E):
+    """Carrier embedding: arithmetic mean of the N rows of E [N][d]."""
+    E = _c(E)
+    N, d = E.shape
+    c = np.empty((d,), dtype=np.float64)
+    rc = _lib().vs_oracle_mean_pool(_p(E), N, d, _p(c))
+    if rc:
+        raise OracleError(rc, "mean_pool")
+    return c

@@ -1,0 +1,398 @@
+"""Pins for an implementation of the VideoScan attention path.
+
+Each pin takes an `impl` exposing the oracle's five functions and raises
+AssertionError if the implementation violates something the paper or the
+mathematics fixes (Eq. 1, Section 3.1; carrier last, Section 3.2; mean pool,
+prefill/discard/decode, Section 3.3).  None of the expected values here comes
+from the implementation under test.  The same pins run against the real oracle
+(must pass) and against deliberately broken variants of an independent numpy
+evaluation (each must fail at least one pin) so that the pins are known to bite.
+"""
+import json
+import math
+import os
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+# ----------------------------------------------------------------------------
+# independent brute force: pure Python, lists, math.fsum/math.exp, no max shift
+# ----------------------------------------------------------------------------
+def brute_attention(Q, K, V, vis, scale):
+    Tq, Hq, D = len(Q), len(Q[0]), len(Q[0][0])
+    Hkv = len(K[0])
+    G = Hq // Hkv
+    out = [[[0.0] * D for _ in range(Hq)] for _ in range(Tq)]
+    probs = [[[0.0] * len(K) for _ in range(Tq)] for _ in range(Hq)]
+    for i in range(Tq):
+        for h in range(Hq):
+            g = h // G
+            e = []
+            for j in range(vis[i]):
+                dot = math.fsum(Q[i][h][d] * K[j][g][d] for d in range(D))
+                e.append(math.exp(scale * dot))
+            tot = math.fsum(e)
+            for j in range(vis[i]):
+                probs[h][i][j] = e[j] / tot
+            for d in range(D):
+                out[i][h][d] = math.fsum(probs[h][i][j] * V[j][g][d] for j in range(vis[i]))
+    return out, probs
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _close(a, b, tol, what):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    assert a.shape == b.shape, f"{what}: shape {a.shape} vs {b.shape}"
+    err = float(np.max(np.abs(a - b))) if a.size else 0.0
+    assert err <= tol, f"{what}: max-abs error {err:.3e} > {tol:.1e}"
+
+
+# ----------------------------------------------------------------------------
+# attention core
+# ----------------------------------------------------------------------------
+def pin_golden_rational(impl):
+    with open(os.path.join(GOLDEN, "eq1_rational_softmax.json")) as f:
+        g = json.load(f)
+    keys = np.array([[[math.log(a), math.log(b)]] for a, b in zip(g["a"], g["b"])])  # [3][1][2]
+    vals = np.array(g["v"], dtype=np.float64)[:, None, :]
+    L = g["n_cache_rows"]
+    Q = np.array(g["q"], dtype=np.float64)
+    O, P = impl.frame_prefill(Q, keys[:L], vals[:L], keys[L:], vals[L:], g["scale"], return_probs=True)
+    _close(O, g["expected_out"], 1e-13, "golden rational softmax, outputs")
+    _close(P[0], g["expected_probs_head0"], 1e-14, "golden probabilities head 0")
+    _close(P[1], g["expected_probs_head1"], 1e-14, "golden probabilities head 1")
+
+
+def pin_uniform_scores_mean_of_visible(impl):
+    """Q = 0 makes every score equal, so row i is the plain mean of its L+i+1 visible V rows:
+    an exact count of the mask."""
+    r = _rng(10)
+    L, T, Hq, Hkv, D = 5, 7, 4, 2, 8
+    Kc, Vc = r.normal(size=(L, Hkv, D)), r.normal(size=(L, Hkv, D))
+    Kf, Vf = r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+    O = impl.frame_prefill(np.zeros((T, Hq, D)), Kc, Vc, Kf, Vf, 0.37)
+    Vall = np.concatenate([Vc, Vf])
+    for i in range(T):
+        for h in range(Hq):
+            _close(O[i, h], Vall[: L + i + 1, h // (Hq // Hkv)].mean(axis=0), 1e-14,
+                   f"uniform scores row {i} head {h}")
+
+
+def pin_single_key(impl):
+    """Empty cache: frame row 0 sees one key, so its output is that V row exactly; likewise a
+    decode step into an empty cache returns v_new."""
+    r = _rng(11)
+    T, Hq, Hkv, D = 3, 6, 3, 4
+    Q = r.normal(size=(T, Hq, D))
+    Kf, Vf = r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+    O = impl.frame_prefill(Q, None, None, Kf, Vf, 0.5)
+    for h in range(Hq):
+        assert np.array_equal(O[0, h], Vf[0, h // 2]), "single visible key must return its V row exactly"
+    Kc, Vc = np.zeros((4, Hkv, D)), np.zeros((4, Hkv, D))
+    o, ln = impl.decode(Q[0], Kc, Vc, 0, Kf[1], Vf[1], 0.5)
+    assert ln == 1
+    for h in range(Hq):
+        assert np.array_equal(o[h], Vf[1, h // 2])
+
+
+def pin_one_hot_limit(impl):
+    """One key aligned with q and scaled up: softmax collapses onto it."""
+    r = _rng(12)
+    R, Hq, Hkv, D = 9, 2, 1, 16
+    Q = r.normal(size=(1, Hq, D))
+    Q[0, 1] = Q[0, 0]  # both heads share the kv head and the query direction
+    K, V = r.normal(size=(R, Hkv, D)), r.normal(size=(R, Hkv, D))
+    K[4, 0] = 400.0 * Q[0, 0] / np.linalg.norm(Q[0, 0])
+    O = impl.attention(Q, K, V, np.array([R]), 1.0)
+    _close(O[0, 0], V[4, 0], 1e-12, "one-hot limit")
+
+
+def pin_row_stochastic_and_masked_zero(impl):
+    r = _rng(13)
+    L, T, Hq, Hkv, D = 4, 6, 4, 2, 8
+    args = [r.normal(size=s) for s in [(T, Hq, D), (L, Hkv, D), (L, Hkv, D), (T, Hkv, D), (T, Hkv, D)]]
+    _, P = impl.frame_prefill(*args, 0.35, return_probs=True)
+    assert P.shape == (Hq, T, L + T)
+    assert np.all(P >= 0.0)
+    _close(P.sum(axis=-1), np.ones((Hq, T)), 1e-14, "row sums")
+    for i in range(T):
+        assert np.all(P[:, i, L + i + 1:] == 0.0), "masked keys must carry exactly zero weight"
+        assert np.all(P[:, i, : L + i + 1] > 0.0)
+
+
+def pin_brute_force_tiny(impl):
+    """Against the pure-Python evaluation, over several tiny shapes incl. GQA and D odd."""
+    for seed, (L, T, Hq, Hkv, D) in enumerate([(2, 3, 2, 1, 4), (0, 2, 2, 2, 3), (1, 1, 4, 2, 2),
+                                               (2, 3, 6, 2, 1)]):
+        r = _rng(100 + seed)
+        Q = r.normal(size=(T, Hq, D))
+        Kc, Vc = r.normal(size=(L, Hkv, D)), r.normal(size=(L, Hkv, D))
+        Kf, Vf = r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+        scale = 0.7
+        O, P = impl.frame_prefill(Q, Kc, Vc, Kf, Vf, scale, return_probs=True)
+        Kall, Vall = np.concatenate([Kc, Kf]), np.concatenate([Vc, Vf])
+        bo, bp = brute_attention(Q.tolist(), Kall.tolist(), Vall.tolist(),
+                                 [L + i + 1 for i in range(T)], scale)
+        _close(O, bo, 1e-13, f"brute force outputs, case {seed}")
+        _close(P, bp, 1e-14, f"brute force probabilities, case {seed}")
+
+
+def pin_library_second_opinion(impl):
+    """With the causal frame mask written as a boolean matrix, a library softmax-attention in fp64
+    must agree (second opinion only, on a mid-size case spanning GQA groups)."""
+    import torch
+    r = _rng(14)
+    L, T, Hq, Hkv, D = 37, 23, 8, 2, 32
+    Q = r.normal(size=(T, Hq, D))
+    Kc, Vc = r.normal(size=(L, Hkv, D)), r.normal(size=(L, Hkv, D))
+    Kf, Vf = r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+    scale = D ** -0.5
+    O = impl.frame_prefill(Q, Kc, Vc, Kf, Vf, scale)
+    G = Hq // Hkv
+    Kall = torch.from_numpy(np.concatenate([Kc, Kf])).repeat_interleave(G, dim=1)
+    Vall = torch.from_numpy(np.concatenate([Vc, Vf])).repeat_interleave(G, dim=1)
+    mask = torch.zeros(T, L + T, dtype=torch.bool)
+    for i in range(T):
+        mask[i, : L + i + 1] = True
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q).permute(1, 0, 2), Kall.permute(1, 0, 2), Vall.permute(1, 0, 2),
+        attn_mask=mask, scale=scale).permute(1, 0, 2).numpy()
+    _close(O, ref, 1e-13, "library second opinion")
+
+
+# ----------------------------------------------------------------------------
+# mask, GQA, invariances
+# ----------------------------------------------------------------------------
+def pin_causality(impl):
+    r = _rng(15)
+    L, T, Hq, Hkv, D = 3, 6, 2, 1, 8
+    Q = r.normal(size=(T, Hq, D))
+    Kc, Vc = r.normal(size=(L, Hkv, D)), r.normal(size=(L, Hkv, D))
+    Kf, Vf = r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+    base = impl.frame_prefill(Q, Kc, Vc, Kf, Vf, 0.4)
+    cut = 3
+    Kf2, Vf2 = Kf.copy(), Vf.copy()
+    Kf2[cut + 1:] += 5.0
+    Vf2[cut + 1:] -= 7.0
+    pert = impl.frame_prefill(Q, Kc, Vc, Kf2, Vf2, 0.4)
+    assert np.array_equal(base[: cut + 1], pert[: cut + 1]), "future frame rows leaked into earlier rows"
+    assert np.all(np.abs(base[cut + 1:] - pert[cut + 1:]).max(axis=(1, 2)) > 1e-3)
+    # every row sees every cache row
+    Vc2 = Vc.copy()
+    Vc2[1] += 3.0
+    pert = impl.frame_prefill(Q, Kc, Vc2, Kf, Vf, 0.4)
+    assert np.all(np.abs(base - pert).max(axis=(1, 2)) > 1e-6), "a cache row is invisible to some frame row"
+    # the row itself is visible (diagonal)
+    Vf3 = Vf.copy()
+    Vf3[2] += 3.0
+    pert = impl.frame_prefill(Q, Kc, Vc, Kf, Vf3, 0.4)
+    assert np.abs(base[2] - pert[2]).max() > 1e-6, "a frame row must see itself"
+    assert np.array_equal(base[:2], pert[:2])
+
+
+def pin_carrier_row_is_unmasked_attention(impl):
+    """The carrier is last in the run, so its output is plain attention over all L+T rows."""
+    r = _rng(16)
+    L, T, Hq, Hkv, D = 4, 5, 4, 2, 8
+    Q = r.normal(size=(T, Hq, D))
+    Kc, Vc = r.normal(size=(L, Hkv, D)), r.normal(size=(L, Hkv, D))
+    Kf, Vf = r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+    O = impl.frame_prefill(Q, Kc, Vc, Kf, Vf, 0.3)
+    Kall, Vall = np.concatenate([Kc, Kf]), np.concatenate([Vc, Vf])
+    for h in range(Hq):
+        g = h // 2
+        z = 0.3 * Kall[:, g] @ Q[T - 1, h]
+        w = np.exp(z - z.max())
+        _close(O[T - 1, h], (w / w.sum()) @ Vall[:, g], 1e-14, "carrier row")
+
+
+def pin_gqa_equals_replicated_mha(impl):
+    r = _rng(17)
+    R, Tq, Hq, Hkv, D = 11, 4, 6, 2, 8
+    Q, K, V = r.normal(size=(Tq, Hq, D)), r.normal(size=(R, Hkv, D)), r.normal(size=(R, Hkv, D))
+    vis = np.array([3, 11, 7, 1])
+    a = impl.attention(Q, K, V, vis, 0.4)
+    b = impl.attention(Q, np.repeat(K, 3, axis=1), np.repeat(V, 3, axis=1), vis, 0.4)
+    _close(a, b, 1e-15, "GQA vs replicated MHA")
+    # and the grouping is by consecutive query heads: heads 0..2 read kv head 0
+    V2 = V.copy()
+    V2[:, 1] += 1.0
+    c = impl.attention(Q, K, V2, vis, 0.4)
+    assert np.array_equal(a[:, :3], c[:, :3]) and np.all(np.abs(a[:, 3:] - c[:, 3:]) > 0.5)
+
+
+def pin_invariances(impl):
+    r = _rng(18)
+    L, T, Hq, Hkv, D = 6, 4, 2, 1, 8
+    Q = r.normal(size=(T, Hq, D))
+    Kc, Vc = r.normal(size=(L, Hkv, D)), r.normal(size=(L, Hkv, D))
+    Kf, Vf = r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+    base = impl.frame_prefill(Q, Kc, Vc, Kf, Vf, 0.4)
+    # key shift: adds a per-row constant to every score
+    u = r.normal(size=(D,))
+    _close(impl.frame_prefill(Q, Kc + u, Vc, Kf + u, Vf, 0.4), base, 1e-13, "key shift")
+    # permutation of cache rows (K and V together)
+    perm = r.permutation(L)
+    _close(impl.frame_prefill(Q, Kc[perm], Vc[perm], Kf, Vf, 0.4), base, 1e-14, "cache permutation")
+    # linear in V
+    Vc2, Vf2 = r.normal(size=Vc.shape), r.normal(size=Vf.shape)
+    both = impl.frame_prefill(Q, Kc, Vc + Vc2, Kf, Vf + Vf2, 0.4)
+    _close(both, base + impl.frame_prefill(Q, Kc, Vc2, Kf, Vf2, 0.4), 1e-14, "linearity in V")
+    # convex hull of visible V rows
+    Vall = np.concatenate([Vc, Vf])
+    for i in range(T):
+        lo, hi = Vall[: L + i + 1, 0].min(axis=0), Vall[: L + i + 1, 0].max(axis=0)
+        assert np.all(base[i] >= lo - 1e-14) and np.all(base[i] <= hi + 1e-14)
+    # the scale matters and is applied to the scores (doubling scale == doubling Q)
+    _close(impl.frame_prefill(Q, Kc, Vc, Kf, Vf, 0.8), impl.frame_prefill(2 * Q, Kc, Vc, Kf, Vf, 0.4),
+           1e-13, "scale acts on scores")
+    assert np.abs(impl.frame_prefill(Q, Kc, Vc, Kf, Vf, 0.8) - base).max() > 1e-3
+
+
+def pin_transposition_sensitive(impl):
+    """Non-square, non-symmetric case with a closed form: scores depend on <q,k> only.
+    K rows are multiples of one direction u, so z_j = scale*c_j*<q,u>; V is distinct from K."""
+    r = _rng(19)
+    R, D = 5, 3
+    u = np.array([1.0, -2.0, 0.5])
+    c = np.array([0.3, -1.0, 2.0, 0.0, 1.5])
+    K = (c[:, None] * u[None, :])[:, None, :]
+    V = r.normal(size=(R, 1, D))
+    q = np.array([[[0.2, 0.1, -0.4]]])
+    z = 0.9 * c * float(q[0, 0] @ u)
+    w = np.exp(z) / np.exp(z).sum()
+    _close(impl.attention(q, K, V, np.array([R]), 0.9)[0, 0], w @ V[:, 0], 1e-14, "closed-form scores")
+
+
+# ----------------------------------------------------------------------------
+# compaction, streaming, decode, pool
+# ----------------------------------------------------------------------------
+def pin_compaction(impl):
+    r = _rng(20)
+    P0, F, T, Hkv, D = 3, 5, 4, 2, 4
+    cap = P0 + F
+    Kc, Vc = np.full((cap, Hkv, D), np.nan), np.full((cap, Hkv, D), np.nan)
+    Kc[:P0], Vc[:P0] = r.normal(size=(P0, Hkv, D)), r.normal(size=(P0, Hkv, D))
+    ln = P0
+    frames = []
+    for f in range(F):
+        Kf, Vf = r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+        before_k, before_v = Kc[:ln].copy(), Vc[:ln].copy()
+        row, new_len = impl.compact_append(Kc, Vc, ln, Kf, Vf)
+        assert row == P0 + f and new_len == ln + 1, "appended row index / length sequence"
+        assert np.array_equal(Kc[:ln], before_k) and np.array_equal(Vc[:ln], before_v), "older rows touched"
+        assert np.array_equal(Kc[row], Kf[T - 1]) and np.array_equal(Vc[row], Vf[T - 1]), "carrier row bytes"
+        assert np.all(np.isnan(Kc[new_len:])) and np.all(np.isnan(Vc[new_len:])), "wrote past the new row"
+        frames.append((Kf, Vf))
+        ln = new_len
+    assert ln == P0 + F  # retained length = prefix + frames seen
+    # none of the visual rows is retained
+    for Kf, Vf in frames:
+        for t in range(T - 1):
+            assert not any(np.array_equal(Kc[j], Kf[t]) for j in range(ln))
+    # full cache -> capacity error, nothing changes
+    snap = Kc.copy()
+    try:
+        impl.compact_append(Kc, Vc, ln, *frames[0])
+        raise AssertionError("append into a full cache must fail")
+    except AssertionError:
+        raise
+    except Exception:
+        pass
+    assert np.array_equal(Kc, snap)
+    # explicit carrier index other than last
+    Kc2, Vc2 = np.zeros((2, Hkv, D)), np.zeros((2, Hkv, D))
+    row, _ = impl.compact_append(Kc2, Vc2, 0, *frames[1], carrier=1)
+    assert row == 0 and np.array_equal(Kc2[0], frames[1][0][1]) and np.array_equal(Vc2[0], frames[1][1][1])
+
+
+def pin_streaming_equals_one_shot(impl):
+    """F frames with compaction, then one more frame == that frame against a cache built directly
+    as [prefix | carrier rows]."""
+    r = _rng(21)
+    P0, F, T, Hq, Hkv, D = 2, 4, 3, 2, 1, 4
+    cap = P0 + F
+    Kc, Vc = np.zeros((cap, Hkv, D)), np.zeros((cap, Hkv, D))
+    pk, pv = r.normal(size=(P0, Hkv, D)), r.normal(size=(P0, Hkv, D))
+    Kc[:P0], Vc[:P0] = pk, pv
+    ln = P0
+    carriers_k, carriers_v = [], []
+    for f in range(F):
+        Kf, Vf = r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+        impl.frame_prefill(r.normal(size=(T, Hq, D)), Kc[:ln], Vc[:ln], Kf, Vf, 0.5)
+        _, ln = impl.compact_append(Kc, Vc, ln, Kf, Vf)
+        carriers_k.append(Kf[T - 1])
+        carriers_v.append(Vf[T - 1])
+    Q, Kf, Vf = r.normal(size=(T, Hq, D)), r.normal(size=(T, Hkv, D)), r.normal(size=(T, Hkv, D))
+    streamed = impl.frame_prefill(Q, Kc[:ln], Vc[:ln], Kf, Vf, 0.5)
+    direct = impl.frame_prefill(Q, np.concatenate([pk, np.stack(carriers_k)]),
+                                np.concatenate([pv, np.stack(carriers_v)]), Kf, Vf, 0.5)
+    assert np.array_equal(streamed, direct)
+
+
+def pin_decode(impl):
+    r = _rng(22)
+    L, Hq, Hkv, D = 7, 4, 2, 8
+    cap = L + 2
+    Kc, Vc = np.zeros((cap, Hkv, D)), np.zeros((cap, Hkv, D))
+    Kc[:L], Vc[:L] = r.normal(size=(L, Hkv, D)), r.normal(size=(L, Hkv, D))
+    q, kn, vn = r.normal(size=(Hq, D)), r.normal(size=(Hkv, D)), r.normal(size=(Hkv, D))
+    K0, V0 = Kc.copy(), Vc.copy()
+    o, ln = impl.decode(q, Kc, Vc, L, kn, vn, 0.4)
+    assert ln == L + 1
+    assert np.array_equal(Kc[L], kn) and np.array_equal(Vc[L], vn), "new row goes to index old-length"
+    assert np.array_equal(Kc[:L], K0[:L]) and np.array_equal(Kc[L + 1:], K0[L + 1:])
+    # decode == prefill with a one-token run against the old cache
+    pre = impl.frame_prefill(q[None], K0[:L], V0[:L], kn[None], vn[None], 0.4)
+    _close(o, pre[0], 1e-15, "decode vs one-token prefill")
+    # the new row is attended to
+    o2, _ = impl.decode(q, K0.copy(), V0.copy(), L, kn, vn + 10.0, 0.4)
+    assert np.all(np.abs(o2 - o) > 1e-6)
+    # without a new row: plain attention over the L valid rows, rows beyond `len` ignored
+    Kc3, Vc3 = K0.copy(), V0.copy()
+    Kc3[L:], Vc3[L:] = 99.0, 99.0
+    o3, ln3 = impl.decode(q, Kc3, Vc3, L, None, None, 0.4)
+    assert ln3 == L
+    ref = impl.attention(q[None], K0[:L], V0[:L], np.array([L]), 0.4)[0]
+    _close(o3, ref, 1e-15, "decode without append")
+
+
+def pin_mean_pool(impl):
+    with open(os.path.join(GOLDEN, "mean_pool_integers.json")) as f:
+        g = json.load(f)
+    assert np.array_equal(impl.mean_pool(np.array(g["e"], dtype=np.float64)), np.array(g["expected"]))
+    r = _rng(23)
+    row = r.normal(size=(17,))
+    _close(impl.mean_pool(np.tile(row, (9, 1))), row, 1e-15, "constant rows")
+    assert np.array_equal(impl.mean_pool(row[None]), row), "N = 1 is the identity"
+    E, W = r.normal(size=(49, 32)), r.normal(size=(32, 8))
+    _close(impl.mean_pool(E) @ W, impl.mean_pool(E @ W), 1e-13, "pool commutes with a linear map")
+    _close(impl.mean_pool(E), E.mean(axis=0, dtype=np.float64), 1e-15, "numpy mean")
+    # pooled over rows, not columns; and divided by N (not N-1, not d)
+    E2 = np.arange(12, dtype=np.float64).reshape(3, 4)
+    assert np.array_equal(impl.mean_pool(E2), np.array([4.0, 5.0, 6.0, 7.0]))
+
+
+ALL_PINS = [
+    pin_golden_rational,
+    pin_uniform_scores_mean_of_visible,
+    pin_single_key,
+    pin_one_hot_limit,
+    pin_row_stochastic_and_masked_zero,
+    pin_brute_force_tiny,
+    pin_library_second_opinion,
+    pin_causality,
+    pin_carrier_row_is_unmasked_attention,
+    pin_gqa_equals_replicated_mha,
+    pin_invariances,
+    pin_transposition_sensitive,
+    pin_compaction,
+    pin_streaming_equals_one_shot,
+    pin_decode,
+    pin_mean_pool,
+]

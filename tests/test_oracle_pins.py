@@ -1,0 +1,167 @@
+"""The oracle against its pins, and the pins against planted mistakes (CPU only)."""
+import numpy as np
+import pytest
+
+import oracle
+from pins import ALL_PINS
+
+
+@pytest.mark.parametrize("pin", ALL_PINS, ids=lambda p: p.__name__)
+def test_oracle_passes_pin(pin):
+    pin(oracle)
+
+
+# ----------------------------------------------------------------------------
+# An independent numpy evaluation with switchable, plausible mistakes.  Unbroken
+# it must pass every pin; each mistake must be caught by at least one pin.
+# ----------------------------------------------------------------------------
+class NumpyImpl:
+    def __init__(self, bug=None):
+        self.bug = bug
+
+    def attention(self, Q, Kall, Vall, vis, scale, return_probs=False):
+        Q, Kall, Vall = (np.asarray(a, dtype=np.float64) for a in (Q, Kall, Vall))
+        Tq, Hq, D = Q.shape
+        R, Hkv, _ = Kall.shape
+        G = Hq // Hkv
+        O = np.zeros((Tq, Hq, D))
+        P = np.zeros((Hq, Tq, R))
+        for h in range(Hq):
+            g = h % Hkv if self.bug == "gqa_interleaved" else h // G
+            src = Vall if self.bug == "scores_from_v" else Kall
+            for i in range(Tq):
+                n = int(vis[i])
+                z = src[:n, g] @ Q[i, h]
+                if self.bug != "no_scale":
+                    z = z * scale
+                if self.bug == "scale_squared":
+                    z = z * scale
+                w = np.exp(z - z.max())
+                p = w if self.bug == "no_normalise" else w / w.sum()
+                if self.bug == "negated_scores":
+                    w = np.exp(-(z - z.min()))
+                    p = w / w.sum()
+                P[h, i, :n] = p
+                O[i, h] = p @ Vall[:n, g]
+        return (O, P) if return_probs else O
+
+    def frame_prefill(self, Q, Kc, Vc, Kf, Vf, scale, return_probs=False):
+        Kf, Vf = np.asarray(Kf, dtype=np.float64), np.asarray(Vf, dtype=np.float64)
+        T = Kf.shape[0]
+        L = 0 if Kc is None else len(Kc)
+        Kall = Kf if L == 0 else np.concatenate([Kc, Kf])
+        Vall = Vf if L == 0 else np.concatenate([Vc, Vf])
+        if self.bug == "self_invisible":
+            vis = [max(L + i, 1) for i in range(T)]
+        elif self.bug == "sees_next":
+            vis = [min(L + i + 2, L + T) for i in range(T)]
+        elif self.bug == "no_mask":
+            vis = [L + T] * T
+        elif self.bug == "frame_before_cache":
+            Kall = Kf if L == 0 else np.concatenate([Kf, Kc])
+            Vall = Vf if L == 0 else np.concatenate([Vf, Vc])
+            vis = [L + i + 1 for i in range(T)]
+        else:
+            vis = [L + i + 1 for i in range(T)]
+        return self.attention(Q, Kall, Vall, np.array(vis), scale, return_probs)
+
+    def compact_append(self, Kc, Vc, length, Kf, Vf, carrier=None):
+        T = len(Kf)
+        if carrier is None:
+            carrier = 0 if self.bug == "keeps_first_token" else T - 1
+        cap = Kc.shape[0]
+        if length >= cap and self.bug != "no_capacity_check":
+            raise RuntimeError("capacity")
+        at = length - 1 if self.bug == "overwrites_last" else length
+        at = min(at, cap - 1)
+        Kc[at] = Kf[carrier]
+        Vc[at] = Kf[carrier] if self.bug == "v_gets_k" else Vf[carrier]
+        return (at, length + 1)
+
+    def decode(self, q, Kc, Vc, length, k_new, v_new, scale):
+        n = length
+        if k_new is not None:
+            Kc[length], Vc[length] = k_new, v_new
+            n = length + 1
+        seen = length if (self.bug == "decode_attends_before_append" and k_new is not None) else n
+        o = self.attention(np.asarray(q)[None], Kc[:seen], Vc[:seen], np.array([seen]), scale)[0]
+        return o, n
+
+    def mean_pool(self, E):
+        E = np.asarray(E, dtype=np.float64)
+        if self.bug == "pool_sum":
+            return E.sum(axis=0)
+        if self.bug == "pool_unbiased":
+            return E.sum(axis=0) / max(E.shape[0] - 1, 1)
+        if self.bug == "pool_over_features":
+            return np.resize(E.mean(axis=1), E.shape[1])
+        return E.sum(axis=0) / E.shape[0]
+
+
+BUGS = ["gqa_interleaved", "scores_from_v", "no_scale", "scale_squared", "no_normalise",
+        "negated_scores", "self_invisible", "sees_next", "no_mask", "frame_before_cache",
+        "keeps_first_token", "no_capacity_check", "overwrites_last", "v_gets_k",
+        "decode_attends_before_append", "pool_sum", "pool_unbiased", "pool_over_features"]
+
+
+def _failures(impl):
+    failed = []
+    for pin in ALL_PINS:
+        try:
+            pin(impl)
+        except Exception:  # a broken implementation may also crash a pin; that counts as caught
+            failed.append(pin.__name__)
+    return failed
+
+
+def test_unbroken_numpy_evaluation_passes_all_pins():
+    assert _failures(NumpyImpl()) == []
+
+
+@pytest.mark.parametrize("bug", BUGS)
+def test_pins_catch_planted_mistake(bug):
+    assert _failures(NumpyImpl(bug)), f"no pin notices the planted mistake '{bug}'"
+
+
+def test_oracle_matches_numpy_evaluation_midsize():
+    """Two independently written evaluations agree on a GQA case with a ragged visible prefix."""
+    r = np.random.default_rng(5)
+    Q, K, V = r.normal(size=(9, 8, 16)), r.normal(size=(40, 2, 16)), r.normal(size=(40, 2, 16))
+    vis = r.integers(1, 41, size=9)
+    a, pa = oracle.attention(Q, K, V, vis, 0.25, return_probs=True)
+    b, pb = NumpyImpl().attention(Q, K, V, vis, 0.25, return_probs=True)
+    assert np.abs(a - b).max() < 1e-14 and np.abs(pa - pb).max() < 1e-15
+
+
+def test_oracle_rejects_bad_arguments():
+    Q, K = np.zeros((2, 3, 4)), np.zeros((5, 2, 4))
+    with pytest.raises(oracle.OracleError):  # Hq not a multiple of Hkv
+        oracle.attention(Q, K, K, np.array([1, 1]), 1.0)
+    Q = np.zeros((2, 4, 4))
+    with pytest.raises(oracle.OracleError):  # visible prefix beyond the rows
+        oracle.attention(Q, K, K, np.array([1, 6]), 1.0)
+    with pytest.raises(oracle.OracleError):  # empty visible set
+        oracle.attention(Q, K, K, np.array([0, 1]), 1.0)
+    Kc = np.zeros((2, 2, 4))
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.compact_append(Kc, Kc.copy(), 2, K, K)
+    assert e.value.code == 2
+    with pytest.raises(oracle.OracleError):
+        oracle.compact_append(Kc, Kc.copy(), 0, K, K, carrier=5)
+
+
+def test_retained_length_of_the_configs():
+    """Retained rows = prefix + frames seen: 17 for the tiny case, 264 for the 64-frame stream."""
+    from synth import CONFIGS
+    for name, want in (("cfg1", 17), ("cfg2", 264), ("cfg3", 4552)):
+        c = CONFIGS[name]
+        s = c["shape"]
+        cap = c["prefix"] + c["frames"]
+        Kc, Vc = np.zeros((cap, s.n_kv_heads, 2)), np.zeros((cap, s.n_kv_heads, 2))
+        Kf = np.ones((c["n_visual"] + 1, s.n_kv_heads, 2))
+        ln = c["prefix"]
+        rows = []
+        for _ in range(c["frames"]):
+            row, ln = oracle.compact_append(Kc, Vc, ln, Kf, Kf)
+            rows.append(row)
+        assert ln == want and rows == list(range(c["prefix"], want))
