@@ -1,0 +1,179 @@
+/*
+ * videoscan.h -- C ABI of the MI355X (gfx950) streaming attention path of VideoScan.
+ *
+ * The library computes, for one decoder layer at a time, the three steps the
+ * method performs on every incoming video frame and on every decoded token
+ * (VideoScan, Sections 3.2 and 3.3):
+ *   1. frame prefill attention  -- Eq. 1 (Section 3.1) for the frame's N visual
+ *      tokens followed by its semantic carrier token, over the rows retained so
+ *      far plus the frame's own tokens (causal inside the frame);
+ *   2. carrier compaction       -- keep the carrier token's K/V row only, append it
+ *      to the per-layer cache, drop the visual tokens' K/V;
+ *   3. decode attention         -- Eq. 1 for one text query per stream over the
+ *      retained rows.
+ * plus the mean pool that forms the carrier's input embedding (Section 3.3).
+ *
+ * General rules (all entry points):
+ *   - Pointers named q, k_f, v_f, out, k, v, k_slab, v_slab, k_new, v_new, e,
+ *     c_out and workspace are DEVICE pointers (HIP global memory of the current
+ *     device), 16-byte aligned, owned by the caller.  vs_shape, vs_cache, `lens`,
+ *     `row_written` are HOST memory.
+ *   - The library never allocates, frees or keeps device memory.  Temporary
+ *     storage comes from the caller's `workspace` (size from vs_workspace_bytes).
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the null stream) and return without waiting.  Buffers must stay valid until
+ *     that work has finished.  Two calls that share a workspace must be ordered
+ *     on one stream.
+ *   - Host-side lengths (vs_cache.len, lens[]) are the truth about how many rows
+ *     are valid; they are updated at enqueue time, only when VS_OK is returned.
+ *   - Errors are return codes.  Argument errors are found before anything is
+ *     launched and leave all lengths untouched.
+ *   - Tensors are dense row-major.  Storage type is vs_shape.dtype: fp32 or
+ *     bf16 (bit pattern = upper 16 bits of an fp32).  Scores, softmax and
+ *     accumulation are fp32 in both cases; outputs are rounded to nearest even.
+ *   - Grouped-query attention: query head h reads KV head h / (n_q_heads /
+ *     n_kv_heads).
+ *   - Supported: head_dim 64 or 128 for fp32; head_dim 128 for bf16;
+ *     n_q_heads a multiple of n_kv_heads with a ratio of at most 8.
+ */
+#ifndef VIDEOSCAN_H
+#define VIDEOSCAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VS_OK = 0,
+    VS_ERR_NULL = 1,        /* a required pointer is NULL */
+    VS_ERR_SHAPE = 2,       /* sizes out of range or inconsistent */
+    VS_ERR_UNSUPPORTED = 3, /* head_dim / dtype / head ratio not implemented */
+    VS_ERR_CAPACITY = 4,    /* append into a full cache, or len > capacity */
+    VS_ERR_WORKSPACE = 5,   /* workspace missing or too small */
+    VS_ERR_ALIGN = 6,       /* a device pointer is not 16-byte aligned */
+    VS_ERR_HIP = 7          /* the HIP runtime reported a launch failure */
+} vs_status;
+
+typedef enum { VS_F32 = 0, VS_BF16 = 1 } vs_dtype;
+
+typedef struct {
+    int32_t n_q_heads;   /* Hq */
+    int32_t n_kv_heads;  /* Hkv, divides Hq */
+    int32_t head_dim;    /* D */
+    int32_t dtype;       /* vs_dtype of q/k/v/out */
+    float softmax_scale; /* multiplies q.k; 1/sqrt(head_dim) in Eq. 1 */
+} vs_shape;
+
+/* Retained K/V rows of one layer of one stream: [text prefix | one carrier row per
+ * frame seen], append-only (Section 3.3: the retained carriers and their KV pairs). */
+typedef struct {
+    void *k;          /* device, [capacity][n_kv_heads][head_dim] */
+    void *v;          /* device, same layout */
+    int32_t capacity; /* rows allocated */
+    int32_t len;      /* rows valid, host-side truth */
+} vs_cache;
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char *vs_status_string(vs_status s);
+
+/*
+ * Bytes of device workspace that any call needs for up to `max_q_tokens` tokens
+ * per frame run, `max_cache_rows` retained rows (per stream) and `n_streams`
+ * decode streams.  Returns 0 if the shape is unsupported.
+ */
+size_t vs_workspace_bytes(const vs_shape *shape, int32_t max_q_tokens, int32_t max_cache_rows,
+                          int32_t n_streams);
+
+/*
+ * Frame prefill attention (Section 3.3, prefilling phase; Eq. 1; carrier last in
+ * the run, Section 3.2).
+ *   q   [n_tokens][Hq][D], k_f / v_f [n_tokens][Hkv][D]: the frame run, visual
+ *   tokens first, carrier token last.  out [n_tokens][Hq][D].
+ * Row i attends to the cache's `len` rows and to frame rows 0..i.  The cache is
+ * only read.  len may be 0.  n_tokens >= 1, n_tokens <= 4096.
+ */
+vs_status vs_frame_prefill_attn(const vs_shape *shape, const vs_cache *cache, const void *q,
+                                const void *k_f, const void *v_f, int32_t n_tokens, void *out,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Carrier compaction and append (Sections 3.2, 3.3: only the carrier's K/V is
+ * kept, the visual tokens' K/V are discarded).  Copies row `carrier_index` of k_f
+ * and v_f ([n_tokens][Hkv][D]; the method uses n_tokens-1) bit for bit into cache
+ * row `len`, stores that row index in *row_written (may be NULL) and increments
+ * cache->len.  VS_ERR_CAPACITY if len == capacity.
+ */
+vs_status vs_carrier_compact_append(const vs_shape *shape, vs_cache *cache, const void *k_f,
+                                    const void *v_f, int32_t n_tokens, int32_t carrier_index,
+                                    int32_t *row_written, void *hip_stream);
+
+/*
+ * Prefill and compaction of one frame in a single launch: same result as
+ * vs_frame_prefill_attn followed by vs_carrier_compact_append with
+ * carrier_index = n_tokens-1.  Nothing is launched and len is unchanged if the
+ * cache is full.
+ */
+vs_status vs_frame_prefill_compact(const vs_shape *shape, vs_cache *cache, const void *q,
+                                   const void *k_f, const void *v_f, int32_t n_tokens, void *out,
+                                   int32_t *row_written, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
+
+/*
+ * Compaction for many caches in one launch (all layers of a frame, or many
+ * streams).  Caches live in slabs k_slab / v_slab [n_caches][capacity][Hkv][D];
+ * frame runs in k_f / v_f [n_caches][n_tokens][Hkv][D].  For every i, row
+ * carrier_index of run i goes to row lens[i] of cache i and lens[i] += 1.
+ * rows_written (host, [n_caches]) may be NULL.  If any cache is full nothing is
+ * done.  Needs 4*n_caches bytes of workspace when n_caches > 64.
+ */
+vs_status vs_carrier_compact_append_batched(const vs_shape *shape, int32_t n_caches, void *k_slab,
+                                            void *v_slab, int32_t capacity, int32_t *lens,
+                                            const void *k_f, const void *v_f, int32_t n_tokens,
+                                            int32_t carrier_index, int32_t *rows_written,
+                                            void *workspace, size_t workspace_bytes,
+                                            void *hip_stream);
+
+/*
+ * Decode attention (Section 3.3, decoding phase; Eq. 1), one query token for each
+ * of n_streams independent streams of one layer.
+ *   k_slab / v_slab [n_streams][capacity][Hkv][D], stream s valid up to lens[s].
+ *   q [n_streams][Hq][D]; k_new / v_new [n_streams][Hkv][D] or both NULL.
+ * If k_new is given, row lens[s] of stream s receives it first and lens[s] += 1;
+ * the query then attends over all valid rows, the new one included.  Every stream
+ * must end with at least one valid row.  1 <= n_streams <= 1024.
+ */
+vs_status vs_decode_attn(const vs_shape *shape, int32_t n_streams, void *k_slab, void *v_slab,
+                         int32_t capacity, int32_t *lens, const void *q, const void *k_new,
+                         const void *v_new, void *out, void *workspace, size_t workspace_bytes,
+                         void *hip_stream);
+
+/*
+ * Carrier embedding (Section 3.3: C^t = (1/N) sum_i E^t_i).  e [n][d] -> c_out [d],
+ * storage type `dtype`, fp32 accumulation in row order, one rounding at the end.
+ * d must be a multiple of 8 (bf16) or 4 (fp32).
+ */
+vs_status vs_carrier_mean_pool(const void *e, int32_t n, int32_t d, int32_t dtype, void *c_out,
+                               void *hip_stream);
+
+/*
+ * Launch-plan overrides for tuning and for tests that must show a result does not
+ * depend on how the keys were split.  Process-wide, not thread-safe; value 0 restores
+ * the library's own choice.  Unknown knobs or out-of-range values: VS_ERR_SHAPE.
+ *   VS_TUNE_PREFILL_SPLITS    workgroups sharing one row tile's keys, 1..32
+ *   VS_TUNE_PREFILL_ROW_BLOCKS 32-row blocks per wavefront in prefill, 1 or 2
+ *   VS_TUNE_DECODE_CHUNK_ROWS rows per decode workgroup, a multiple of 128
+ */
+typedef enum {
+    VS_TUNE_PREFILL_SPLITS = 0,
+    VS_TUNE_PREFILL_ROW_BLOCKS = 1,
+    VS_TUNE_DECODE_CHUNK_ROWS = 2
+} vs_tune_knob;
+vs_status vs_set_tuning(int32_t knob, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VIDEOSCAN_H */

@@ -1,0 +1,24 @@
+"""MI355X (gfx950) streaming attention path of VideoScan: thin Python binding over
+libvideoscan.so.  All arithmetic runs in the HIP kernels behind the C ABI declared in
+include/videoscan.h; this package only marshals torch device tensors into pointers."""
+from .binding import (  # noqa: F401
+    VSError,
+    VS_BF16,
+    VS_F32,
+    Cache,
+    Shape,
+    carrier_compact_append,
+    carrier_compact_append_batched,
+    carrier_mean_pool,
+    decode_attn,
+    frame_prefill_attn,
+    frame_prefill_compact,
+    lib,
+    set_tuning,
+    TUNE_PREFILL_SPLITS,
+    TUNE_PREFILL_ROW_BLOCKS,
+    TUNE_DECODE_CHUNK_ROWS,
+    lib_path,
+    status_string,
+    workspace_bytes,
+)

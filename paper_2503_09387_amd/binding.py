@@ -1,0 +1,183 @@
+"""ctypes binding of libvideoscan.so.  Function names mirror the C ABI without the vs_
+prefix.  Tensors are torch CUDA(ROCm) tensors; the current torch stream is used unless
+one is given.  There is no fallback: if the library is missing, importing `lib()` raises."""
+import ctypes
+import os
+
+VS_F32, VS_BF16 = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = [
+    "vs_status_string", "vs_workspace_bytes", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
+    "vs_carrier_compact_append", "vs_carrier_compact_append_batched", "vs_decode_attn",
+    "vs_carrier_mean_pool", "vs_set_tuning",
+]
+
+
+class VSError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: {status_string(code)} (vs_status {code})")
+        self.code = code
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float)]
+
+    @classmethod
+    def make(cls, n_q_heads, n_kv_heads, head_dim, dtype, softmax_scale=None):
+        code = {"f32": VS_F32, "bf16": VS_BF16}.get(dtype, dtype)
+        if softmax_scale is None:
+            softmax_scale = float(head_dim) ** -0.5
+        return cls(n_q_heads, n_kv_heads, head_dim, code, softmax_scale)
+
+
+class _CCache(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("capacity", ctypes.c_int32), ("len", ctypes.c_int32)]
+
+
+class Cache:
+    """Retained K/V rows of one layer of one stream: device tensors [capacity][Hkv][D] and a
+    host-side length."""
+
+    def __init__(self, k, v, length=0):
+        assert k.shape == v.shape and k.is_contiguous() and v.is_contiguous()
+        self.k, self.v = k, v
+        self.c = _CCache(k.data_ptr(), v.data_ptr(), k.shape[0], int(length))
+
+    @property
+    def len(self):
+        return self.c.len
+
+    @len.setter
+    def len(self, n):
+        self.c.len = int(n)
+
+    @property
+    def capacity(self):
+        return self.c.capacity
+
+
+def lib_path():
+    return os.path.join(_HERE, "libvideoscan.so")
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(path)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        sp, cp, ip = ctypes.POINTER(Shape), ctypes.POINTER(_CCache), ctypes.POINTER(ctypes.c_int32)
+        L.vs_status_string.restype = ctypes.c_char_p
+        L.vs_status_string.argtypes = [ctypes.c_int]
+        L.vs_workspace_bytes.restype = sz
+        L.vs_workspace_bytes.argtypes = [sp, i32, i32, i32]
+        L.vs_frame_prefill_attn.argtypes = [sp, cp, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.vs_frame_prefill_compact.argtypes = [sp, cp, vp, vp, vp, i32, vp, ip, vp, sz, vp]
+        L.vs_carrier_compact_append.argtypes = [sp, cp, vp, vp, i32, i32, ip, vp]
+        L.vs_carrier_compact_append_batched.argtypes = [sp, i32, vp, vp, i32, ip, vp, vp, i32, i32, ip,
+                                                        vp, sz, vp]
+        L.vs_decode_attn.argtypes = [sp, i32, vp, vp, i32, ip, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_carrier_mean_pool.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.vs_set_tuning.argtypes = [i32, i32]
+        for name in EXPORTS[2:]:
+            getattr(L, name).restype = ctypes.c_int
+        _LIB = L
+    return _LIB
+
+
+def status_string(code):
+    return lib().vs_status_string(int(code)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is not None:
+        return ctypes.c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _ptr(workspace), workspace.numel() * workspace.element_size()
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise VSError(rc, what)
+
+
+def workspace_bytes(shape, max_q_tokens, max_cache_rows, n_streams):
+    return int(lib().vs_workspace_bytes(ctypes.byref(shape), max_q_tokens, max_cache_rows, n_streams))
+
+
+def frame_prefill_attn(shape, cache, q, k_f, v_f, out, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().vs_frame_prefill_attn(ctypes.byref(shape), ctypes.byref(cache.c), _ptr(q), _ptr(k_f),
+                                       _ptr(v_f), q.shape[0], _ptr(out), wp, wb, _stream(stream)),
+           "vs_frame_prefill_attn")
+
+
+def frame_prefill_compact(shape, cache, q, k_f, v_f, out, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    row = ctypes.c_int32(-1)
+    _check(lib().vs_frame_prefill_compact(ctypes.byref(shape), ctypes.byref(cache.c), _ptr(q), _ptr(k_f),
+                                          _ptr(v_f), q.shape[0], _ptr(out), ctypes.byref(row), wp, wb,
+                                          _stream(stream)), "vs_frame_prefill_compact")
+    return row.value
+
+
+def carrier_compact_append(shape, cache, k_f, v_f, carrier_index=None, stream=None):
+    n = k_f.shape[0]
+    row = ctypes.c_int32(-1)
+    _check(lib().vs_carrier_compact_append(ctypes.byref(shape), ctypes.byref(cache.c), _ptr(k_f), _ptr(v_f),
+                                           n, n - 1 if carrier_index is None else carrier_index,
+                                           ctypes.byref(row), _stream(stream)), "vs_carrier_compact_append")
+    return row.value
+
+
+def carrier_compact_append_batched(shape, k_slab, v_slab, lens, k_f, v_f, carrier_index=None,
+                                   workspace=None, stream=None):
+    """lens: ctypes int32 array [n_caches] (host), updated in place.  Returns rows written."""
+    n_caches, capacity = k_slab.shape[0], k_slab.shape[1]
+    n = k_f.shape[1]
+    rows = (ctypes.c_int32 * n_caches)()
+    wp, wb = _ws(workspace)
+    _check(lib().vs_carrier_compact_append_batched(
+        ctypes.byref(shape), n_caches, _ptr(k_slab), _ptr(v_slab), capacity, lens, _ptr(k_f), _ptr(v_f),
+        n, n - 1 if carrier_index is None else carrier_index, rows, wp, wb, _stream(stream)),
+        "vs_carrier_compact_append_batched")
+    return list(rows)
+
+
+def decode_attn(shape, k_slab, v_slab, lens, q, k_new, v_new, out, workspace, stream=None):
+    """lens: ctypes int32 array [n_streams] (host), += 1 per stream when k_new is given."""
+    n_streams, capacity = k_slab.shape[0], k_slab.shape[1]
+    wp, wb = _ws(workspace)
+    _check(lib().vs_decode_attn(ctypes.byref(shape), n_streams, _ptr(k_slab), _ptr(v_slab), capacity, lens,
+                                _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), wp, wb, _stream(stream)),
+           "vs_decode_attn")
+
+
+def carrier_mean_pool(e, c_out, dtype, stream=None):
+    code = {"f32": VS_F32, "bf16": VS_BF16}.get(dtype, dtype)
+    _check(lib().vs_carrier_mean_pool(_ptr(e), e.shape[0], e.shape[1], code, _ptr(c_out), _stream(stream)),
+           "vs_carrier_mean_pool")
+
+
+TUNE_PREFILL_SPLITS, TUNE_PREFILL_ROW_BLOCKS, TUNE_DECODE_CHUNK_ROWS = 0, 1, 2
+
+
+def set_tuning(knob, value):
+    _check(lib().vs_set_tuning(int(knob), int(value)), "vs_set_tuning")

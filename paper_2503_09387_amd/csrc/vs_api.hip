@@ -1,0 +1,300 @@
+// C ABI of the library: argument checks, host-side length bookkeeping, dispatch.
+// Everything that can be refused is refused here, before any launch, so that the
+// kernels may assume consistent shapes.  See include/videoscan.h for the contract.
+#include <math.h>
+
+#include "vs_internal.h"
+
+using namespace vs;
+
+namespace vs {
+int g_tune_prefill_splits = 0;
+int g_tune_prefill_row_blocks = 0;
+int g_tune_decode_chunk_rows = 0;
+}  // namespace vs
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+vs_status check_shape(const vs_shape* s) {
+    if (!s) return VS_ERR_NULL;
+    if (s->n_q_heads < 1 || s->n_kv_heads < 1 || s->head_dim < 1) return VS_ERR_SHAPE;
+    if (s->n_q_heads % s->n_kv_heads != 0) return VS_ERR_SHAPE;
+    if (!isfinite(s->softmax_scale) || !(s->softmax_scale > 0.f)) return VS_ERR_SHAPE;
+    if (s->dtype != VS_F32 && s->dtype != VS_BF16) return VS_ERR_UNSUPPORTED;
+    if (s->n_q_heads / s->n_kv_heads > kMaxGroup) return VS_ERR_UNSUPPORTED;
+    if (s->n_q_heads > 4096) return VS_ERR_UNSUPPORTED;
+    if (s->dtype == VS_F32 && s->head_dim != 64 && s->head_dim != 128) return VS_ERR_UNSUPPORTED;
+    if (s->dtype == VS_BF16 && s->head_dim != 128) return VS_ERR_UNSUPPORTED;
+    return VS_OK;
+}
+
+inline size_t elem_bytes(const vs_shape* s) { return s->dtype == VS_F32 ? 4 : 2; }
+inline int64_t row_bytes(const vs_shape* s) {
+    return (int64_t)s->n_kv_heads * s->head_dim * (int64_t)elem_bytes(s);
+}
+
+vs_status check_cache(const vs_cache* c, bool need_room) {
+    if (!c) return VS_ERR_NULL;
+    if (c->capacity < 0 || c->len < 0) return VS_ERR_SHAPE;
+    if (c->len > c->capacity) return VS_ERR_CAPACITY;
+    if ((c->len > 0 || need_room) && (!c->k || !c->v)) return VS_ERR_NULL;
+    if (!aligned16(c->k) || !aligned16(c->v)) return VS_ERR_ALIGN;
+    if (need_room && c->len == c->capacity) return VS_ERR_CAPACITY;
+    return VS_OK;
+}
+
+constexpr int32_t kMaxTokens = 4096;
+constexpr int32_t kMaxStreams = 1024;
+
+size_t round256(size_t x) { return (x + 255) & ~size_t(255); }
+
+vs_status prefill_common(const vs_shape* shape, vs_cache* cache, bool append, const void* q,
+                         const void* k_f, const void* v_f, int32_t n_tokens, void* out,
+                         int32_t* row_written, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+    vs_status st = check_shape(shape);
+    if (st != VS_OK) return st;
+    st = check_cache(cache, append);
+    if (st != VS_OK) return st;
+    if (!q || !k_f || !v_f || !out) return VS_ERR_NULL;
+    if (n_tokens < 1 || n_tokens > kMaxTokens) return VS_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k_f) || !aligned16(v_f) || !aligned16(out)) return VS_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t rb = row_bytes(shape);
+    char* kdst = append ? static_cast<char*>(cache->k) + (int64_t)cache->len * rb : nullptr;
+    char* vdst = append ? static_cast<char*>(cache->v) + (int64_t)cache->len * rb : nullptr;
+    hipError_t e;
+    if (shape->dtype == VS_BF16) {
+        const size_t need = prefill_mfma_workspace_bytes(*shape, n_tokens);
+        if (!workspace || workspace_bytes < need) return VS_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return VS_ERR_ALIGN;
+        e = launch_prefill_mfma(*shape, cache->k, cache->v, cache->len, q, k_f, v_f, n_tokens, out,
+                                kdst, vdst, workspace, stream);
+    } else {
+        e = launch_prefill_simple(*shape, cache->k, cache->v, cache->len, q, k_f, v_f, n_tokens, out,
+                                  stream);
+        if (e == hipSuccess && append) {
+            LenTable t{};
+            t.v[0] = cache->len;
+            e = launch_append_rows(1, cache->k, cache->v, 0, &t, nullptr, k_f, v_f, 0,
+                                   (int64_t)(n_tokens - 1) * rb, (int32_t)rb, stream);
+        }
+    }
+    if (e != hipSuccess) return VS_ERR_HIP;
+    if (append) {
+        if (row_written) *row_written = cache->len;
+        cache->len += 1;
+    }
+    return VS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* vs_status_string(vs_status s) {
+    switch (s) {
+        case VS_OK: return "ok";
+        case VS_ERR_NULL: return "required pointer is NULL";
+        case VS_ERR_SHAPE: return "sizes out of range or inconsistent";
+        case VS_ERR_UNSUPPORTED: return "head_dim / dtype / head ratio not supported";
+        case VS_ERR_CAPACITY: return "cache full or len > capacity";
+        case VS_ERR_WORKSPACE: return "workspace missing or too small";
+        case VS_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case VS_ERR_HIP: return "HIP launch failure";
+    }
+    return "unknown status";
+}
+
+size_t vs_workspace_bytes(const vs_shape* shape, int32_t max_q_tokens, int32_t max_cache_rows,
+                          int32_t n_streams) {
+    if (check_shape(shape) != VS_OK) return 0;
+    if (max_q_tokens < 0 || max_cache_rows < 0 || n_streams < 0) return 0;
+    if (max_q_tokens > kMaxTokens || n_streams > kMaxStreams) return 0;
+    size_t need = 256;
+    if (shape->dtype == VS_BF16) {
+        if (max_q_tokens > 0) need = need > prefill_mfma_workspace_bytes(*shape, max_q_tokens)
+                                         ? need : prefill_mfma_workspace_bytes(*shape, max_q_tokens);
+        if (n_streams > 0) {
+            const int chunk = n_streams < kMaxStreamsPerLaunch ? n_streams : kMaxStreamsPerLaunch;
+            const size_t d = decode_mfma_workspace_bytes(*shape, chunk, max_cache_rows);
+            need = need > d ? need : d;
+        }
+    }
+    // batched compaction of more than 64 caches stages the lengths here
+    const size_t lens = round256(sizeof(int32_t) * (size_t)(n_streams > 0 ? n_streams : 0));
+    return round256(need) + lens;
+}
+
+vs_status vs_frame_prefill_attn(const vs_shape* shape, const vs_cache* cache, const void* q,
+                                const void* k_f, const void* v_f, int32_t n_tokens, void* out,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return prefill_common(shape, const_cast<vs_cache*>(cache), false, q, k_f, v_f, n_tokens, out,
+                          nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+vs_status vs_frame_prefill_compact(const vs_shape* shape, vs_cache* cache, const void* q,
+                                   const void* k_f, const void* v_f, int32_t n_tokens, void* out,
+                                   int32_t* row_written, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream) {
+    return prefill_common(shape, cache, true, q, k_f, v_f, n_tokens, out, row_written, workspace,
+                          workspace_bytes, hip_stream);
+}
+
+vs_status vs_carrier_compact_append(const vs_shape* shape, vs_cache* cache, const void* k_f,
+                                    const void* v_f, int32_t n_tokens, int32_t carrier_index,
+                                    int32_t* row_written, void* hip_stream) {
+    vs_status st = check_shape(shape);
+    if (st != VS_OK) return st;
+    if (!k_f || !v_f) return VS_ERR_NULL;
+    if (n_tokens < 1 || carrier_index < 0 || carrier_index >= n_tokens) return VS_ERR_SHAPE;
+    st = check_cache(cache, true);
+    if (st != VS_OK) return st;
+    if (!aligned16(k_f) || !aligned16(v_f)) return VS_ERR_ALIGN;
+    const int64_t rb = row_bytes(shape);
+    LenTable t{};
+    t.v[0] = cache->len;
+    hipError_t e = launch_append_rows(1, cache->k, cache->v, 0, &t, nullptr, k_f, v_f, 0,
+                                      (int64_t)carrier_index * rb, (int32_t)rb,
+                                      static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return VS_ERR_HIP;
+    if (row_written) *row_written = cache->len;
+    cache->len += 1;
+    return VS_OK;
+}
+
+vs_status vs_carrier_compact_append_batched(const vs_shape* shape, int32_t n_caches, void* k_slab,
+                                            void* v_slab, int32_t capacity, int32_t* lens,
+                                            const void* k_f, const void* v_f, int32_t n_tokens,
+                                            int32_t carrier_index, int32_t* rows_written,
+                                            void* workspace, size_t workspace_bytes,
+                                            void* hip_stream) {
+    vs_status st = check_shape(shape);
+    if (st != VS_OK) return st;
+    if (!k_slab || !v_slab || !lens || !k_f || !v_f) return VS_ERR_NULL;
+    if (n_caches < 1 || n_caches > (1 << 20) || capacity < 1) return VS_ERR_SHAPE;
+    if (n_tokens < 1 || carrier_index < 0 || carrier_index >= n_tokens) return VS_ERR_SHAPE;
+    if (!aligned16(k_slab) || !aligned16(v_slab) || !aligned16(k_f) || !aligned16(v_f)) return VS_ERR_ALIGN;
+    for (int32_t i = 0; i < n_caches; ++i) {
+        if (lens[i] < 0) return VS_ERR_SHAPE;
+        if (lens[i] >= capacity) return VS_ERR_CAPACITY;
+    }
+    const int64_t rb = row_bytes(shape);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (n_caches <= kMaxStreamsPerLaunch) {
+        LenTable t{};
+        for (int32_t i = 0; i < n_caches; ++i) t.v[i] = lens[i];
+        e = launch_append_rows(n_caches, k_slab, v_slab, (int64_t)capacity * rb, &t, nullptr, k_f, v_f,
+                               (int64_t)n_tokens * rb, (int64_t)carrier_index * rb, (int32_t)rb, stream);
+    } else {
+        if (!workspace || workspace_bytes < sizeof(int32_t) * (size_t)n_caches) return VS_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return VS_ERR_ALIGN;
+        // lens is pageable host memory: the runtime stages the copy before returning
+        e = hipMemcpyAsync(workspace, lens, sizeof(int32_t) * (size_t)n_caches, hipMemcpyHostToDevice,
+                           stream);
+        if (e == hipSuccess)
+            e = launch_append_rows(n_caches, k_slab, v_slab, (int64_t)capacity * rb, nullptr,
+                                   static_cast<const int32_t*>(workspace), k_f, v_f,
+                                   (int64_t)n_tokens * rb, (int64_t)carrier_index * rb, (int32_t)rb,
+                                   stream);
+    }
+    if (e != hipSuccess) return VS_ERR_HIP;
+    for (int32_t i = 0; i < n_caches; ++i) {
+        if (rows_written) rows_written[i] = lens[i];
+        lens[i] += 1;
+    }
+    return VS_OK;
+}
+
+vs_status vs_decode_attn(const vs_shape* shape, int32_t n_streams, void* k_slab, void* v_slab,
+                         int32_t capacity, int32_t* lens, const void* q, const void* k_new,
+                         const void* v_new, void* out, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+    vs_status st = check_shape(shape);
+    if (st != VS_OK) return st;
+    if (!k_slab || !v_slab || !lens || !q || !out) return VS_ERR_NULL;
+    if ((k_new == nullptr) != (v_new == nullptr)) return VS_ERR_NULL;
+    if (n_streams < 1 || n_streams > kMaxStreams || capacity < 1) return VS_ERR_SHAPE;
+    if (!aligned16(k_slab) || !aligned16(v_slab) || !aligned16(q) || !aligned16(out) ||
+        !aligned16(k_new) || !aligned16(v_new))
+        return VS_ERR_ALIGN;
+    const int add = k_new ? 1 : 0;
+    int32_t max_rows = 0;
+    for (int32_t s = 0; s < n_streams; ++s) {
+        if (lens[s] < 0) return VS_ERR_SHAPE;
+        if (lens[s] > capacity || lens[s] + add > capacity) return VS_ERR_CAPACITY;
+        if (lens[s] + add < 1) return VS_ERR_SHAPE;
+        if (lens[s] + add > max_rows) max_rows = lens[s] + add;
+    }
+    const bool mfma = shape->dtype == VS_BF16;
+    if (mfma) {
+        const int chunk = n_streams < kMaxStreamsPerLaunch ? n_streams : kMaxStreamsPerLaunch;
+        if (!workspace || workspace_bytes < decode_mfma_workspace_bytes(*shape, chunk, max_rows))
+            return VS_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return VS_ERR_ALIGN;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t rb = row_bytes(shape);
+    const int64_t qo_stride = (int64_t)shape->n_q_heads * shape->head_dim * (int64_t)elem_bytes(shape);
+    for (int32_t s0 = 0; s0 < n_streams; s0 += kMaxStreamsPerLaunch) {
+        const int32_t ns = (n_streams - s0) < kMaxStreamsPerLaunch ? (n_streams - s0) : kMaxStreamsPerLaunch;
+        char* ks = static_cast<char*>(k_slab) + (int64_t)s0 * capacity * rb;
+        char* vs_ = static_cast<char*>(v_slab) + (int64_t)s0 * capacity * rb;
+        LenTable t{};
+        hipError_t e = hipSuccess;
+        if (add) {
+            for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i];
+            e = launch_append_rows(ns, ks, vs_, (int64_t)capacity * rb, &t, nullptr,
+                                   static_cast<const char*>(k_new) + (int64_t)s0 * rb,
+                                   static_cast<const char*>(v_new) + (int64_t)s0 * rb, rb, 0,
+                                   (int32_t)rb, stream);
+            if (e != hipSuccess) return VS_ERR_HIP;
+        }
+        for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i] + add;
+        const char* qs = static_cast<const char*>(q) + (int64_t)s0 * qo_stride;
+        char* os = static_cast<char*>(out) + (int64_t)s0 * qo_stride;
+        if (mfma)
+            e = launch_decode_mfma(*shape, ns, ks, vs_, capacity, t, qs, os, workspace, stream);
+        else
+            e = launch_decode_simple(*shape, ns, ks, vs_, capacity, t, qs, os, stream);
+        if (e != hipSuccess) return VS_ERR_HIP;
+    }
+    if (add)
+        for (int32_t s = 0; s < n_streams; ++s) lens[s] += 1;
+    return VS_OK;
+}
+
+vs_status vs_set_tuning(int32_t knob, int32_t value) {
+    if (value < 0) return VS_ERR_SHAPE;
+    switch (knob) {
+        case VS_TUNE_PREFILL_SPLITS:
+            if (value > kMaxPrefillSplits) return VS_ERR_SHAPE;
+            g_tune_prefill_splits = value;
+            return VS_OK;
+        case VS_TUNE_PREFILL_ROW_BLOCKS:
+            if (value > 2) return VS_ERR_SHAPE;
+            g_tune_prefill_row_blocks = value;
+            return VS_OK;
+        case VS_TUNE_DECODE_CHUNK_ROWS:
+            if (value % 128 != 0) return VS_ERR_SHAPE;
+            g_tune_decode_chunk_rows = value;
+            return VS_OK;
+    }
+    return VS_ERR_SHAPE;
+}
+
+vs_status vs_carrier_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, void* c_out,
+                               void* hip_stream) {
+    if (!e || !c_out) return VS_ERR_NULL;
+    if (dtype != VS_F32 && dtype != VS_BF16) return VS_ERR_UNSUPPORTED;
+    if (n < 1 || d < 1) return VS_ERR_SHAPE;
+    if (d % (dtype == VS_F32 ? 4 : 8) != 0) return VS_ERR_SHAPE;
+    if (!aligned16(e) || !aligned16(c_out)) return VS_ERR_ALIGN;
+    return launch_mean_pool(e, n, d, dtype, c_out, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? VS_OK : VS_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,61 @@
+// Internal declarations shared by the C-ABI layer and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "videoscan.h"
+
+namespace vs {
+
+constexpr int kMaxStreamsPerLaunch = 64;  // lengths travel by value in the kernel arguments
+constexpr int kMaxPrefillSplits = 32;
+constexpr int kMaxGroup = 8;              // query heads per KV head
+
+// launch-plan overrides (0 = automatic), set through vs_set_tuning
+extern int g_tune_prefill_splits;
+extern int g_tune_prefill_row_blocks;
+extern int g_tune_decode_chunk_rows;
+
+struct LenTable {
+    int32_t v[kMaxStreamsPerLaunch];
+};
+
+// ---- storage <-> fp32 -------------------------------------------------------
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(__bf16 x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ __bf16 from_f32<__bf16>(float x) { return (__bf16)x; }  // RNE
+
+// ---- launchers (each validates nothing: the C-ABI layer has done it) ---------
+// fp32-arithmetic reference-shaped path, any storage type (used for VS_F32).
+hipError_t launch_prefill_simple(const vs_shape& s, const void* kc, const void* vc, int32_t len,
+                                 const void* q, const void* kf, const void* vf, int32_t n_tokens,
+                                 void* out, hipStream_t st);
+hipError_t launch_decode_simple(const vs_shape& s, int32_t n_streams, const void* k_slab,
+                                const void* v_slab, int32_t capacity, const LenTable& lens,
+                                const void* q, void* out, hipStream_t st);
+
+// bf16 MFMA prefill with split along cache rows; optional fused carrier append.
+size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens);
+hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc, int32_t len,
+                               const void* q, const void* kf, const void* vf, int32_t n_tokens,
+                               void* out, void* k_append_dst, void* v_append_dst, void* workspace,
+                               hipStream_t st);
+
+// bf16 split-K decode over ragged streams.
+size_t decode_mfma_workspace_bytes(const vs_shape& s, int32_t n_streams, int32_t max_rows);
+hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, const void* k_slab,
+                              const void* v_slab, int32_t capacity, const LenTable& lens,
+                              const void* q, void* out, void* workspace, hipStream_t st);
+
+// row copies
+hipError_t launch_append_rows(int32_t n_caches, void* k_slab, void* v_slab, int64_t cache_stride_bytes,
+                              const LenTable* lens_by_value, const int32_t* lens_device,
+                              const void* k_src, const void* v_src, int64_t src_stride_bytes,
+                              int64_t src_row_offset_bytes, int32_t row_bytes, hipStream_t st);
+
+hipError_t launch_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, void* c_out,
+                            hipStream_t st);
+
+}  // namespace vs

@@ -1,0 +1,222 @@
+// fp32-arithmetic attention path (used for VS_F32 storage), row copies and the mean pool.
+//
+// The attention kernel here is the small, definition-shaped one: a workgroup per
+// (query token, query head), scores for 256 keys at a time, running-max softmax
+// (Eq. 1 of the VideoScan paper, Section 3.1) and a value accumulation with one
+// thread per output coordinate.  It exists for fp32 storage, where the shapes are
+// tiny and accuracy (1e-5) is what matters; the bf16 shapes go through the MFMA
+// kernels.
+#include "vs_internal.h"
+
+namespace vs {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+template <bool kMax>
+__device__ __forceinline__ float block_reduce(float x, float* red) {
+    x = kMax ? wave_max(x) : wave_sum(x);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();  // red may still be read from the previous reduction
+    if ((threadIdx.x & 63) == 0) red[w] = x;
+    __syncthreads();
+    float r = red[0];
+#pragma unroll
+    for (int i = 1; i < kThreads / 64; ++i) r = kMax ? fmaxf(r, red[i]) : r + red[i];
+    return r;
+}
+
+// Grid: (query tokens, query heads, streams).  Stream z reads its cache at
+// kc + z*cache_stride (elements), valid rows lens.v[z] (or `len` when lens_used == 0).
+// Frame rows (kf != nullptr) follow the cache rows; query token i sees frame rows 0..i.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void attn_simple_kernel(
+    const T* __restrict__ kc, const T* __restrict__ vc, int64_t cache_stride, int32_t len,
+    LenTable lens, int lens_used, const T* __restrict__ q, const T* __restrict__ kf,
+    const T* __restrict__ vf, T* __restrict__ out, int Hq, int Hkv, float scale) {
+    const int i = blockIdx.x, h = blockIdx.y, z = blockIdx.z;
+    const int g = h / (Hq / Hkv);
+    const int tid = threadIdx.x;
+    const int L = lens_used ? lens.v[z] : len;
+    const int n = L + (kf ? i + 1 : 0);
+    const T* kcz = kc + (int64_t)z * cache_stride;
+    const T* vcz = vc + (int64_t)z * cache_stride;
+    const int64_t qrow = ((int64_t)z * gridDim.x + i) * Hq + h;
+
+    __shared__ float s_q[D];
+    __shared__ float s_p[kThreads];
+    __shared__ float s_red[kThreads / 64];
+    __shared__ float s_acc[kThreads];
+
+    if (tid < D) s_q[tid] = to_f32(q[qrow * D + tid]);
+    __syncthreads();
+
+    constexpr int KG = kThreads / D;  // key groups in the value accumulation
+    const int d = tid % D, kg = tid / D;
+    float m = -INFINITY, l = 0.f, acc = 0.f;
+
+    for (int base = 0; base < n; base += kThreads) {
+        const int j = base + tid;
+        float zj = -INFINITY;
+        if (j < n) {
+            const T* krow = (j < L) ? kcz + ((int64_t)j * Hkv + g) * D
+                                    : kf + ((int64_t)(j - L) * Hkv + g) * D;
+            float dot = 0.f;
+#pragma unroll 8
+            for (int e = 0; e < D; ++e) dot = fmaf(s_q[e], to_f32(krow[e]), dot);
+            zj = dot * scale;
+        }
+        const float cmax = block_reduce<true>(zj, s_red);  // finite: key `base` is visible
+        const float m_new = fmaxf(m, cmax);
+        const float alpha = expf(m - m_new);                // 0 on the first chunk
+        const float p = (j < n) ? expf(zj - m_new) : 0.f;
+        const float csum = block_reduce<false>(p, s_red);
+        l = l * alpha + csum;
+        acc *= alpha;
+        m = m_new;
+        s_p[tid] = p;
+        __syncthreads();
+        const int cnt = min(kThreads, n - base);
+        for (int jj = kg; jj < cnt; jj += KG) {
+            const int jr = base + jj;
+            const T* vrow = (jr < L) ? vcz + ((int64_t)jr * Hkv + g) * D
+                                     : vf + ((int64_t)(jr - L) * Hkv + g) * D;
+            acc = fmaf(s_p[jj], to_f32(vrow[d]), acc);
+        }
+        __syncthreads();
+    }
+    s_acc[tid] = acc;
+    __syncthreads();
+    if (tid < D) {
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < KG; ++k) t += s_acc[k * D + tid];
+        out[qrow * D + tid] = from_f32<T>(t / l);
+    }
+}
+
+template <typename T>
+hipError_t launch_attn_simple(const vs_shape& s, const void* kc, const void* vc, int64_t cache_stride,
+                              int32_t len, const LenTable& lens, int lens_used, int n_streams,
+                              const void* q, const void* kf, const void* vf, int32_t n_tokens,
+                              void* out, hipStream_t st) {
+    dim3 grid(n_tokens, s.n_q_heads, n_streams), block(kThreads);
+#define VS_GO(DD)                                                                              \
+    attn_simple_kernel<T, DD><<<grid, block, 0, st>>>(                                           \
+        (const T*)kc, (const T*)vc, cache_stride, len, lens, lens_used, (const T*)q,             \
+        (const T*)kf, (const T*)vf, (T*)out, s.n_q_heads, s.n_kv_heads, s.softmax_scale)
+    if (s.head_dim == 64) VS_GO(64);
+    else VS_GO(128);
+#undef VS_GO
+    return hipGetLastError();
+}
+
+// ---- row copies ------------------------------------------------------------
+// Block (i, which): copies `row_bytes` (multiple of 16) from run i's chosen row into
+// row len_i of cache i, for K (which = 0) or V (which = 1).
+__global__ __launch_bounds__(64) void append_rows_kernel(
+    char* __restrict__ k_slab, char* __restrict__ v_slab, int64_t cache_stride_bytes, LenTable lens,
+    const int32_t* __restrict__ lens_device, const char* __restrict__ k_src,
+    const char* __restrict__ v_src, int64_t src_stride_bytes, int64_t src_row_offset_bytes,
+    int32_t row_bytes) {
+    const int i = blockIdx.x;
+    const int32_t len = lens_device ? lens_device[i] : lens.v[i];
+    char* dst = (blockIdx.y ? v_slab : k_slab) + (int64_t)i * cache_stride_bytes + (int64_t)len * row_bytes;
+    const char* src = (blockIdx.y ? v_src : k_src) + (int64_t)i * src_stride_bytes + src_row_offset_bytes;
+    for (int o = threadIdx.x * 16; o < row_bytes; o += 64 * 16)
+        *reinterpret_cast<uint4*>(dst + o) = *reinterpret_cast<const uint4*>(src + o);
+}
+
+// ---- mean pool ---------------------------------------------------------------
+// Block: 64 column chunks x 4 row groups.  Row group r sums rows r, r+4, ... in order in
+// fp32; the four partial sums are added in order 0..3; one rounding at the end.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void mean_pool_kernel(const T* __restrict__ e, int n, int d,
+                                                        T* __restrict__ c) {
+    const int col = (blockIdx.x * 64 + (threadIdx.x & 63)) * VEC;
+    const int rg = threadIdx.x >> 6;
+    __shared__ float part[4][64][VEC];
+    float s[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) s[k] = 0.f;
+    if (col < d) {
+        for (int r = rg; r < n; r += 4) {
+            alignas(16) T tmp[VEC];
+            *reinterpret_cast<uint4*>(tmp) = *reinterpret_cast<const uint4*>(e + (int64_t)r * d + col);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) s[k] += to_f32(tmp[k]);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) part[rg][threadIdx.x & 63][k] = s[k];
+    __syncthreads();
+    if (rg == 0 && col < d) {
+        alignas(16) T tmp[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const int t = threadIdx.x;
+            const float tot = ((part[0][t][k] + part[1][t][k]) + part[2][t][k]) + part[3][t][k];
+            tmp[k] = from_f32<T>(tot / (float)n);
+        }
+        *reinterpret_cast<uint4*>(c + col) = *reinterpret_cast<const uint4*>(tmp);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_prefill_simple(const vs_shape& s, const void* kc, const void* vc, int32_t len,
+                                 const void* q, const void* kf, const void* vf, int32_t n_tokens,
+                                 void* out, hipStream_t st) {
+    LenTable none{};
+    if (s.dtype == VS_F32)
+        return launch_attn_simple<float>(s, kc, vc, 0, len, none, 0, 1, q, kf, vf, n_tokens, out, st);
+    return launch_attn_simple<__bf16>(s, kc, vc, 0, len, none, 0, 1, q, kf, vf, n_tokens, out, st);
+}
+
+hipError_t launch_decode_simple(const vs_shape& s, int32_t n_streams, const void* k_slab,
+                                const void* v_slab, int32_t capacity, const LenTable& lens,
+                                const void* q, void* out, hipStream_t st) {
+    const int64_t stride = (int64_t)capacity * s.n_kv_heads * s.head_dim;
+    if (s.dtype == VS_F32)
+        return launch_attn_simple<float>(s, k_slab, v_slab, stride, 0, lens, 1, n_streams, q, nullptr,
+                                         nullptr, 1, out, st);
+    return launch_attn_simple<__bf16>(s, k_slab, v_slab, stride, 0, lens, 1, n_streams, q, nullptr,
+                                      nullptr, 1, out, st);
+}
+
+hipError_t launch_append_rows(int32_t n_caches, void* k_slab, void* v_slab, int64_t cache_stride_bytes,
+                              const LenTable* lens_by_value, const int32_t* lens_device,
+                              const void* k_src, const void* v_src, int64_t src_stride_bytes,
+                              int64_t src_row_offset_bytes, int32_t row_bytes, hipStream_t st) {
+    LenTable t{};
+    if (lens_by_value) t = *lens_by_value;
+    append_rows_kernel<<<dim3(n_caches, 2), 64, 0, st>>>(
+        (char*)k_slab, (char*)v_slab, cache_stride_bytes, t, lens_device, (const char*)k_src,
+        (const char*)v_src, src_stride_bytes, src_row_offset_bytes, row_bytes);
+    return hipGetLastError();
+}
+
+hipError_t launch_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, void* c_out,
+                            hipStream_t st) {
+    if (dtype == VS_F32) {
+        const int blocks = (d / 4 + 63) / 64;
+        mean_pool_kernel<float, 4><<<blocks, 256, 0, st>>>((const float*)e, n, d, (float*)c_out);
+    } else {
+        const int blocks = (d / 8 + 63) / 64;
+        mean_pool_kernel<__bf16, 8><<<blocks, 256, 0, st>>>((const __bf16*)e, n, d, (__bf16*)c_out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace vs

@@ -1,0 +1,165 @@
+"""The C-ABI library on a machine without a GPU: it loads, exports what the header declares,
+and refuses bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2503_09387_amd as vs
+from paper_2503_09387_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000  # 16-byte aligned, never dereferenced: every call below must fail first
+ODD = FAKE + 4
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "videoscan.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vs_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = _declared()
+    assert {"vs_frame_prefill_attn", "vs_carrier_compact_append", "vs_decode_attn",
+            "vs_carrier_mean_pool", "vs_workspace_bytes"} <= set(names)
+    lib = vs.lib()
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in the header but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_status_strings():
+    seen = {vs.status_string(c) for c in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+    assert vs.status_string(99) == "unknown status"
+
+
+def _shape(hq=28, hkv=4, d=128, dt=vs.VS_BF16, scale=None):
+    return vs.Shape.make(hq, hkv, d, dt, scale)
+
+
+def _cache(k=FAKE, v=FAKE, cap=8, ln=2):
+    return binding._CCache(k, v, cap, ln)
+
+
+def _prefill(shape, cache, q=FAKE, kf=FAKE, vf=FAKE, n=4, out=FAKE, ws=FAKE, wsb=1 << 30):
+    return vs.lib().vs_frame_prefill_attn(ctypes.byref(shape), ctypes.byref(cache), q, kf, vf, n, out,
+                                          ws, wsb, None)
+
+
+def test_shape_validation():
+    c = _cache()
+    assert _prefill(_shape(hq=28, hkv=5), c) == 2          # Hq % Hkv
+    assert _prefill(_shape(hq=36, hkv=4), c) == 3          # ratio above 8
+    assert _prefill(_shape(d=96), c) == 3                  # head_dim
+    assert _prefill(_shape(d=64), c) == 3                  # bf16 needs 128
+    assert _prefill(_shape(dt=7), c) == 3
+    assert _prefill(_shape(scale=float("nan")), c) == 2
+    assert _prefill(_shape(scale=-1.0), c) == 2
+    assert vs.lib().vs_frame_prefill_attn(None, ctypes.byref(c), FAKE, FAKE, FAKE, 4, FAKE, FAKE, 64, None) == 1
+    assert vs.workspace_bytes(_shape(d=96), 16, 16, 1) == 0
+    assert vs.workspace_bytes(_shape(), 170, 4552, 16) >= 256
+
+
+def test_prefill_argument_errors():
+    s = _shape()
+    assert _prefill(s, _cache(), q=None) == 1
+    assert _prefill(s, _cache(), out=None) == 1
+    assert _prefill(s, _cache(k=None)) == 1
+    assert _prefill(s, _cache(), n=0) == 2
+    assert _prefill(s, _cache(), n=5000) == 2
+    assert _prefill(s, _cache(ln=9)) == 4                  # len > capacity
+    assert _prefill(s, _cache(ln=-1)) == 2
+    assert _prefill(s, _cache(), q=ODD) == 6
+    assert _prefill(s, _cache(k=ODD)) == 6
+    assert _prefill(s, _cache(), ws=None) == 5
+    assert _prefill(s, _cache(), wsb=16) == 5
+    assert _prefill(s, _cache(), ws=ODD) == 6
+
+
+def test_append_argument_errors_leave_len_untouched():
+    s = _shape()
+    L = vs.lib()
+    row = ctypes.c_int32(-7)
+
+    def app(cache, kf=FAKE, vf=FAKE, n=4, ci=3):
+        return L.vs_carrier_compact_append(ctypes.byref(s), ctypes.byref(cache), kf, vf, n, ci,
+                                           ctypes.byref(row), None)
+
+    full = _cache(cap=8, ln=8)
+    assert app(full) == 4 and full.len == 8 and row.value == -7
+    c = _cache()
+    assert app(c, ci=4) == 2 and app(c, ci=-1) == 2 and app(c, n=0) == 2
+    assert app(c, kf=None) == 1 and app(c, vf=ODD) == 6
+    assert app(_cache(k=None)) == 1
+    assert c.len == 2
+    # fused prefill+compaction refuses a full cache before launching
+    assert L.vs_frame_prefill_compact(ctypes.byref(s), ctypes.byref(full), FAKE, FAKE, FAKE, 4, FAKE,
+                                      ctypes.byref(row), FAKE, 1 << 30, None) == 4
+    assert full.len == 8
+
+
+def test_batched_append_argument_errors():
+    s = _shape()
+    L = vs.lib()
+    lens = (ctypes.c_int32 * 3)(1, 8, 2)
+
+    def go(n=3, cap=8, ci=3, ks=FAKE, ws=None, wsb=0, lens_=lens):
+        return L.vs_carrier_compact_append_batched(ctypes.byref(s), n, ks, FAKE, cap, lens_, FAKE, FAKE, 4,
+                                                   ci, None, ws, wsb, None)
+
+    assert go() == 4 and list(lens) == [1, 8, 2]           # one cache is full: nothing happens
+    assert go(n=0) == 2 and go(ci=9) == 2 and go(ks=None) == 1 and go(ks=ODD) == 6
+    many = (ctypes.c_int32 * 100)(*([0] * 100))
+    assert go(n=100, lens_=many) == 5                      # needs workspace for the lengths
+    assert list(many) == [0] * 100
+
+
+def test_decode_argument_errors():
+    s = _shape()
+    L = vs.lib()
+    lens = (ctypes.c_int32 * 2)(5, 8)
+
+    def dec(n=2, cap=8, q=FAKE, kn=FAKE, vn=FAKE, ws=FAKE, wsb=1 << 30, lens_=lens):
+        return L.vs_decode_attn(ctypes.byref(s), n, FAKE, FAKE, cap, lens_, q, kn, vn, FAKE, ws, wsb, None)
+
+    assert dec() == 4 and list(lens) == [5, 8]             # stream 1 has no room for the new row
+    assert dec(kn=None) == 1                               # k_new without v_new
+    assert dec(n=0) == 2 and dec(n=2000) == 2 and dec(q=None) == 1 and dec(q=ODD) == 6
+    ok_lens = (ctypes.c_int32 * 2)(5, 7)
+    assert dec(lens_=ok_lens, ws=None) == 5 and dec(lens_=ok_lens, wsb=8) == 5
+    empty = (ctypes.c_int32 * 2)(0, 3)
+    assert dec(lens_=empty, kn=None, vn=None) == 2         # a stream with nothing to attend to
+    assert list(ok_lens) == [5, 7] and list(empty) == [0, 3]
+
+
+def test_mean_pool_and_tuning_argument_errors():
+    L = vs.lib()
+    assert L.vs_carrier_mean_pool(None, 4, 8, 0, FAKE, None) == 1
+    assert L.vs_carrier_mean_pool(FAKE, 0, 8, 0, FAKE, None) == 2
+    assert L.vs_carrier_mean_pool(FAKE, 4, 6, 0, FAKE, None) == 2   # d % 4
+    assert L.vs_carrier_mean_pool(FAKE, 4, 12, 1, FAKE, None) == 2  # d % 8 for bf16
+    assert L.vs_carrier_mean_pool(FAKE, 4, 8, 5, FAKE, None) == 3
+    assert L.vs_carrier_mean_pool(ODD, 4, 8, 0, FAKE, None) == 6
+    assert L.vs_set_tuning(0, 33) == 2 and L.vs_set_tuning(1, 3) == 2
+    assert L.vs_set_tuning(2, 100) == 2 and L.vs_set_tuning(9, 1) == 2
+    assert L.vs_set_tuning(0, 4) == 0 and L.vs_set_tuning(0, 0) == 0
+
+
+def test_product_path_does_not_touch_the_oracle():
+    """The package must not import or mention the oracle: it is test infrastructure only."""
+    pkg = os.path.join(ROOT, "paper_2503_09387_amd")
+    for base, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(base, f)).read()
+                assert "oracle" not in text.lower(), f"{f} refers to the oracle"
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "_HERE", str(tmp_path))
+    with pytest.raises(RuntimeError):
+        binding.lib()

@@ -1,0 +1,374 @@
+"""GPU parity: the HIP path behind the C ABI against the CPU fp64 oracle on the same seeded
+bytes.  Integer results (row indices, lengths, copied rows) must be bit-exact; floats within
+the tolerances in gpu_util."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_09387_amd as vs
+from gpu_util import (DEV, check_close, lens_array, oracle_prefill_rows, run_prefill, scale32,
+                      torch_dtype, vs_shape, workspace)
+from synth import (CONFIGS, AttnShape, cache_rows, cfg1_inputs, decode_lengths, decode_step_inputs,
+                   draw, frame_inputs, to_f64)
+
+pytestmark = pytest.mark.gpu
+
+QW = CONFIGS["cfg2"]["shape"]
+
+
+@pytest.fixture(autouse=True)
+def _reset_tuning():
+    yield
+    for knob in (0, 1, 2):
+        vs.set_tuning(knob, 0)
+
+
+def same_bits(dev_t, host_t):
+    return torch.equal(dev_t.cpu().view(torch.uint8), host_t.contiguous().view(torch.uint8))
+
+
+# ---------------------------------------------------------------------------- cfg1
+def test_cfg1_tiny_fp32_pool_prefill_compact():
+    c = CONFIGS["cfg1"]
+    s = c["shape"]
+    x = cfg1_inputs(c)
+    L, T = c["prefix"], c["n_visual"] + 1
+    # carrier embedding
+    e = x["e"].to(DEV)
+    pooled = torch.empty(c["hidden"], dtype=torch.float32, device=DEV)
+    vs.carrier_mean_pool(e, pooled, "f32")
+    check_close(pooled, oracle.mean_pool(to_f64(x["e"])), "f32", "mean pool")
+    # prefill
+    out, cache, _ = run_prefill(s, x["k_c"], x["v_c"], L, x["q"], x["k_f"], x["v_f"], capacity=L + 1)
+    ref = oracle_prefill_rows(s, x["q"], x["k_c"], x["v_c"], L, x["k_f"], x["v_f"])
+    check_close(out, ref, "f32", "cfg1 prefill")
+    # compaction
+    row = vs.carrier_compact_append(vs_shape(s), cache, x["k_f"].to(DEV), x["v_f"].to(DEV))
+    torch.cuda.synchronize()
+    ok_k, ok_v = to_f64(x["k_c"]).copy(), to_f64(x["v_c"]).copy()
+    ok_k, ok_v = np.concatenate([ok_k, np.zeros((1,) + ok_k.shape[1:])]), np.concatenate([ok_v, np.zeros((1,) + ok_v.shape[1:])])
+    orow, olen = oracle.compact_append(ok_k, ok_v, L, to_f64(x["k_f"]), to_f64(x["v_f"]))
+    assert (row, cache.len) == (orow, olen) == (16, 17)
+    assert np.array_equal(cache.k.double().cpu().numpy(), ok_k) and np.array_equal(cache.v.double().cpu().numpy(), ok_v)
+    # fused entry point gives the same bits
+    out2, cache2, row2 = run_prefill(s, x["k_c"], x["v_c"], L, x["q"], x["k_f"], x["v_f"], capacity=L + 1, fused=True)
+    assert row2 == 16 and cache2.len == 17
+    assert torch.equal(out2, out) and torch.equal(cache2.k, cache.k) and torch.equal(cache2.v, cache.v)
+
+
+# ---------------------------------------------------------------------------- cfg2
+@pytest.mark.parametrize("fused", [False, True])
+def test_cfg2_stream_of_64_frames(fused):
+    c = CONFIGS["cfg2"]
+    s, P0, F, T = c["shape"], c["prefix"], c["frames"], c["n_visual"] + 1
+    pk, pv = cache_rows(c["seed"], s, P0, c["sigma"])
+    cap = P0 + F
+    kc = torch.zeros((cap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+    vc = torch.zeros_like(kc)
+    kc[:P0].copy_(pk)
+    vc[:P0].copy_(pv)
+    cache = vs.Cache(kc, vc, P0)
+    ws = workspace(s, T, cap, 0)
+    ok, ov = np.zeros((cap, s.n_kv_heads, s.head_dim)), np.zeros((cap, s.n_kv_heads, s.head_dim))
+    ok[:P0], ov[:P0] = to_f64(pk), to_f64(pv)
+    olen = P0
+    sh = vs_shape(s)
+    worst = (0.0, 0.0)
+    for f in range(F):
+        q, kf, vf = frame_inputs(c["seed"], s, T, c["sigma"], frame=f)
+        qd, kfd, vfd = q.to(DEV), kf.to(DEV), vf.to(DEV)
+        out = torch.empty_like(qd)
+        if fused:
+            row = vs.frame_prefill_compact(sh, cache, qd, kfd, vfd, out, ws)
+        else:
+            vs.frame_prefill_attn(sh, cache, qd, kfd, vfd, out, ws)
+            row = vs.carrier_compact_append(sh, cache, kfd, vfd)
+        ref = oracle.frame_prefill(to_f64(q), ok[:olen], ov[:olen], to_f64(kf), to_f64(vf), scale32(s))
+        orow, olen = oracle.compact_append(ok, ov, olen, to_f64(kf), to_f64(vf))
+        assert (row, cache.len) == (orow, olen), f"frame {f}"
+        torch.cuda.synchronize()
+        e = check_close(out, ref, "bf16", f"cfg2 frame {f}")
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+    assert cache.len == 264
+    assert np.array_equal(kc.double().cpu().numpy(), ok) and np.array_equal(vc.double().cpu().numpy(), ov)
+    print(f"cfg2 worst max-abs {worst[0]:.2e} mean-abs {worst[1]:.2e}")
+
+
+# ---------------------------------------------------------------------------- cfg3
+def test_cfg3_long_stream_28_layers_sampled():
+    """Full shapes (28 layers, 4296 retained rows, 170-token frames), the stream shortened to 3
+    frames placed at the start, middle and end of the 256-frame run via the initial length.
+    Indices, lengths and appended bytes on every (frame, layer); floats on sampled layers and
+    sampled tokens."""
+    c = CONFIGS["cfg3"]
+    s, T, NL = c["shape"], c["n_visual"] + 1, c["layers"]
+    sh = vs_shape(s)
+    cap = c["prefix"] + c["frames"]
+    ws = workspace(s, T, cap, 0)
+    sample_layers = {0, 13, 27}
+    tokens = np.array([0, 1, 37, 84, 85, 127, 168, 169])
+    for start_frame in (0, 127, 253):
+        caches, host = [], []
+        for l in range(NL):
+            L0 = c["prefix"] + start_frame
+            hk, hv = cache_rows(c["seed"], s, L0, c["sigma"], layer=l)
+            kc = torch.zeros((cap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+            vc = torch.zeros_like(kc)
+            kc[:L0].copy_(hk)
+            vc[:L0].copy_(hv)
+            caches.append(vs.Cache(kc, vc, L0))
+            host.append([hk, hv])
+        for f in range(start_frame, start_frame + 3):
+            for l in range(NL):
+                q, kf, vf = frame_inputs(c["seed"], s, T, c["sigma"], frame=f, layer=l)
+                qd, kfd, vfd = q.to(DEV), kf.to(DEV), vf.to(DEV)
+                out = torch.empty_like(qd)
+                L = caches[l].len
+                row = vs.frame_prefill_compact(sh, caches[l], qd, kfd, vfd, out, ws)
+                assert row == c["prefix"] + f and caches[l].len == row + 1
+                if l in sample_layers:
+                    ref = oracle_prefill_rows(s, q, host[l][0], host[l][1], L, kf, vf, tokens)
+                    torch.cuda.synchronize()
+                    check_close(out[torch.from_numpy(tokens).to(DEV)], ref, "bf16", f"cfg3 frame {f} layer {l}")
+                host[l][0] = torch.cat([host[l][0], kf[T - 1:]])
+                host[l][1] = torch.cat([host[l][1], vf[T - 1:]])
+        torch.cuda.synchronize()
+        for l in range(NL):
+            n = caches[l].len
+            assert n == c["prefix"] + start_frame + 3
+            assert same_bits(caches[l].k[:n], host[l][0]) and same_bits(caches[l].v[:n], host[l][1])
+            assert not caches[l].k[n:].any() and not caches[l].v[n:].any()
+    assert c["prefix"] + c["frames"] == 4552
+
+
+# ---------------------------------------------------------------------------- cfg4
+def test_cfg4_decode_16_ragged_streams():
+    """Full launch shape (16 streams, lengths U[512,8192]+128, capacity 8384); 2 of the 28 layers
+    (each layer is the same launch), 6 of the 64 steps with floats checked on every one."""
+    c = CONFIGS["cfg4"]
+    s, S = c["shape"], c["streams"]
+    sh = vs_shape(s)
+    lens0 = decode_lengths(c["seed"], S, c["carrier_lo"], c["carrier_hi"], c["text_hist"])
+    assert min(lens0) >= 640 and max(lens0) <= 8320
+    cap = c["carrier_hi"] + c["text_hist"] + c["steps"]
+    ws = workspace(s, 0, cap, S)
+    for layer in (0, 27):
+        ks = torch.zeros((S, cap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+        vsl = torch.zeros_like(ks)
+        ok = [np.zeros((cap, s.n_kv_heads, s.head_dim)) for _ in range(S)]
+        ov = [np.zeros((cap, s.n_kv_heads, s.head_dim)) for _ in range(S)]
+        for i in range(S):
+            hk, hv = cache_rows(c["seed"], s, lens0[i], c["sigma"], layer=layer, stream=i)
+            ks[i, :lens0[i]].copy_(hk)
+            vsl[i, :lens0[i]].copy_(hv)
+            ok[i][:lens0[i]], ov[i][:lens0[i]] = to_f64(hk), to_f64(hv)
+        lens = lens_array(lens0)
+        olens = list(lens0)
+        for step in range(6):
+            q, kn, vn = decode_step_inputs(c["seed"], s, S, c["sigma"], step=step, layer=layer)
+            out = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+            vs.decode_attn(sh, ks, vsl, lens, q.to(DEV), kn.to(DEV), vn.to(DEV), out, ws)
+            ref = np.zeros((S, s.n_q_heads, s.head_dim))
+            for i in range(S):
+                ref[i], olens[i] = oracle.decode(to_f64(q[i]), ok[i], ov[i], olens[i], to_f64(kn[i]),
+                                                 to_f64(vn[i]), scale32(s))
+            assert list(lens) == olens, f"lengths after step {step}"
+            torch.cuda.synchronize()
+            check_close(out, ref, "bf16", f"cfg4 layer {layer} step {step}")
+        for i in range(S):
+            assert np.array_equal(ks[i].double().cpu().numpy(), ok[i])
+            assert np.array_equal(vsl[i].double().cpu().numpy(), ov[i])
+
+
+# ---------------------------------------------------------------------------- cfg5
+def test_cfg5_dense_and_compact_cache_same_frame():
+    c = CONFIGS["cfg5"]
+    s, T = c["shape"], c["n_visual"] + 1
+    q, kf, vf = frame_inputs(c["seed"], s, T, c["sigma"])
+    tokens = np.array([0, 2, 36, 37, 90, 128, 168, 169])
+    for name, rows, stream in (("dense", c["dense_rows"], 0), ("compact", c["compact_rows"], 1)):
+        hk, hv = cache_rows(c["seed"], s, rows, c["sigma"], stream=stream)
+        out, _, _ = run_prefill(s, hk, hv, rows, q, kf, vf)
+        if name == "compact":
+            ref = oracle_prefill_rows(s, q, hk, hv, rows, kf, vf)
+            check_close(out, ref, "bf16", "cfg5 compact")
+        else:
+            ref = oracle_prefill_rows(s, q, hk, hv, rows, kf, vf, tokens)
+            check_close(out[torch.from_numpy(tokens).to(DEV)], ref, "bf16", "cfg5 dense (sampled tokens)")
+
+
+# ---------------------------------------------------------------------------- prefill edges
+@pytest.mark.parametrize("L,T,gain", [(0, 1, 1), (0, 5, 1), (1, 1, 1), (63, 2, 1), (64, 64, 1), (65, 170, 1),
+                                      (200, 170, 8), (263, 170, 1), (1000, 19, 8), (4551, 170, 8), (130, 512, 1)])
+def test_prefill_bf16_shapes_and_peaked_softmax(L, T, gain):
+    s = QW
+    hk, hv = cache_rows(11, s, max(L, 1), 0.5)
+    q, kf, vf = frame_inputs(11, s, T, 0.5, frame=L, layer=T % 7, q_gain=gain)
+    out, _, _ = run_prefill(s, hk, hv, L, q, kf, vf)
+    check_close(out, oracle_prefill_rows(s, q, hk, hv, L, kf, vf), "bf16", f"L={L} T={T} gain={gain}")
+    if L == 0:  # a single visible key returns its V row exactly
+        assert same_bits(out[0].reshape(s.n_kv_heads, s.group, -1)[:, 0], vf[0])
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 8), (8, 1), (12, 4), (16, 2)])
+def test_prefill_other_head_groupings(hq, hkv):
+    s = AttnShape(hq, hkv, 128, "bf16")
+    L, T = 150, 70
+    hk, hv = cache_rows(12, s, L, 0.5)
+    q, kf, vf = frame_inputs(12, s, T, 0.5, q_gain=4)
+    out, _, _ = run_prefill(s, hk, hv, L, q, kf, vf)
+    check_close(out, oracle_prefill_rows(s, q, hk, hv, L, kf, vf), "bf16", f"Hq={hq} Hkv={hkv}")
+
+
+@pytest.mark.parametrize("row_blocks", [1, 2])
+def test_prefill_result_does_not_depend_on_the_split(row_blocks):
+    s = QW
+    L, T = 1500, 170
+    hk, hv = cache_rows(13, s, L, 0.5)
+    q, kf, vf = frame_inputs(13, s, T, 0.5, q_gain=4)
+    ref = oracle_prefill_rows(s, q, hk, hv, L, kf, vf)
+    vs.set_tuning(vs.TUNE_PREFILL_ROW_BLOCKS, row_blocks)
+    outs = []
+    for splits in (1, 2, 5, 12, 32):
+        vs.set_tuning(vs.TUNE_PREFILL_SPLITS, splits)
+        out, _, _ = run_prefill(s, hk, hv, L, q, kf, vf)
+        check_close(out, ref, "bf16", f"splits={splits} row_blocks={row_blocks}")
+        outs.append(out.float())
+    for o in outs[1:]:
+        assert (o - outs[0]).abs().max().item() <= 2 ** -7 * outs[0].abs().max().item()
+
+
+def test_prefill_uniform_scores_is_running_mean_at_full_size():
+    """Q = 0: every row is the mean of its visible V rows (closed form, any size)."""
+    s = QW
+    L, T = 4296, 170
+    hk, hv = cache_rows(14, s, L, 0.5)
+    _, kf, vf = frame_inputs(14, s, T, 0.5)
+    q = torch.zeros((T, s.n_q_heads, s.head_dim), dtype=torch.bfloat16)
+    out, _, _ = run_prefill(s, hk, hv, L, q, kf, vf)
+    v_all = np.concatenate([to_f64(hv), to_f64(vf)])
+    csum = np.cumsum(v_all, axis=0)
+    ref = np.stack([csum[L + t] / (L + t + 1) for t in range(T)])  # [T][Hkv][D]
+    ref = np.repeat(ref, s.group, axis=1)
+    check_close(out, ref, "bf16", "uniform scores")
+
+
+def test_prefill_fp32_path_larger_shapes():
+    for (hq, hkv, d, L, T) in [(4, 2, 128, 700, 9), (6, 3, 64, 0, 3), (8, 1, 64, 300, 40)]:
+        s = AttnShape(hq, hkv, d, "f32")
+        hk, hv = cache_rows(15, s, max(L, 1), 1.0)
+        q, kf, vf = frame_inputs(15, s, T, 1.0)
+        out, _, _ = run_prefill(s, hk, hv, L, q, kf, vf)
+        check_close(out, oracle_prefill_rows(s, q, hk, hv, L, kf, vf), "f32", f"fp32 {hq}/{hkv}/{d} L={L}")
+
+
+# ---------------------------------------------------------------------------- decode edges
+def _decode_case(s, lens0, cap, seed, gain=1.0, with_new=True):
+    S = len(lens0)
+    dt = torch_dtype(s.dtype)
+    sigma = 0.5 if s.dtype == "bf16" else 1.0
+    ks = torch.zeros((S, cap, s.n_kv_heads, s.head_dim), dtype=dt, device=DEV)
+    vsl = torch.zeros_like(ks)
+    ok, ov = [], []
+    for i in range(S):
+        hk, hv = cache_rows(seed, s, max(lens0[i], 1), sigma, stream=i)
+        ks[i, :lens0[i]].copy_(hk[:lens0[i]])
+        vsl[i, :lens0[i]].copy_(hv[:lens0[i]])
+        a, b = np.zeros((cap, s.n_kv_heads, s.head_dim)), np.zeros((cap, s.n_kv_heads, s.head_dim))
+        a[:lens0[i]], b[:lens0[i]] = to_f64(hk[:lens0[i]]), to_f64(hv[:lens0[i]])
+        ok.append(a)
+        ov.append(b)
+    q, kn, vn = decode_step_inputs(seed, s, S, sigma, q_gain=gain)
+    lens = lens_array(lens0)
+    out = torch.full(q.shape, float("nan"), dtype=dt, device=DEV)
+    ws = workspace(s, 0, cap, S)
+    vs.decode_attn(vs_shape(s), ks, vsl, lens, q.to(DEV), kn.to(DEV) if with_new else None,
+                   vn.to(DEV) if with_new else None, out, ws)
+    torch.cuda.synchronize()
+    ref = np.zeros((S, s.n_q_heads, s.head_dim))
+    for i in range(S):
+        ref[i], n = oracle.decode(to_f64(q[i]), ok[i], ov[i], lens0[i], to_f64(kn[i]) if with_new else None,
+                                  to_f64(vn[i]) if with_new else None, scale32(s))
+        assert lens[i] == n
+        assert np.array_equal(ks[i].double().cpu().numpy(), ok[i]) and np.array_equal(vsl[i].double().cpu().numpy(), ov[i])
+    return out, ref, (q, kn, vn)
+
+
+@pytest.mark.parametrize("lens0,gain", [([0], 1), ([1, 2, 30, 31, 32, 33, 126, 127, 128, 129, 1000, 5], 1),
+                                        ([777], 8), ([8319, 640, 4000], 8)])
+def test_decode_ragged_lengths(lens0, gain):
+    out, ref, (q, kn, vn) = _decode_case(QW, lens0, 8384 if max(lens0) > 1000 else 1024, 21, gain)
+    check_close(out, ref, "bf16", f"decode lens={lens0}")
+    if lens0 == [0]:  # empty cache: the output is the new V row exactly
+        assert same_bits(out[0].reshape(QW.n_kv_heads, QW.group, -1)[:, 0], vn[0])
+
+
+def test_decode_without_new_row_and_many_streams():
+    lens0 = [40 + 13 * i for i in range(70)]  # more than one launch worth of streams
+    out, ref, _ = _decode_case(QW, lens0, 1024, 22, with_new=False)
+    check_close(out, ref, "bf16", "decode, 70 streams, no append")
+
+
+def test_decode_result_does_not_depend_on_the_chunking():
+    ref_out = None
+    for chunk in (128, 256, 1024, 8192):
+        vs.set_tuning(vs.TUNE_DECODE_CHUNK_ROWS, chunk)
+        out, ref, _ = _decode_case(QW, [3000, 129, 5000], 5120, 23, gain=4)
+        check_close(out, ref, "bf16", f"chunk_rows={chunk}")
+        if ref_out is None:
+            ref_out = out.float()
+        assert (out.float() - ref_out).abs().max().item() <= 2 ** -7 * ref_out.abs().max().item()
+
+
+def test_decode_equals_one_token_prefill():
+    s, L = QW, 900
+    out, ref, (q, kn, vn) = _decode_case(s, [L], 1024, 24, gain=4)
+    hk, hv = cache_rows(24, s, L, 0.5, stream=0)
+    pre, _, _ = run_prefill(s, hk, hv, L, q[0:1], kn[0:1], vn[0:1])
+    check_close(pre, ref, "bf16", "one-token prefill vs oracle decode")
+    assert (pre.float() - out.float()).abs().max().item() <= 2 ** -7 * out.float().abs().max().item()
+
+
+def test_decode_fp32_path():
+    s = AttnShape(4, 2, 64, "f32")
+    out, ref, _ = _decode_case(s, [5, 300, 1], 512, 25)
+    check_close(out, ref, "f32", "fp32 decode")
+
+
+# ---------------------------------------------------------------------------- pool, batched append
+@pytest.mark.parametrize("n,d,dtype", [(169, 3584, "bf16"), (49, 256, "f32"), (1, 8, "bf16"), (7, 1000, "f32")])
+def test_mean_pool(n, d, dtype):
+    e = draw(31, (n, d), 1.0, dtype)
+    out = torch.empty(d, dtype=torch_dtype(dtype), device=DEV)
+    vs.carrier_mean_pool(e.to(DEV), out, dtype)
+    torch.cuda.synchronize()
+    ref = oracle.mean_pool(to_f64(e))
+    got = out.double().cpu().numpy()
+    if dtype == "f32":
+        assert np.abs(got - ref).max() <= 1e-6
+    else:  # one bf16 rounding of an fp32 mean
+        assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-30)
+
+
+@pytest.mark.parametrize("n_caches", [28, 4096])
+def test_batched_compaction(n_caches):
+    s, T, cap = QW, 6, 5
+    rng = np.random.default_rng(5)
+    lens0 = rng.integers(0, cap, size=n_caches).tolist()
+    ks = torch.zeros((n_caches, cap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+    vsl = torch.zeros_like(ks)
+    kf = draw(41, (n_caches, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
+    vf = draw(42, (n_caches, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
+    lens = lens_array(lens0)
+    ws = torch.empty(max(4 * n_caches, 256), dtype=torch.uint8, device=DEV)
+    rows = vs.carrier_compact_append_batched(vs_shape(s), ks, vsl, lens, kf.to(DEV), vf.to(DEV), workspace=ws)
+    torch.cuda.synchronize()
+    assert rows == lens0 and list(lens) == [n + 1 for n in lens0]
+    want_k, want_v = torch.zeros(ks.shape, dtype=torch.bfloat16), torch.zeros(ks.shape, dtype=torch.bfloat16)
+    for i in range(n_caches):
+        want_k[i, lens0[i]] = kf[i, T - 1]
+        want_v[i, lens0[i]] = vf[i, T - 1]
+    assert same_bits(ks, want_k) and same_bits(vsl, want_v)
