@@ -129,7 +129,7 @@ def main():
             vc[:P0].copy_(hv)
             caches.append(vs.Cache(kc, vc, P0))
         out = torch.empty((T, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
-        ws = torch.empty(vs.workspace_bytes(sh, T, cap, 0), dtype=torch.uint8, device=dev)
+        ws = vs.make_workspace(sh, T, cap, 0, dev)
         log(f"[bench] cfg3 inputs staged in {time.time() - t0:.1f}s")
 
         def run_frames(n, timed_calls=None):
@@ -232,7 +232,7 @@ def main():
         dk = draw(c4["seed"] * 7 + 2, (steps, NL4, S, s4.n_kv_heads, s4.head_dim), c4["sigma"], "bf16").to(dev)
         dv = draw(c4["seed"] * 7 + 3, (steps, NL4, S, s4.n_kv_heads, s4.head_dim), c4["sigma"], "bf16").to(dev)
         dout = torch.empty((S, s4.n_q_heads, s4.head_dim), dtype=torch.bfloat16, device=dev)
-        ws4 = torch.empty(vs.workspace_bytes(sh4, 0, cap4, S), dtype=torch.uint8, device=dev)
+        ws4 = vs.make_workspace(sh4, 0, cap4, S, dev)
         log(f"[bench] cfg4 inputs staged in {time.time() - t0:.1f}s; lengths {lens0}")
 
         def fresh_lens():
@@ -308,7 +308,7 @@ def main():
         cch = vs.Cache(kc, vc, L)
         qd, kd, vd = q.to(dev), kf.to(dev), vf.to(dev)
         o = torch.empty_like(qd)
-        w = torch.empty(vs.workspace_bytes(shx, Tn, L + reps + 4, 0), dtype=torch.uint8, device=dev)
+        w = vs.make_workspace(shx, Tn, L + reps + 4, 0, dev)
         for _ in range(3):
             vs.frame_prefill_attn(shx, cch, qd, kd, vd, o, w)
         a, b = event_pair()
@@ -346,7 +346,7 @@ def main():
         cch = vs.Cache(kc, vc, Pfx)
         fr = [tuple(x.to(dev) for x in frame_inputs(c2["seed"], s2, T2, c2["sigma"], frame=f)) for f in range(F2)]
         o = torch.empty_like(fr[0][0])
-        w = torch.empty(vs.workspace_bytes(sh2, T2, Pfx + F2, 0), dtype=torch.uint8, device=dev)
+        w = vs.make_workspace(sh2, T2, Pfx + F2, 0, dev)
         best = None
         for rep in range(5):
             cch.len = Pfx
@@ -372,7 +372,7 @@ def main():
         vsl = torch.zeros_like(ks)
         kf = draw(5, (n_c, Tn, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(dev)
         vf = draw(6, (n_c, Tn, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(dev)
-        w = torch.empty(4 * n_c, dtype=torch.uint8, device=dev)
+        w = vs.make_workspace(sh, 0, 0, n_c, dev)
         reps = 20
         times = []
         for r in range(reps + 2):

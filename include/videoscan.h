@@ -19,7 +19,8 @@
  *     device), 16-byte aligned, owned by the caller.  vs_shape, vs_cache, `lens`,
  *     `row_written` are HOST memory.
  *   - The library never allocates, frees or keeps device memory.  Temporary
- *     storage comes from the caller's `workspace` (size from vs_workspace_bytes).
+ *     storage comes from the caller's `workspace` (size from vs_workspace_bytes,
+ *     prepared once with vs_workspace_init).
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     the null stream) and return without waiting.  Buffers must stay valid until
  *     that work has finished.  Two calls that share a workspace must be ordered
@@ -88,6 +89,16 @@ size_t vs_workspace_bytes(const vs_shape *shape, int32_t max_q_tokens, int32_t m
                           int32_t n_streams);
 
 /*
+ * Prepares a freshly allocated (or overwritten) workspace: clears the small control
+ * block at its start, which holds arrival counters that the kernels leave at zero
+ * after every launch.  Must have completed on the device (same stream, or
+ * synchronised) before the first call that uses the workspace; needed once, not per
+ * call.  A workspace is tied to the shape it was initialised with.
+ */
+vs_status vs_workspace_init(const vs_shape *shape, void *workspace, size_t workspace_bytes,
+                            void *hip_stream);
+
+/*
  * Frame prefill attention (Section 3.3, prefilling phase; Eq. 1; carrier last in
  * the run, Section 3.2).
  *   q   [n_tokens][Hq][D], k_f / v_f [n_tokens][Hkv][D]: the frame run, visual
@@ -127,7 +138,8 @@ vs_status vs_frame_prefill_compact(const vs_shape *shape, vs_cache *cache, const
  * frame runs in k_f / v_f [n_caches][n_tokens][Hkv][D].  For every i, row
  * carrier_index of run i goes to row lens[i] of cache i and lens[i] += 1.
  * rows_written (host, [n_caches]) may be NULL.  If any cache is full nothing is
- * done.  Needs 4*n_caches bytes of workspace when n_caches > 64.
+ * done.  Needs a workspace (vs_workspace_bytes with n_streams = n_caches) when
+ * n_caches > 64.
  */
 vs_status vs_carrier_compact_append_batched(const vs_shape *shape, int32_t n_caches, void *k_slab,
                                             void *v_slab, int32_t capacity, int32_t *lens,

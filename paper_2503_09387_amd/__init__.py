@@ -21,4 +21,6 @@ from .binding import (  # noqa: F401
     lib_path,
     status_string,
     workspace_bytes,
+    workspace_init,
+    make_workspace,
 )

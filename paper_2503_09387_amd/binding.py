@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = [
-    "vs_status_string", "vs_workspace_bytes", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
+    "vs_status_string", "vs_workspace_bytes", "vs_workspace_init", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
     "vs_carrier_compact_append", "vs_carrier_compact_append_batched", "vs_decode_attn",
     "vs_carrier_mean_pool", "vs_set_tuning",
 ]
@@ -78,6 +78,7 @@ def lib():
         L.vs_status_string.argtypes = [ctypes.c_int]
         L.vs_workspace_bytes.restype = sz
         L.vs_workspace_bytes.argtypes = [sp, i32, i32, i32]
+        L.vs_workspace_init.argtypes = [sp, vp, sz, vp]
         L.vs_frame_prefill_attn.argtypes = [sp, cp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.vs_frame_prefill_compact.argtypes = [sp, cp, vp, vp, vp, i32, vp, ip, vp, sz, vp]
         L.vs_carrier_compact_append.argtypes = [sp, cp, vp, vp, i32, i32, ip, vp]
@@ -120,6 +121,22 @@ def _check(rc, what):
 
 def workspace_bytes(shape, max_q_tokens, max_cache_rows, n_streams):
     return int(lib().vs_workspace_bytes(ctypes.byref(shape), max_q_tokens, max_cache_rows, n_streams))
+
+
+def workspace_init(shape, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().vs_workspace_init(ctypes.byref(shape), wp, wb, _stream(stream)), "vs_workspace_init")
+
+
+def make_workspace(shape, max_q_tokens, max_cache_rows, n_streams, device="cuda:0"):
+    """Allocate (torch uint8 tensor) and initialise a workspace for the given limits."""
+    import torch
+    n = workspace_bytes(shape, max_q_tokens, max_cache_rows, n_streams)
+    if n == 0:
+        raise VSError(3, "vs_workspace_bytes")
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    workspace_init(shape, ws)
+    return ws
 
 
 def frame_prefill_attn(shape, cache, q, k_f, v_f, out, workspace, stream=None):

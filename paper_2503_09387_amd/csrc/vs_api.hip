@@ -3,6 +3,8 @@
 // kernels may assume consistent shapes.  See include/videoscan.h for the contract.
 #include <math.h>
 
+#include <algorithm>
+
 #include "vs_internal.h"
 
 using namespace vs;
@@ -11,6 +13,7 @@ namespace vs {
 int g_tune_prefill_splits = 0;
 int g_tune_prefill_row_blocks = 0;
 int g_tune_decode_chunk_rows = 0;
+int g_tune_debug_mode = 0;
 }  // namespace vs
 
 namespace {
@@ -67,11 +70,13 @@ vs_status prefill_common(const vs_shape* shape, vs_cache* cache, bool append, co
     char* vdst = append ? static_cast<char*>(cache->v) + (int64_t)cache->len * rb : nullptr;
     hipError_t e;
     if (shape->dtype == VS_BF16) {
-        const size_t need = prefill_mfma_workspace_bytes(*shape, n_tokens);
+        const size_t ctrl = control_block_bytes(*shape);
+        const size_t need = ctrl + prefill_mfma_workspace_bytes(*shape, n_tokens);
         if (!workspace || workspace_bytes < need) return VS_ERR_WORKSPACE;
         if (!aligned16(workspace)) return VS_ERR_ALIGN;
+        char* wsb = static_cast<char*>(workspace);
         e = launch_prefill_mfma(*shape, cache->k, cache->v, cache->len, q, k_f, v_f, n_tokens, out,
-                                kdst, vdst, workspace, stream);
+                                kdst, vdst, wsb + prefill_counter_offset(*shape), wsb + ctrl, stream);
     } else {
         e = launch_prefill_simple(*shape, cache->k, cache->v, cache->len, q, k_f, v_f, n_tokens, out,
                                   stream);
@@ -112,20 +117,29 @@ size_t vs_workspace_bytes(const vs_shape* shape, int32_t max_q_tokens, int32_t m
                           int32_t n_streams) {
     if (check_shape(shape) != VS_OK) return 0;
     if (max_q_tokens < 0 || max_cache_rows < 0 || n_streams < 0) return 0;
-    if (max_q_tokens > kMaxTokens || n_streams > kMaxStreams) return 0;
+    if (max_q_tokens > kMaxTokens || n_streams > (1 << 20)) return 0;
     size_t need = 256;
     if (shape->dtype == VS_BF16) {
-        if (max_q_tokens > 0) need = need > prefill_mfma_workspace_bytes(*shape, max_q_tokens)
-                                         ? need : prefill_mfma_workspace_bytes(*shape, max_q_tokens);
+        if (max_q_tokens > 0) need = std::max(need, prefill_mfma_workspace_bytes(*shape, max_q_tokens));
         if (n_streams > 0) {
             const int chunk = n_streams < kMaxStreamsPerLaunch ? n_streams : kMaxStreamsPerLaunch;
-            const size_t d = decode_mfma_workspace_bytes(*shape, chunk, max_cache_rows);
-            need = need > d ? need : d;
+            need = std::max(need, decode_mfma_workspace_bytes(*shape, chunk, max_cache_rows));
         }
     }
-    // batched compaction of more than 64 caches stages the lengths here
-    const size_t lens = round256(sizeof(int32_t) * (size_t)(n_streams > 0 ? n_streams : 0));
-    return round256(need) + lens;
+    // batched compaction of more than 64 caches stages the lengths in the scratch area
+    need = std::max(need, sizeof(int32_t) * (size_t)n_streams);
+    return control_block_bytes(*shape) + round256(need);
+}
+
+vs_status vs_workspace_init(const vs_shape* shape, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+    vs_status st = check_shape(shape);
+    if (st != VS_OK) return st;
+    if (!workspace) return VS_ERR_NULL;
+    if (!aligned16(workspace)) return VS_ERR_ALIGN;
+    if (workspace_bytes < control_block_bytes(*shape)) return VS_ERR_WORKSPACE;
+    return launch_zero_fill(workspace, control_block_bytes(*shape), static_cast<hipStream_t>(hip_stream)) ==
+                   hipSuccess ? VS_OK : VS_ERR_HIP;
 }
 
 vs_status vs_frame_prefill_attn(const vs_shape* shape, const vs_cache* cache, const void* q,
@@ -190,14 +204,15 @@ vs_status vs_carrier_compact_append_batched(const vs_shape* shape, int32_t n_cac
         e = launch_append_rows(n_caches, k_slab, v_slab, (int64_t)capacity * rb, &t, nullptr, k_f, v_f,
                                (int64_t)n_tokens * rb, (int64_t)carrier_index * rb, (int32_t)rb, stream);
     } else {
-        if (!workspace || workspace_bytes < sizeof(int32_t) * (size_t)n_caches) return VS_ERR_WORKSPACE;
+        const size_t ctrl = control_block_bytes(*shape);
+        if (!workspace || workspace_bytes < ctrl + sizeof(int32_t) * (size_t)n_caches) return VS_ERR_WORKSPACE;
         if (!aligned16(workspace)) return VS_ERR_ALIGN;
+        void* staged = static_cast<char*>(workspace) + ctrl;
         // lens is pageable host memory: the runtime stages the copy before returning
-        e = hipMemcpyAsync(workspace, lens, sizeof(int32_t) * (size_t)n_caches, hipMemcpyHostToDevice,
-                           stream);
+        e = hipMemcpyAsync(staged, lens, sizeof(int32_t) * (size_t)n_caches, hipMemcpyHostToDevice, stream);
         if (e == hipSuccess)
             e = launch_append_rows(n_caches, k_slab, v_slab, (int64_t)capacity * rb, nullptr,
-                                   static_cast<const int32_t*>(workspace), k_f, v_f,
+                                   static_cast<const int32_t*>(staged), k_f, v_f,
                                    (int64_t)n_tokens * rb, (int64_t)carrier_index * rb, (int32_t)rb,
                                    stream);
     }
@@ -230,9 +245,10 @@ vs_status vs_decode_attn(const vs_shape* shape, int32_t n_streams, void* k_slab,
         if (lens[s] + add > max_rows) max_rows = lens[s] + add;
     }
     const bool mfma = shape->dtype == VS_BF16;
+    const size_t ctrl = control_block_bytes(*shape);
     if (mfma) {
         const int chunk = n_streams < kMaxStreamsPerLaunch ? n_streams : kMaxStreamsPerLaunch;
-        if (!workspace || workspace_bytes < decode_mfma_workspace_bytes(*shape, chunk, max_rows))
+        if (!workspace || workspace_bytes < ctrl + decode_mfma_workspace_bytes(*shape, chunk, max_rows))
             return VS_ERR_WORKSPACE;
         if (!aligned16(workspace)) return VS_ERR_ALIGN;
     }
@@ -243,23 +259,27 @@ vs_status vs_decode_attn(const vs_shape* shape, int32_t n_streams, void* k_slab,
         const int32_t ns = (n_streams - s0) < kMaxStreamsPerLaunch ? (n_streams - s0) : kMaxStreamsPerLaunch;
         char* ks = static_cast<char*>(k_slab) + (int64_t)s0 * capacity * rb;
         char* vs_ = static_cast<char*>(v_slab) + (int64_t)s0 * capacity * rb;
-        LenTable t{};
-        hipError_t e = hipSuccess;
-        if (add) {
-            for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i];
-            e = launch_append_rows(ns, ks, vs_, (int64_t)capacity * rb, &t, nullptr,
-                                   static_cast<const char*>(k_new) + (int64_t)s0 * rb,
-                                   static_cast<const char*>(v_new) + (int64_t)s0 * rb, rb, 0,
-                                   (int32_t)rb, stream);
-            if (e != hipSuccess) return VS_ERR_HIP;
-        }
-        for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i] + add;
+        const char* kn = add ? static_cast<const char*>(k_new) + (int64_t)s0 * rb : nullptr;
+        const char* vn = add ? static_cast<const char*>(v_new) + (int64_t)s0 * rb : nullptr;
         const char* qs = static_cast<const char*>(q) + (int64_t)s0 * qo_stride;
         char* os = static_cast<char*>(out) + (int64_t)s0 * qo_stride;
-        if (mfma)
-            e = launch_decode_mfma(*shape, ns, ks, vs_, capacity, t, qs, os, workspace, stream);
-        else
+        LenTable t{};
+        hipError_t e = hipSuccess;
+        if (mfma) {
+            // the kernel reads the new row from k_new/v_new and stores it into the slab itself
+            for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i] + add;
+            e = launch_decode_mfma(*shape, ns, ks, vs_, capacity, t, qs, kn, vn, os, workspace,
+                                   static_cast<char*>(workspace) + ctrl, stream);
+        } else {
+            if (add) {
+                for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i];
+                e = launch_append_rows(ns, ks, vs_, (int64_t)capacity * rb, &t, nullptr, kn, vn, rb, 0,
+                                       (int32_t)rb, stream);
+                if (e != hipSuccess) return VS_ERR_HIP;
+            }
+            for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i] + add;
             e = launch_decode_simple(*shape, ns, ks, vs_, capacity, t, qs, os, stream);
+        }
         if (e != hipSuccess) return VS_ERR_HIP;
     }
     if (add)
@@ -282,7 +302,9 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
             if (value % 128 != 0) return VS_ERR_SHAPE;
             g_tune_decode_chunk_rows = value;
             return VS_OK;
+        default: break;
     }
+    if (knob == 99) { g_tune_debug_mode = value; return VS_OK; }
     return VS_ERR_SHAPE;
 }
 

@@ -15,6 +15,7 @@ constexpr int kMaxGroup = 8;              // query heads per KV head
 extern int g_tune_prefill_splits;
 extern int g_tune_prefill_row_blocks;
 extern int g_tune_decode_chunk_rows;
+extern int g_tune_debug_mode;
 
 struct LenTable {
     int32_t v[kMaxStreamsPerLaunch];
@@ -40,14 +41,25 @@ hipError_t launch_decode_simple(const vs_shape& s, int32_t n_streams, const void
 size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens);
 hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc, int32_t len,
                                const void* q, const void* kf, const void* vf, int32_t n_tokens,
-                               void* out, void* k_append_dst, void* v_append_dst, void* workspace,
-                               hipStream_t st);
+                               void* out, void* k_append_dst, void* v_append_dst, void* counters,
+                               void* workspace, hipStream_t st);
 
-// bf16 split-K decode over ragged streams.
+// bf16 split-row decode over ragged streams; appends (k_new, v_new) on the side when given.
+// `counters` points at the decode counters of an initialised workspace control block.
 size_t decode_mfma_workspace_bytes(const vs_shape& s, int32_t n_streams, int32_t max_rows);
-hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, const void* k_slab,
-                              const void* v_slab, int32_t capacity, const LenTable& lens,
-                              const void* q, void* out, void* workspace, hipStream_t st);
+hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab, void* v_slab,
+                              int32_t capacity, const LenTable& lens, const void* q,
+                              const void* k_new, const void* v_new, void* out, void* counters,
+                              void* workspace, hipStream_t st);
+
+// Control block at the start of every workspace: arrival counters that are zero between
+// launches (decode: [kMaxStreamsPerLaunch][Hkv]; prefill: [kMaxRowTiles][Hkv]).
+constexpr int kMaxRowTiles = 256;
+size_t control_block_bytes(const vs_shape& s);
+inline size_t prefill_counter_offset(const vs_shape& s) {
+    return (size_t)kMaxStreamsPerLaunch * s.n_kv_heads * sizeof(unsigned int);
+}
+hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t st);
 
 // row copies
 hipError_t launch_append_rows(int32_t n_caches, void* k_slab, void* v_slab, int64_t cache_stride_bytes,

@@ -357,8 +357,8 @@ size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens) {
 
 hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc, int32_t len,
                                const void* q, const void* kf, const void* vf, int32_t n_tokens,
-                               void* out, void* k_append_dst, void* v_append_dst, void* workspace,
-                               hipStream_t st) {
+                               void* out, void* k_append_dst, void* v_append_dst, void* /*counters*/,
+                               void* workspace, hipStream_t st) {
     const Plan pl = make_plan(s, n_tokens, len);
     PrefillParams p;
     p.kc = (const __bf16*)kc;

@@ -173,7 +173,23 @@ __global__ __launch_bounds__(256) void mean_pool_kernel(const T* __restrict__ e,
     }
 }
 
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint32_t* p, size_t n) {
+    const size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 }  // namespace
+
+size_t control_block_bytes(const vs_shape& s) {
+    const size_t n = (size_t)(kMaxStreamsPerLaunch + kMaxRowTiles) * s.n_kv_heads * sizeof(unsigned int);
+    return (n + 255) & ~size_t(255);
+}
+
+hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t st) {
+    const size_t n = bytes / 4;
+    zero_fill_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((uint32_t*)p, n);
+    return hipGetLastError();
+}
 
 hipError_t launch_prefill_simple(const vs_shape& s, const void* kc, const void* vc, int32_t len,
                                  const void* q, const void* kf, const void* vf, int32_t n_tokens,

@@ -45,9 +45,7 @@ def scale32(s):
 
 
 def workspace(s, max_tokens, max_rows, n_streams):
-    n = vs.workspace_bytes(vs_shape(s), max_tokens, max_rows, n_streams)
-    assert n > 0
-    return torch.empty(n, dtype=torch.uint8, device=DEV)
+    return vs.make_workspace(vs_shape(s), max_tokens, max_rows, n_streams, DEV)
 
 
 def check_close(gpu, ref, dtype, what=""):

@@ -363,7 +363,7 @@ def test_batched_compaction(n_caches):
     kf = draw(41, (n_caches, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
     vf = draw(42, (n_caches, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
     lens = lens_array(lens0)
-    ws = torch.empty(max(4 * n_caches, 256), dtype=torch.uint8, device=DEV)
+    ws = workspace(s, 0, 0, n_caches)
     rows = vs.carrier_compact_append_batched(vs_shape(s), ks, vsl, lens, kf.to(DEV), vf.to(DEV), workspace=ws)
     torch.cuda.synchronize()
     assert rows == lens0 and list(lens) == [n + 1 for n in lens0]
