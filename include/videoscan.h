@@ -175,12 +175,12 @@ vs_status vs_carrier_mean_pool(const void *e, int32_t n, int32_t d, int32_t dtyp
  * depend on how the keys were split.  Process-wide, not thread-safe; value 0 restores
  * the library's own choice.  Unknown knobs or out-of-range values: VS_ERR_SHAPE.
  *   VS_TUNE_PREFILL_SPLITS    workgroups sharing one row tile's keys, 1..32
- *   VS_TUNE_PREFILL_ROW_BLOCKS 32-row blocks per wavefront in prefill, 1 or 2
+ *   VS_TUNE_PREFILL_KV_GROUPS  key groups (sets of 4 wavefronts) per prefill workgroup, 1 or 2
  *   VS_TUNE_DECODE_CHUNK_ROWS rows per decode workgroup, a multiple of 128
  */
 typedef enum {
     VS_TUNE_PREFILL_SPLITS = 0,
-    VS_TUNE_PREFILL_ROW_BLOCKS = 1,
+    VS_TUNE_PREFILL_KV_GROUPS = 1,
     VS_TUNE_DECODE_CHUNK_ROWS = 2
 } vs_tune_knob;
 vs_status vs_set_tuning(int32_t knob, int32_t value);

@@ -16,7 +16,7 @@ from .binding import (  # noqa: F401
     lib,
     set_tuning,
     TUNE_PREFILL_SPLITS,
-    TUNE_PREFILL_ROW_BLOCKS,
+    TUNE_PREFILL_KV_GROUPS,
     TUNE_DECODE_CHUNK_ROWS,
     lib_path,
     status_string,

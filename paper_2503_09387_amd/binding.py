@@ -193,7 +193,7 @@ def carrier_mean_pool(e, c_out, dtype, stream=None):
            "vs_carrier_mean_pool")
 
 
-TUNE_PREFILL_SPLITS, TUNE_PREFILL_ROW_BLOCKS, TUNE_DECODE_CHUNK_ROWS = 0, 1, 2
+TUNE_PREFILL_SPLITS, TUNE_PREFILL_KV_GROUPS, TUNE_DECODE_CHUNK_ROWS = 0, 1, 2
 
 
 def set_tuning(knob, value):

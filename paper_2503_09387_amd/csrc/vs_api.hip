@@ -11,7 +11,7 @@ using namespace vs;
 
 namespace vs {
 int g_tune_prefill_splits = 0;
-int g_tune_prefill_row_blocks = 0;
+int g_tune_prefill_kv_groups = 0;
 int g_tune_decode_chunk_rows = 0;
 int g_tune_debug_mode = 0;
 }  // namespace vs
@@ -294,9 +294,9 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
             if (value > kMaxPrefillSplits) return VS_ERR_SHAPE;
             g_tune_prefill_splits = value;
             return VS_OK;
-        case VS_TUNE_PREFILL_ROW_BLOCKS:
+        case VS_TUNE_PREFILL_KV_GROUPS:
             if (value > 2) return VS_ERR_SHAPE;
-            g_tune_prefill_row_blocks = value;
+            g_tune_prefill_kv_groups = value;
             return VS_OK;
         case VS_TUNE_DECODE_CHUNK_ROWS:
             if (value % 128 != 0) return VS_ERR_SHAPE;

@@ -13,7 +13,7 @@ constexpr int kMaxGroup = 8;              // query heads per KV head
 
 // launch-plan overrides (0 = automatic), set through vs_set_tuning
 extern int g_tune_prefill_splits;
-extern int g_tune_prefill_row_blocks;
+extern int g_tune_prefill_kv_groups;
 extern int g_tune_decode_chunk_rows;
 extern int g_tune_debug_mode;
 

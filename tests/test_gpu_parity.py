@@ -223,19 +223,19 @@ def test_prefill_other_head_groupings(hq, hkv):
     check_close(out, oracle_prefill_rows(s, q, hk, hv, L, kf, vf), "bf16", f"Hq={hq} Hkv={hkv}")
 
 
-@pytest.mark.parametrize("row_blocks", [1, 2])
-def test_prefill_result_does_not_depend_on_the_split(row_blocks):
+@pytest.mark.parametrize("kv_groups", [1, 2])
+def test_prefill_result_does_not_depend_on_the_split(kv_groups):
     s = QW
     L, T = 1500, 170
     hk, hv = cache_rows(13, s, L, 0.5)
     q, kf, vf = frame_inputs(13, s, T, 0.5, q_gain=4)
     ref = oracle_prefill_rows(s, q, hk, hv, L, kf, vf)
-    vs.set_tuning(vs.TUNE_PREFILL_ROW_BLOCKS, row_blocks)
+    vs.set_tuning(vs.TUNE_PREFILL_KV_GROUPS, kv_groups)
     outs = []
     for splits in (1, 2, 5, 12, 32):
         vs.set_tuning(vs.TUNE_PREFILL_SPLITS, splits)
         out, _, _ = run_prefill(s, hk, hv, L, q, kf, vf)
-        check_close(out, ref, "bf16", f"splits={splits} row_blocks={row_blocks}")
+        check_close(out, ref, "bf16", f"splits={splits} kv_groups={kv_groups}")
         outs.append(out.float())
     for o in outs[1:]:
         assert (o - outs[0]).abs().max().item() <= 2 ** -7 * outs[0].abs().max().item()
