@@ -26,6 +26,16 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+SLEEP_CYCLES = 20_000_000   # ~10 ms spin kernel that lets the host queue a batch of launches behind it
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark's
+# kernels (profiles/*.md), scaled by what the same counters read for a plain 1 GiB copy
+# (FETCH_SIZE x2.0, WRITE_SIZE x1.0).  Static because counters cannot be read inside a timed run.
+TRAFFIC = {
+    "prefill_mfma_kernel": None,
+    "decode_mfma_kernel": {"fetch_bytes": 159.2e6, "write_bytes": 4.56e6,
+                           "note": "cfg4 launch shape, algorithmic 159.4e6 bytes"},
+}
 
 
 def log(*a):
@@ -132,20 +142,28 @@ def main():
         ws = vs.make_workspace(sh, T, cap, 0, dev)
         log(f"[bench] cfg3 inputs staged in {time.time() - t0:.1f}s")
 
+        st = vs.current_stream_handle()
+        frames_in = [[(qp[f, l], kp[f, l], vp[f, l]) for l in range(NL)] for f in range(POOL_FRAMES)]
+
         def run_frames(n, timed_calls=None):
             for f in range(n):
-                vs.carrier_mean_pool(ep[f % POOL_FRAMES], carrier_emb, "bf16")
+                fin = frames_in[f % POOL_FRAMES]
+                timed = timed_calls is not None and (f % 8 == 0)
+                if timed:
+                    # keep the GPU busy while this frame's launches and events are queued, so that
+                    # the events bracket kernel execution and not the host's launch latency
+                    torch.cuda._sleep(SLEEP_CYCLES)
+                vs.carrier_mean_pool(ep[f % POOL_FRAMES], carrier_emb, "bf16", stream=st)
                 for l in range(NL):
-                    if timed_calls is not None and (f % 8 == 0):
+                    q_, k_, v_ = fin[l]
+                    if timed:
                         a, b = event_pair()
                         a.record()
-                        vs.frame_prefill_compact(sh, caches[l], qp[f % POOL_FRAMES, l], kp[f % POOL_FRAMES, l],
-                                                 vp[f % POOL_FRAMES, l], out, ws)
+                        vs.frame_prefill_compact(sh, caches[l], q_, k_, v_, out, ws, stream=st)
                         b.record()
                         timed_calls.append((a, b, caches[l].len - 1))
                     else:
-                        vs.frame_prefill_compact(sh, caches[l], qp[f % POOL_FRAMES, l], kp[f % POOL_FRAMES, l],
-                                                 vp[f % POOL_FRAMES, l], out, ws)
+                        vs.frame_prefill_compact(sh, caches[l], q_, k_, v_, out, ws, stream=st)
 
         def reset():
             for cch in caches:
@@ -164,11 +182,20 @@ def main():
         wall = time.perf_counter() - t0
         gpu_ms = ev0.elapsed_time(ev1)
         assert all(cch.len == P0 + K for cch in caches)
-        # second pass: HIP events around every prefill launch of every 8th frame
+        # second and third pass: HIP events (on the launch stream) around every call of every 8th
+        # frame; first the whole call, then with the split-merge kernel switched off so that the
+        # events bracket the attention kernel alone (what rocprofv3 reports per kernel)
         reset()
         calls = []
         run_frames(K, calls)
         torch.cuda.synchronize()
+        call_durs = np.array([a.elapsed_time(b) * 1e-3 for a, b, _ in calls])
+        vs.set_tuning(vs.TUNE_SKIP_MERGE, 1)
+        reset()
+        calls = []
+        run_frames(K, calls)
+        torch.cuda.synchronize()
+        vs.set_tuning(vs.TUNE_SKIP_MERGE, 0)
         durs = np.array([a.elapsed_time(b) * 1e-3 for a, b, _ in calls])
         fl = np.array([prefill_flops(s, L, T) for _, _, L in calls], dtype=np.float64)
         by = np.array([prefill_bytes(s, L, T) for _, _, L in calls], dtype=np.float64)
@@ -176,20 +203,24 @@ def main():
         stream_out = dict(
             value=K / wall, ms_per_step=wall * 1e3 / K, gpu_ms_per_step=gpu_ms / K,
             roofline=dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                          frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
-                          kernel="prefill_mfma_kernel (+ split merge), per vs_frame_prefill_compact call",
+                          frac=achieved / PEAK_BF16_TFLOPS,
+                          traffic=TRAFFIC.get("prefill_mfma_kernel"),
+                          kernel="prefill_mfma_kernel<2> (attention + fused carrier compaction), timed alone",
                           avg_launch_us=float(durs.mean() * 1e6), launches_timed=len(calls),
+                          whole_call_us=float(call_durs.mean() * 1e6),
+                          whole_call_tflops=float(fl.sum() / call_durs.sum() / 1e12),
                           algorithmic_gflop_per_launch=float(fl.mean() / 1e9),
                           algorithmic_mbytes_per_launch=float(by.mean() / 1e6)))
-        log(f"[bench] cfg3: {K / wall:.1f} frames/s, {wall * 1e3 / K:.3f} ms/frame, prefill launch "
-            f"{durs.mean() * 1e6:.1f} us, {achieved:.1f} TFLOP/s ({100 * achieved / PEAK_BF16_TFLOPS:.1f}% of bf16 peak)")
+        log(f"[bench] cfg3: {K / wall:.1f} frames/s, {wall * 1e3 / K:.3f} ms/frame; attention kernel "
+            f"{durs.mean() * 1e6:.1f} us = {achieved:.1f} TFLOP/s ({100 * achieved / PEAK_BF16_TFLOPS:.1f}% of bf16 "
+            f"peak); whole call {call_durs.mean() * 1e6:.1f} us")
         del qp, kp, vp
 
     # ------------------------------------------------------------------ CPU baseline (oracle)
     cpu = None
     if "cpu" in parts:
         import oracle
-        sample = [(0, 0), (127, 13), (255, 27)]
+        sample = [(f, l) for f in (0, 127, 255) for l in range(0, NL, 2)]  # 42 frame-layers
         t_tot = 0.0
         for f, l in sample:
             L = P0 + f
@@ -201,8 +232,9 @@ def main():
             t_tot += time.perf_counter() - t0
         per_layer = t_tot / len(sample)
         cpu = dict(value=1.0 / (per_layer * NL), unit="frames/s", cores=oracle.num_threads(), kind="oracle",
-                   sample=f"prefill of (frame, layer) in {sample} of cfg3, {t_tot:.1f}s of CPU work; frames/s "
-                          f"extrapolated as 1/(28 x mean per-layer time); fp64, OpenMP",
+                   sample=f"prefill of frames 0/127/255 x even layers of cfg3 ({len(sample)} frame-layers, "
+                          f"{t_tot:.1f}s of CPU work); frames/s extrapolated as 1/(28 x mean per-layer time); "
+                          f"fp64, OpenMP",
                    affinity_cores=len(os.sched_getaffinity(0)))
         log(f"[bench] oracle: {per_layer:.2f} s per frame-layer on {cpu['cores']} threads")
 
@@ -238,17 +270,24 @@ def main():
         def fresh_lens():
             return [(ctypes.c_int32 * S)(*lens0) for _ in range(NL4)]
 
+        st4 = vs.current_stream_handle()
+        steps_in = [[(dq[t, l], dk[t, l], dv[t, l]) for l in range(NL4)] for t in range(steps)]
+
         def run_decode(n, lens, timed_calls=None):
             for t in range(n):
+                timed = timed_calls is not None and (t % 4 == 0)
+                if timed:
+                    torch.cuda._sleep(SLEEP_CYCLES)
                 for l in range(NL4):
-                    if timed_calls is not None and (t % 4 == 0):
+                    q_, k_, v_ = steps_in[t][l]
+                    if timed:
                         a, b = event_pair()
                         a.record()
-                        vs.decode_attn(sh4, slabs[l][0], slabs[l][1], lens[l], dq[t, l], dk[t, l], dv[t, l], dout, ws4)
+                        vs.decode_attn(sh4, slabs[l][0], slabs[l][1], lens[l], q_, k_, v_, dout, ws4, stream=st4)
                         b.record()
                         timed_calls.append((a, b, list(lens[l])))
                     else:
-                        vs.decode_attn(sh4, slabs[l][0], slabs[l][1], lens[l], dq[t, l], dk[t, l], dv[t, l], dout, ws4)
+                        vs.decode_attn(sh4, slabs[l][0], slabs[l][1], lens[l], q_, k_, v_, dout, ws4, stream=st4)
 
         run_decode(min(4, steps), fresh_lens())
         torch.cuda.synchronize()
@@ -261,6 +300,13 @@ def main():
         calls = []
         run_decode(steps, fresh_lens(), calls)
         torch.cuda.synchronize()
+        call_durs = np.array([a.elapsed_time(b) * 1e-3 for a, b, _ in calls])
+        # restore the slabs' appended rows do not matter for timing; time the attention kernel alone
+        vs.set_tuning(vs.TUNE_SKIP_MERGE, 1)
+        calls = []
+        run_decode(steps, fresh_lens(), calls)
+        torch.cuda.synchronize()
+        vs.set_tuning(vs.TUNE_SKIP_MERGE, 0)
         durs = np.array([a.elapsed_time(b) * 1e-3 for a, b, _ in calls])
         by = np.array([decode_bytes(s4, la) for _, _, la in calls], dtype=np.float64)
         gbs = float(by.sum() / durs.sum() / 1e9)
@@ -270,28 +316,34 @@ def main():
             config={"workload": "cfg4: 16 streams, retained rows U[512,8192]+128, 28 layers, bf16 GQA 28/4, D=128; "
                                 "4 distinct layer slabs drawn on the host, copied to the 28 layers"},
             roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS,
-                          traffic=None, kernel="append_rows + decode_mfma_kernel + decode_combine, per vs_decode_attn call",
+                          traffic=TRAFFIC.get("decode_mfma_kernel"),
+                          kernel="decode_mfma_kernel (attention + fused append of the new row), timed alone",
                           avg_launch_us=float(durs.mean() * 1e6), launches_timed=len(calls),
+                          whole_call_us=float(call_durs.mean() * 1e6),
+                          whole_call_gbs=float(by.sum() / call_durs.sum() / 1e9),
                           algorithmic_mbytes_per_launch=float(by.mean() / 1e6)))
-        log(f"[bench] cfg4: {S * steps / wall:.0f} tok/s, {wall * 1e3 / steps:.3f} ms/step, layer launch "
-            f"{durs.mean() * 1e6:.1f} us, {gbs:.0f} GB/s ({100 * gbs / PEAK_HBM_GBS:.1f}% of HBM peak)")
+        log(f"[bench] cfg4: {S * steps / wall:.0f} tok/s, {wall * 1e3 / steps:.3f} ms/step; attention kernel "
+            f"{durs.mean() * 1e6:.1f} us = {gbs:.0f} GB/s ({100 * gbs / PEAK_HBM_GBS:.1f}% of HBM peak); whole call "
+            f"{call_durs.mean() * 1e6:.1f} us")
         if "cpu" in parts:
             import oracle
             t_tot = 0.0
-            for l in (0, 1):
+            n_l, n_t = 4, 8
+            for l in range(n_l):
                 for i in range(S):
                     n = lens0[i]
                     ok = np.zeros((n + 1, s4.n_kv_heads, s4.head_dim))
                     ov = np.zeros_like(ok)
                     ok[:n], ov[:n] = to_f64(slabs[l][0][i, :n].cpu()), to_f64(slabs[l][1][i, :n].cpu())
-                    q1, k1, v1 = to_f64(dq[0, l, i].cpu()), to_f64(dk[0, l, i].cpu()), to_f64(dv[0, l, i].cpu())
-                    t0 = time.perf_counter()
-                    oracle.decode(q1, ok, ov, n, k1, v1, float(np.float32(s4.scale)))
-                    t_tot += time.perf_counter() - t0
-            per_step = t_tot / 2 * NL4
+                    for t in range(n_t):
+                        q1, k1, v1 = to_f64(dq[t, l, i].cpu()), to_f64(dk[t, l, i].cpu()), to_f64(dv[t, l, i].cpu())
+                        t0 = time.perf_counter()
+                        oracle.decode(q1, ok, ov, n, k1, v1, float(np.float32(s4.scale)))
+                        t_tot += time.perf_counter() - t0
+            per_step = t_tot / (n_l * n_t) * NL4
             decode_out["cpu_baseline"] = dict(value=S / per_step, unit="tok/s", cores=oracle.num_threads(), kind="oracle",
-                                              sample=f"step 0 of layers 0 and 1, all 16 streams, {t_tot:.1f}s; "
-                                                     f"extrapolated to 28 layers")
+                                              sample=f"{n_t} steps of {n_l} layers, all 16 streams at their initial "
+                                                     f"lengths, {t_tot:.1f}s of CPU work; extrapolated to 28 layers")
         del slabs, base, dq, dk, dv
 
     # ------------------------------------------------------------------ cfg2 / cfg5 / compaction extras

@@ -177,11 +177,15 @@ vs_status vs_carrier_mean_pool(const void *e, int32_t n, int32_t d, int32_t dtyp
  *   VS_TUNE_PREFILL_SPLITS    workgroups sharing one row tile's keys, 1..32
  *   VS_TUNE_PREFILL_KV_GROUPS  key groups (sets of 4 wavefronts) per prefill workgroup, 1 or 2
  *   VS_TUNE_DECODE_CHUNK_ROWS rows per decode workgroup, a multiple of 128
+ *   VS_TUNE_SKIP_MERGE        1 = do not launch the kernels that merge split results, so that
+ *                             the attention kernels can be timed alone; outputs of calls whose
+ *                             keys were split are then NOT written.  Measurement only.
  */
 typedef enum {
     VS_TUNE_PREFILL_SPLITS = 0,
     VS_TUNE_PREFILL_KV_GROUPS = 1,
-    VS_TUNE_DECODE_CHUNK_ROWS = 2
+    VS_TUNE_DECODE_CHUNK_ROWS = 2,
+    VS_TUNE_SKIP_MERGE = 3
 } vs_tune_knob;
 vs_status vs_set_tuning(int32_t knob, int32_t value);
 

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     carrier_compact_append,
     carrier_compact_append_batched,
     carrier_mean_pool,
+    current_stream_handle,
     decode_attn,
     frame_prefill_attn,
     frame_prefill_compact,
@@ -18,6 +19,7 @@ from .binding import (  # noqa: F401
     TUNE_PREFILL_SPLITS,
     TUNE_PREFILL_KV_GROUPS,
     TUNE_DECODE_CHUNK_ROWS,
+    TUNE_SKIP_MERGE,
     lib_path,
     status_string,
     workspace_bytes,

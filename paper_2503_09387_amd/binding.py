@@ -102,10 +102,19 @@ def _ptr(t):
 
 
 def _stream(stream):
-    if stream is not None:
-        return ctypes.c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
+    """hipStream_t for the call: an int handle, a torch stream, or None = torch's current stream."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    elif not isinstance(stream, int):
+        stream = stream.cuda_stream
+    return ctypes.c_void_p(stream)
+
+
+def current_stream_handle():
+    """The raw handle of torch's current stream; pass it as `stream=` to skip the lookup per call."""
     import torch
-    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return int(torch.cuda.current_stream().cuda_stream)
 
 
 def _ws(workspace):
@@ -193,7 +202,7 @@ def carrier_mean_pool(e, c_out, dtype, stream=None):
            "vs_carrier_mean_pool")
 
 
-TUNE_PREFILL_SPLITS, TUNE_PREFILL_KV_GROUPS, TUNE_DECODE_CHUNK_ROWS = 0, 1, 2
+TUNE_PREFILL_SPLITS, TUNE_PREFILL_KV_GROUPS, TUNE_DECODE_CHUNK_ROWS, TUNE_SKIP_MERGE = 0, 1, 2, 3
 
 
 def set_tuning(knob, value):

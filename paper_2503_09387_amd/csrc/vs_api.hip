@@ -14,6 +14,7 @@ int g_tune_prefill_splits = 0;
 int g_tune_prefill_kv_groups = 0;
 int g_tune_decode_chunk_rows = 0;
 int g_tune_debug_mode = 0;
+int g_tune_skip_merge = 0;
 }  // namespace vs
 
 namespace {
@@ -301,6 +302,10 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
         case VS_TUNE_DECODE_CHUNK_ROWS:
             if (value % 128 != 0) return VS_ERR_SHAPE;
             g_tune_decode_chunk_rows = value;
+            return VS_OK;
+        case VS_TUNE_SKIP_MERGE:
+            if (value > 1) return VS_ERR_SHAPE;
+            g_tune_skip_merge = value;
             return VS_OK;
         default: break;
     }

@@ -389,7 +389,7 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     else if (g_tune_debug_mode == 3) decode_mfma_kernel<0, 1><<<grid, kThreads, 0, st>>>(p);
     else decode_mfma_kernel<0, 2><<<grid, kThreads, 0, st>>>(p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.max_chunks == 1) return e;
+    if (e != hipSuccess || p.max_chunks == 1 || g_tune_skip_merge) return e;
     decode_combine_kernel<<<dim3(n_streams, s.n_q_heads), D, 0, st>>>(p);
     return hipGetLastError();
 }

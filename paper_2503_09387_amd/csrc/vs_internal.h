@@ -16,6 +16,7 @@ extern int g_tune_prefill_splits;
 extern int g_tune_prefill_kv_groups;
 extern int g_tune_decode_chunk_rows;
 extern int g_tune_debug_mode;
+extern int g_tune_skip_merge;
 
 struct LenTable {
     int32_t v[kMaxStreamsPerLaunch];

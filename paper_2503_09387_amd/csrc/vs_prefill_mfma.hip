@@ -489,7 +489,7 @@ hipError_t launch_kvg(const PrefillParams& p, const Plan& pl, int n_kv_heads, hi
     const int grid = pl.n_row_tiles * pl.nsplit * n_kv_heads;
     prefill_mfma_kernel<KVG><<<grid, kGroupThreads * KVG, kLds, st>>>(p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.nsplit == 1) return e;
+    if (e != hipSuccess || pl.nsplit == 1 || g_tune_skip_merge) return e;
     prefill_combine_kernel<<<dim3(pl.n_row_tiles * 4 * 4 * 2, n_kv_heads), 64, 0, st>>>(p);
     return hipGetLastError();
 }

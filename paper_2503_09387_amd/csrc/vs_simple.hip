@@ -139,19 +139,33 @@ __global__ __launch_bounds__(64) void append_rows_kernel(
 }
 
 // ---- mean pool ---------------------------------------------------------------
-// Block: 64 column chunks x 4 row groups.  Row group r sums rows r, r+4, ... in order in
-// fp32; the four partial sums are added in order 0..3; one rounding at the end.
+// Block: 16 column chunks (of VEC columns) x 16 row groups, so that a frame's rows are read
+// with many loads in flight.  Row group r sums rows r, r+16, ... in order in fp32 (4 rows are
+// loaded before they are added); the 16 partial sums are added in order 0..15; one rounding.
+constexpr int kPoolCols = 16, kPoolRowGroups = 16;
 template <typename T, int VEC>
-__global__ __launch_bounds__(256) void mean_pool_kernel(const T* __restrict__ e, int n, int d,
-                                                        T* __restrict__ c) {
-    const int col = (blockIdx.x * 64 + (threadIdx.x & 63)) * VEC;
-    const int rg = threadIdx.x >> 6;
-    __shared__ float part[4][64][VEC];
+__global__ __launch_bounds__(kPoolCols * kPoolRowGroups) void mean_pool_kernel(
+    const T* __restrict__ e, int n, int d, T* __restrict__ c) {
+    const int cl = threadIdx.x % kPoolCols, rg = threadIdx.x / kPoolCols;
+    const int col = (blockIdx.x * kPoolCols + cl) * VEC;
+    __shared__ float part[kPoolRowGroups][kPoolCols][VEC];
     float s[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) s[k] = 0.f;
     if (col < d) {
-        for (int r = rg; r < n; r += 4) {
+        int r = rg;
+        for (; r + 3 * kPoolRowGroups < n; r += 4 * kPoolRowGroups) {
+            alignas(16) T tmp[4][VEC];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                *reinterpret_cast<uint4*>(tmp[u]) =
+                    *reinterpret_cast<const uint4*>(e + (int64_t)(r + u * kPoolRowGroups) * d + col);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) s[k] += to_f32(tmp[u][k]);
+        }
+        for (; r < n; r += kPoolRowGroups) {
             alignas(16) T tmp[VEC];
             *reinterpret_cast<uint4*>(tmp) = *reinterpret_cast<const uint4*>(e + (int64_t)r * d + col);
 #pragma unroll
@@ -159,14 +173,15 @@ __global__ __launch_bounds__(256) void mean_pool_kernel(const T* __restrict__ e,
         }
     }
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) part[rg][threadIdx.x & 63][k] = s[k];
+    for (int k = 0; k < VEC; ++k) part[rg][cl][k] = s[k];
     __syncthreads();
     if (rg == 0 && col < d) {
         alignas(16) T tmp[VEC];
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
-            const int t = threadIdx.x;
-            const float tot = ((part[0][t][k] + part[1][t][k]) + part[2][t][k]) + part[3][t][k];
+            float tot = part[0][cl][k];
+#pragma unroll
+            for (int g = 1; g < kPoolRowGroups; ++g) tot += part[g][cl][k];
             tmp[k] = from_f32<T>(tot / (float)n);
         }
         *reinterpret_cast<uint4*>(c + col) = *reinterpret_cast<const uint4*>(tmp);
@@ -226,11 +241,11 @@ hipError_t launch_append_rows(int32_t n_caches, void* k_slab, void* v_slab, int6
 hipError_t launch_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, void* c_out,
                             hipStream_t st) {
     if (dtype == VS_F32) {
-        const int blocks = (d / 4 + 63) / 64;
-        mean_pool_kernel<float, 4><<<blocks, 256, 0, st>>>((const float*)e, n, d, (float*)c_out);
+        const int blocks = (d / 4 + kPoolCols - 1) / kPoolCols;
+        mean_pool_kernel<float, 4><<<blocks, kPoolCols * kPoolRowGroups, 0, st>>>((const float*)e, n, d, (float*)c_out);
     } else {
-        const int blocks = (d / 8 + 63) / 64;
-        mean_pool_kernel<__bf16, 8><<<blocks, 256, 0, st>>>((const __bf16*)e, n, d, (__bf16*)c_out);
+        const int blocks = (d / 8 + kPoolCols - 1) / kPoolCols;
+        mean_pool_kernel<__bf16, 8><<<blocks, kPoolCols * kPoolRowGroups, 0, st>>>((const __bf16*)e, n, d, (__bf16*)c_out);
     }
     return hipGetLastError();
 }

@@ -145,6 +145,7 @@ def test_mean_pool_and_tuning_argument_errors():
     assert L.vs_carrier_mean_pool(ODD, 4, 8, 0, FAKE, None) == 6
     assert L.vs_set_tuning(0, 33) == 2 and L.vs_set_tuning(1, 3) == 2
     assert L.vs_set_tuning(2, 100) == 2 and L.vs_set_tuning(9, 1) == 2
+    assert L.vs_set_tuning(3, 2) == 2 and L.vs_set_tuning(3, 1) == 0 and L.vs_set_tuning(3, 0) == 0
     assert L.vs_set_tuning(0, 4) == 0 and L.vs_set_tuning(0, 0) == 0
 
 

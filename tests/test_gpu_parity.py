@@ -22,7 +22,7 @@ QW = CONFIGS["cfg2"]["shape"]
 @pytest.fixture(autouse=True)
 def _reset_tuning():
     yield
-    for knob in (0, 1, 2):
+    for knob in (0, 1, 2, 3):
         vs.set_tuning(knob, 0)
 
 
