@@ -21,7 +21,17 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def generate() -> None:
+    """Write the generated instruction sequences that vs_prefill_mfma.hip includes."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("gen_prefill_asm", os.path.join(CSRC, "gen_prefill_asm.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    mod.main(os.path.join(CSRC, "vs_prefill_asm.inc"))
+
+
 def build(verbose: bool = False) -> str:
+    generate()
     cmd = [HIPCC] + FLAGS + ["-o", LIB] + sources()
     if verbose:
         print(" ".join(cmd))

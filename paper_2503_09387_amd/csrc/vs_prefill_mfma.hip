@@ -26,6 +26,8 @@
 //   * Workgroup id = row_tile * (nsplit*Hkv) + (split*Hkv + kv_head): with nsplit*Hkv a
 //     multiple of 8, all workgroups that read one K/V slice run on one XCD (ids are
 //     dealt round-robin to the 8 XCDs) and share its L2.
+#include <type_traits>
+
 #include "vs_internal.h"
 
 namespace vs {
@@ -39,14 +41,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int D = 128;
-constexpr int BM = 128;    // packed query rows per workgroup
+constexpr int BM = 128;    // packed query rows per workgroup: two wavefronts of 64 rows
 constexpr int BN = 64;     // keys per tile
-constexpr int KSTR = 136;  // LDS row stride of the K tile in elements (272 B)
-constexpr int VSTR = 160;  // LDS row stride of the V tile in elements (320 B)
-constexpr int kGroupThreads = 256;
+constexpr int kRowBytes = D * 2;               // one K or V row of one head in LDS
+constexpr int kTileBytes = BN * kRowBytes;     // 16 KB
+constexpr int kStageBytes = 2 * kTileBytes;    // K tile then V tile
+constexpr int kGroupLds = 2 * kStageBytes;     // two stages per key group
+constexpr int kGroupThreads = 128;             // two wavefronts per key group
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kStageBytes = BN * KSTR * 2 + BN * VSTR * 2;  // one K tile + one V tile
-constexpr int kGroupLds = 2 * kStageBytes;                  // two stages per key group
+constexpr int kFrameTileCost = 2;              // load-balancing weight of a tile with frame rows
 
 struct PrefillParams {
     const __bf16* kc;
@@ -56,7 +59,7 @@ struct PrefillParams {
     const __bf16* vf;
     __bf16* out;
     // partial accumulators, normalised, in register order:
-    // [nsplit*Hkv][row tiles][4 waves][4 dim blocks][2][64 lanes] x 8 bf16
+    // [nsplit*Hkv][row tiles][4 row groups of 32][4 dim blocks][2][64 lanes] x 8 bf16
     __bf16* part_o;
     float* part_ml;  // [nsplit*Hkv][m_pad][2]: reference (log2 units), row sum
     __bf16* k_append_dst;
@@ -67,322 +70,448 @@ struct PrefillParams {
     unsigned long long* dbg;  // tuning aid: per-workgroup timestamps, normally null
 };
 
+typedef __attribute__((address_space(1))) const void* global_cptr;
+typedef __attribute__((address_space(3))) void* lds_ptr;
+
 __device__ __forceinline__ float xhalf(float x) {  // value held by lane ^ 32
     return __shfl_xor(x, 32);
 }
 
-__device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-        (__attribute__((address_space(3))) bf16x4*)(p));
+__device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(p));
 }
 
-template <int KVG>
-__global__ __launch_bounds__(kGroupThreads * KVG, KVG == 1 ? 2 : 1) void prefill_mfma_kernel(PrefillParams p) {
-    extern __shared__ __attribute__((aligned(16))) char dyn_smem[];  // per key group: two stages of (K tile, V tile)
+// 16 bytes per lane from global memory straight into LDS: lane i's bytes land at dst + 16*i
+// (dst is the same for the whole wavefront); completion is counted by vmcnt.
+__device__ __forceinline__ void load_to_lds16(const char* src, char* dst) {
+    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)dst, 16, 0, 0);
+}
+
+// The matrix instructions are issued from hand-scheduled blocks of inline assembly
+// (vs_prefill_asm.inc, written by gen_prefill_asm.py, which also documents the register plan):
+// output accumulators and query fragments live in a[0:191] for the whole kernel and are never
+// values the compiler sees; every block names those registers as clobbered.
+#include "vs_prefill_asm.inc"
+
+template <int NKG>
+__global__ __launch_bounds__(kGroupThreads * NKG) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void prefill_mfma_kernel(PrefillParams p) {
+    extern __shared__ __attribute__((aligned(1024))) char dyn_smem[];  // per key group: two K tiles, two V tiles
 
     const unsigned long long t_start = p.dbg ? wall_clock64() : 0;
     const int tid = threadIdx.x;
-    const int kg = tid / kGroupThreads;        // key group of this wave
-    const int gtid = tid - kg * kGroupThreads;  // thread index inside the key group
-    const int lane = tid & 63, rg = (tid >> 6) & 3;  // rg: which 32 rows of the tile
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rb = w & 1;   // which 64 rows of the tile
+    const int kg = w >> 1;  // key group of this wave
     const int l32 = lane & 31, hi = lane >> 5;
     const int C = p.nsplit * p.Hkv;
     const int rt = blockIdx.x / C;
     const int c = blockIdx.x % C;
     const int split = c / p.Hkv, g = c % p.Hkv;
     const int L = p.L, T = p.T, G = p.G;
-    const int64_t kv_row_stride = (int64_t)p.Hkv * D;
-    char* const my_smem = dyn_smem + kg * kGroupLds;
+    const int64_t kv_row_bytes = (int64_t)p.Hkv * kRowBytes;
+    char* const k_ring = dyn_smem + kg * kGroupLds;
+    char* const v_ring = k_ring + 2 * kTileBytes;
 
     const int row0 = rt * BM;
-    const int wrow0 = row0 + rg * 32;
+    const int wrow0 = row0 + rb * 64;
     const int last_row = min(row0 + BM, p.M) - 1;
     const int tmax = last_row / G;                        // < T
     const int n_tiles = (L + tmax + 1 + BN - 1) / BN;     // key tiles this row tile can see
-    const int tile_begin = (int)((int64_t)n_tiles * split / p.nsplit);
-    const int tile_end = (int)((int64_t)n_tiles * (split + 1) / p.nsplit);
-    // key group kg takes tiles tile_begin + kg, + KVG, ...; every group runs n_steps barriers
-    const int n_steps = (tile_end - tile_begin + KVG - 1) / KVG;
+    // The tiles are shared out by cost: a tile that holds frame rows (causal mask, staging
+    // through the slower path) counts kFrameTileCost plain tiles.  cum(t) = cost of tiles 0..t-1;
+    // split i takes the tiles whose cum lies in [i, i+1) * total / nsplit.
+    const int n_plain = min(L / BN, n_tiles);
+    const int total_cost = n_plain + kFrameTileCost * (n_tiles - n_plain);
+    auto first_tile_at = [&](int i) {  // smallest t with cum(t) >= i * total / nsplit
+        const int target = (int)(((int64_t)total_cost * i + p.nsplit - 1) / p.nsplit);
+        return target <= n_plain ? target : n_plain + (target - n_plain + kFrameTileCost - 1) / kFrameTileCost;
+    };
+    const int tile_begin = first_tile_at(split);
+    const int tile_end = split + 1 == p.nsplit ? n_tiles : first_tile_at(split + 1);
+    // key group kg takes tiles tile_begin + kg, + NKG, ...: its tile number s is tile
+    // my_first + s*NKG; every group runs n_steps barriers
+    const int n_steps = (tile_end - tile_begin + NKG - 1) / NKG;
     const int my_first = tile_begin + kg;
+    const int n_my = (tile_end - my_first + NKG - 1) / NKG;  // tiles of this group (<= n_steps)
 
-    // ---- global -> register staging of one K/V tile: 4 x 16 B of K and of V per thread ----
-    uint4 kreg0, kreg1, kreg2, kreg3, vreg0, vreg1, vreg2, vreg3;
-    const int srow = gtid >> 4, sc16 = gtid & 15;  // this thread stages rows srow + 16n, 16-byte piece sc16
-#define VS_FETCH1(n, KR, VR)                                                             \
-    do {                                                                                 \
-        const int j = tile_ * BN + srow + 16 * (n);                                      \
-        uint4 kz = make_uint4(0, 0, 0, 0), vz = kz;                                      \
-        if (j < L) {                                                                     \
-            const int64_t off = ((int64_t)j * p.Hkv + g) * D + sc16 * 8;                 \
-            kz = *reinterpret_cast<const uint4*>(p.kc + off);                            \
-            vz = *reinterpret_cast<const uint4*>(p.vc + off);                            \
-        } else if (j < L + T) {                                                          \
-            const int64_t off = ((int64_t)(j - L) * p.Hkv + g) * D + sc16 * 8;           \
-            kz = *reinterpret_cast<const uint4*>(p.kf + off);                            \
-            vz = *reinterpret_cast<const uint4*>(p.vf + off);                            \
-        }                                                                                \
-        KR = kz;                                                                         \
-        VR = vz;                                                                         \
-    } while (0)
-#define VS_FETCH(tile)                                                                   \
-    do {                                                                                 \
-        const int tile_ = (tile);                                                        \
-        VS_FETCH1(0, kreg0, vreg0); VS_FETCH1(1, kreg1, vreg1);                          \
-        VS_FETCH1(2, kreg2, vreg2); VS_FETCH1(3, kreg3, vreg3);                          \
-    } while (0)
-#define VS_STAGE1(n, KR, VR)                                                             \
-    do {                                                                                 \
-        *reinterpret_cast<uint4*>(&ks_[(srow + 16 * (n)) * KSTR + sc16 * 8]) = KR;       \
-        *reinterpret_cast<uint4*>(&vs_[(srow + 16 * (n)) * VSTR + sc16 * 8]) = VR;       \
-    } while (0)
-#define VS_STAGE(buf)                                                                    \
-    do {                                                                                 \
-        __bf16* ks_ = reinterpret_cast<__bf16*>(my_smem + (buf) * kStageBytes);          \
-        __bf16* vs_ = ks_ + BN * KSTR;                                                   \
-        VS_STAGE1(0, kreg0, vreg0); VS_STAGE1(1, kreg1, vreg1);                          \
-        VS_STAGE1(2, kreg2, vreg2); VS_STAGE1(3, kreg3, vreg3);                          \
-    } while (0)
+    // ---- global -> LDS staging --------------------------------------------------------------
+    // A tile is 64 rows of 256 B.  One load instruction of a wavefront fills 1 KB = 4 rows
+    // ("chunk"): lane i fills 16-byte slot i&15 of row i>>4.  Which 16-byte piece of the row a
+    // slot holds is permuted so that the fragment reads below are free of bank conflicts:
+    //   K: slot = piece ^ (row & 15)         (32 lanes read one piece of 32 consecutive rows)
+    //   V: slot = piece ^ ((row & 3) << 1)   (a transposing read takes 32 B of each of 4 rows)
+    // Wave rb of the key group loads chunks 8*rb .. 8*rb+7 of a tile.
+    const int lr = lane >> 4, ls = lane & 15;
+    int k_src_off[4];  // byte offset of this lane's piece from the chunk's first row, chunk & 3 = x
+#pragma unroll
+    for (int x = 0; x < 4; ++x) k_src_off[x] = lr * (int)kv_row_bytes + ((ls ^ lr ^ (x << 2)) << 4);
+    const int v_src_off = lr * (int)kv_row_bytes + ((ls ^ (lr << 1)) << 4);
 
-    // the first key tile is requested before anything else (tiles past the range read as
-    // zeros and are fully masked, so a group without work in a step stays harmless)
-    kreg0 = kreg1 = kreg2 = kreg3 = vreg0 = vreg1 = vreg2 = vreg3 = make_uint4(0, 0, 0, 0);
-    if (my_first < tile_end) VS_FETCH(my_first);
+    // tile number s of this group -> K ring (is_v = false) or V ring, slot s & 1
+    auto issue = [&](int s, bool is_v) {
+        if (s >= n_my) return;
+        const int tile = my_first + s * NKG;
+        char* dst = (is_v ? v_ring : k_ring) + (s & 1) * kTileBytes + rb * (8 * 1024);
+        const int j0 = tile * BN + rb * 32;  // first row this wave loads
+        if (tile * BN + BN <= L) {
+            const char* src = reinterpret_cast<const char*>(is_v ? p.vc : p.kc) + ((int64_t)j0 * p.Hkv + g) * kRowBytes;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                load_to_lds16(src + u * 4 * kv_row_bytes + (is_v ? v_src_off : k_src_off[u & 3]), dst + u * 1024);
+        } else {
+            // the tile holds frame rows or runs past the end: rows past the last key re-read the
+            // last row (finite values; every such key is masked)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = min(j0 + 4 * u + lr, L + T - 1);
+                const char* row = (j < L)
+                    ? reinterpret_cast<const char*>(is_v ? p.vc : p.kc) + ((int64_t)j * p.Hkv + g) * kRowBytes
+                    : reinterpret_cast<const char*>(is_v ? p.vf : p.kf) + ((int64_t)(j - L) * p.Hkv + g) * kRowBytes;
+                const int piece = is_v ? (ls ^ (lr << 1)) : (ls ^ lr ^ ((u & 3) << 2));
+                load_to_lds16(row + (piece << 4), dst + u * 1024);
+            }
+        }
+    };
+
+    // the first tiles are requested before anything else
+    issue(0, false);
+    issue(0, true);
+    issue(1, false);
 
     // fused carrier compaction: one workgroup copies the last frame row into the cache
     if (p.k_append_dst && blockIdx.x == 0) {
-        const int n16 = (int)(kv_row_stride / 8);  // 16-byte chunks per row
-        const uint4* ksrc = reinterpret_cast<const uint4*>(p.kf + (int64_t)(T - 1) * kv_row_stride);
-        const uint4* vsrc = reinterpret_cast<const uint4*>(p.vf + (int64_t)(T - 1) * kv_row_stride);
-        for (int ch = tid; ch < n16; ch += kGroupThreads * KVG) {
+        const int n16 = (int)(kv_row_bytes / 16);  // 16-byte chunks per row
+        const uint4* ksrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.kf) + (int64_t)(T - 1) * kv_row_bytes);
+        const uint4* vsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.vf) + (int64_t)(T - 1) * kv_row_bytes);
+        for (int ch = tid; ch < n16; ch += kGroupThreads * NKG) {
             reinterpret_cast<uint4*>(p.k_append_dst)[ch] = ksrc[ch];
             reinterpret_cast<uint4*>(p.v_append_dst)[ch] = vsrc[ch];
         }
     }
 
-    // ---- Q fragments: B operand of S^T = K Q^T, lane (col q = l32, k = 8*hi..8*hi+7) ----
-    bf16x8 qf[8];
-    const int r_mine = wrow0 + l32;
-    int jmax;  // last key index visible to this lane's query row (causal test)
+    // ---- Q fragments: B operand of S^T = K Q^T, lane (col q = l32, k = 8*hi..8*hi+7); the wave
+    //      holds two row groups r = 0, 1 of 32 rows.  They are parked in a[128:191]. ----
+    int r_mine[2], jmax[2];  // jmax: last key index visible to this lane's query row (causal test)
     {
-        const int rr = min(r_mine, p.M - 1);
-        const int t = rr / G, hl = rr - t * G;
-        jmax = L + t;
-        const __bf16* qrow = p.q + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
+        bf16x8 qf[2][8];
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-            qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * hi);
+        for (int r = 0; r < 2; ++r) {
+            r_mine[r] = wrow0 + 32 * r + l32;
+            const int rr = min(r_mine[r], p.M - 1);
+            const int t = rr / G, hl = rr - t * G;
+            jmax[r] = L + t;
+            const __bf16* qrow = p.q + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                qf[r][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * hi);
+        }
+        asm volatile(VS_ASM_LOAD_Q
+                     :
+                     : "{v[128:131]}"(qf[0][0]), "{v[132:135]}"(qf[0][1]), "{v[136:139]}"(qf[0][2]), "{v[140:143]}"(qf[0][3]),
+                       "{v[144:147]}"(qf[0][4]), "{v[148:151]}"(qf[0][5]), "{v[152:155]}"(qf[0][6]), "{v[156:159]}"(qf[0][7]),
+                       "{v[160:163]}"(qf[1][0]), "{v[164:167]}"(qf[1][1]), "{v[168:171]}"(qf[1][2]), "{v[172:175]}"(qf[1][3]),
+                       "{v[176:179]}"(qf[1][4]), "{v[180:183]}"(qf[1][5]), "{v[184:187]}"(qf[1][6]), "{v[188:191]}"(qf[1][7])
+                     : VS_CLOB_ACC);
     }
+    asm volatile(VS_ASM_INIT_O : : : VS_CLOB_ACC);
 
-    f32x16 o[4];
-    float m_ref = -INFINITY, l_run = 0.f;  // softmax reference (log2 units); this lane's share of the row sum
+    float m_ref[2] = {-INFINITY, -INFINITY};  // softmax reference (log2 units)
+    float l_run[2] = {0.f, 0.f};              // this lane's share of the row sum
+
+    // LDS read addresses (bytes inside a tile)
+    unsigned k_rd[8];  // K fragment of step kk: row l32 (+32b), piece 2kk+hi
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
-
-    if (n_steps > 0) {
-        VS_STAGE(0);
-        if (my_first + KVG < tile_end) VS_FETCH(my_first + KVG);
-    }
-
+    for (int kk = 0; kk < 8; ++kk) k_rd[kk] = l32 * kRowBytes + (((2 * kk + hi) ^ (l32 & 15)) << 4);
     const int i16 = lane & 15, dh = (lane >> 4) & 1;
-    const int voff = (4 * hi + (i16 >> 2)) * VSTR + 16 * dh + 4 * (i16 & 3);  // this lane's corner of a V^T fragment
+    unsigned v_rd[2];  // V^T fragment corner, dim block parity x: row 4hi + (i16>>2), piece 4x + 2dh + ((i16&3)>>1)
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+        v_rd[x] = (4 * hi + (i16 >> 2)) * kRowBytes + (((4 * x + 2 * dh + ((i16 & 3) >> 1)) ^ ((i16 >> 2) << 1)) << 4) + 8 * (i16 & 1);
+    const unsigned k_ring_lds = (unsigned)(size_t)(lds_ptr)k_ring;  // LDS byte addresses of the rings
+    const unsigned v_ring_lds = (unsigned)(size_t)(lds_ptr)v_ring;
 
-    // S^T for 32 keys (sub-block b of the staged tile): 8 K fragments against the Q fragments
-    auto qk = [&](const __bf16* Ks, int b, f32x16& sc) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) sc[e] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(32 * b + l32) * KSTR + 16 * kk + 8 * hi]);
-            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], sc, 0, 0, 0);
+    // ---- pipeline state lives in fixed registers between the blocks: raw scores of the
+    // sub-block in flight S[parity][row group] in v[128:191], packed probabilities
+    // P[parity][row group][step] in v[216:247] (sub-block n of this group uses parity n & 1).
+    // Every block names them as clobbered, and the code between the blocks is small enough
+    // that the compiler stays in the low registers there (the build checks the listing).
+#define VS_ADDR(kb, vb)                                                                          \
+    [ka0] "v"(k_rd[0] + (kb)), [ka1] "v"(k_rd[1] + (kb)), [ka2] "v"(k_rd[2] + (kb)), [ka3] "v"(k_rd[3] + (kb)), \
+    [ka4] "v"(k_rd[4] + (kb)), [ka5] "v"(k_rd[5] + (kb)), [ka6] "v"(k_rd[6] + (kb)), [ka7] "v"(k_rd[7] + (kb)), \
+    [va0] "v"(v_rd[0] + (vb)), [va1] "v"(v_rd[1] + (vb))
+#define VS_CLOBBERS VS_CLOB_ACC, VS_CLOB_S, VS_CLOB_FRAG, VS_CLOB_TMP, VS_CLOB_P
+
+    // tile number s of this group: LDS byte addresses of its K and V tiles, first key index
+    auto k_tile = [&](int s) { return k_ring_lds + (s & 1) * kTileBytes; };
+    auto v_tile = [&](int s) { return v_ring_lds + (s & 1) * kTileBytes; };
+    auto key0 = [&](int n) { return (my_first + (n >> 1) * NKG) * BN + 32 * (n & 1); };  // of sub-block n
+
+    // Sub-block n has gone through the speculative softmax (reference possibly stale); its PV
+    // product has not been issued.  Commit its row sums, or, if a probability came out above
+    // 2^8 (or overflowed), redo it exactly from the raw scores: reference refreshed from their
+    // maximum, accumulators and sums rescaled, probabilities rebuilt.
+    // Sub-block 0 ran against the made-up reference 0: there an underflow (a lane that can see
+    // a key but whose sum vanished) also sends it to the exact pass, which then starts from no
+    // reference at all.
+    auto commit = [&](int n, float sum0, float sum1) {
+        bool redo = !(sum0 <= 256.f) || !(sum1 <= 256.f);
+        if (n == 0) {
+            const int jl = key0(0) + 4 * hi;  // this lane's smallest key
+            redo = redo || (jl <= jmax[0] && sum0 < 0x1p-40f) || (jl <= jmax[1] && sum1 < 0x1p-40f);
         }
-    };
-    // key j = jb + 8*(e>>2) + 4*hi + (e&3) is visible to the row iff j <= jmax
-    auto mask = [&](int jb, f32x16& sc) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-            if (jb + 8 * (e >> 2) + 4 * hi + (e & 3) > jmax) sc[e] = -INFINITY;
-    };
-    // p = 2^(s*c - reference) in place; returns this lane's sum
-    auto expo = [&](f32x16& sc) {
-        const float m_sub = (m_ref == -INFINITY) ? 0.f : m_ref;
-        float r0 = 0.f, r1 = 0.f;
-#pragma unroll
-        for (int e = 0; e < 16; e += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[e], p.scale_log2e, -m_sub));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[e + 1], p.scale_log2e, -m_sub));
-            sc[e] = p0;
-            sc[e + 1] = p1;
-            r0 += p0;
-            r1 += p1;
+        if (!__any(redo)) {
+            l_run[0] += sum0;
+            l_run[1] += sum1;
+            return;
         }
-        return r0 + r1;
-    };
-    // O^T += V^T P^T for the 32 keys of sub-block b.  k-slot 4c+j of step t is key
-    // 16t + 8c + 4hi + j, i.e. probability registers 8t .. 8t+7 of the sub-block.
-    auto pv = [&](const __bf16* Vs, int b, const f32x16& sc) {
-        bf16x8 pf[2];
+        if (n == 0) m_ref[0] = m_ref[1] = -INFINITY;
+        const int par = n & 1, j0 = key0(n);
+        float alpha[2];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int r = 0; r < 2; ++r) {
+            f32x16 x;  // raw scores S[par][r], fetched from their fixed registers
+            if (par == 0 && r == 0) asm volatile("" : "={v[128:143]}"(x));
+            if (par == 0 && r == 1) asm volatile("" : "={v[144:159]}"(x));
+            if (par == 1 && r == 0) asm volatile("" : "={v[160:175]}"(x));
+            if (par == 1 && r == 1) asm volatile("" : "={v[176:191]}"(x));
+            if (j0 + 32 > L) {
 #pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const bf16x2 pr = __builtin_convertvector(f32x2{sc[8 * t + e], sc[8 * t + e + 1]}, bf16x2);
-                pf[t][e] = pr[0];
-                pf[t][e + 1] = pr[1];
+                for (int e = 0; e < 16; ++e)
+                    if (j0 + 8 * (e >> 2) + 4 * hi + (e & 3) > jmax[r]) x[e] = -INFINITY;
             }
+            float mx = -INFINITY;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, x[e]);
+            mx = fmaxf(mx, xhalf(mx)) * p.scale_log2e;
+            const float m_new = fmaxf(m_ref[r], mx);
+            alpha[r] = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref[r] - m_new);
+            m_ref[r] = m_new;
+            const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;
+            float sum = 0.f;
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                const bf16x4 lo = lds_read_tr(Vs + voff + (32 * b + 16 * t) * VSTR + 32 * db);
-                const bf16x4 hi4 = lds_read_tr(Vs + voff + (32 * b + 16 * t + 8) * VSTR + 32 * db);
-                const bf16x8 a = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[t], o[db], 0, 0, 0);
+            for (int t = 0; t < 2; ++t) {
+                bf16x8 pk8;
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(x[8 * t + e], p.scale_log2e, -m_sub));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(x[8 * t + e + 1], p.scale_log2e, -m_sub));
+                    const bf16x2 pk = __builtin_convertvector(f32x2{p0, p1}, bf16x2);
+                    pk8[e] = pk[0];
+                    pk8[e + 1] = pk[1];
+                    sum += (float)pk[0] + (float)pk[1];
+                }
+                // P[par][r][t] goes back to its fixed registers 216 + 4*(4*par + 2*r + t)
+                switch (4 * par + 2 * r + t) {
+                    case 0: asm volatile("" : : "{v[216:219]}"(pk8)); break;
+                    case 1: asm volatile("" : : "{v[220:223]}"(pk8)); break;
+                    case 2: asm volatile("" : : "{v[224:227]}"(pk8)); break;
+                    case 3: asm volatile("" : : "{v[228:231]}"(pk8)); break;
+                    case 4: asm volatile("" : : "{v[232:235]}"(pk8)); break;
+                    case 5: asm volatile("" : : "{v[236:239]}"(pk8)); break;
+                    case 6: asm volatile("" : : "{v[240:243]}"(pk8)); break;
+                    default: asm volatile("" : : "{v[244:247]}"(pk8)); break;
+                }
             }
+            l_run[r] = l_run[r] * alpha[r] + sum;
         }
+        if (__any(alpha[0] != 1.f || alpha[1] != 1.f))
+            asm volatile(VS_ASM_RESCALE : : [alpha0] "v"(alpha[0]), [alpha1] "v"(alpha[1]) : VS_CLOB_ACC, VS_CLOB_TMP);
     };
-    // Does the speculative pass (stale reference) have to be redone for this sub-block?  Yes if
-    // some probability came out above 2^8 (or overflowed), or if a row that can see a key of this
-    // sub-block has no reference yet.
-    auto stale = [&](float rs, int jb) {
-        return __any(!(rs <= 256.f) || (m_ref == -INFINITY && jb + 4 * hi <= jmax));
-    };
-    // Exact pass: recompute the raw scores, refresh the reference from their maximum, rescale the
-    // accumulators and redo the probabilities.  Runs once at the start and then rarely.
-    auto refresh = [&](const __bf16* Ks, int b, int jb, bool masked, f32x16& sc) {
-        qk(Ks, b, sc);
-        if (masked) mask(jb, sc);
-        float mx = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[e]);
-        mx = fmaxf(mx, xhalf(mx)) * p.scale_log2e;
-        const float m_new = fmaxf(m_ref, mx);
-        const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
-        m_ref = m_new;
-        l_run *= alpha;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-        return expo(sc);
-    };
+
+    // One pipeline step with a softmax part: runs the block `ASM` and commits sub-block n.
+#define VS_STEP(ASM, n, kb, vb)                                                                      \
+    do {                                                                                             \
+        float sum0_, sum1_;                                                                          \
+        const float ms0_ = (m_ref[0] == -INFINITY) ? 0.f : m_ref[0];                                 \
+        const float ms1_ = (m_ref[1] == -INFINITY) ? 0.f : m_ref[1];                                 \
+        asm volatile(ASM                                                                             \
+                     : [sum0] "=&v"(sum0_), [sum1] "=&v"(sum1_)                            \
+                     : VS_ADDR(kb, vb), [ms0] "v"(ms0_), [ms1] "v"(ms1_), [scale] "s"(p.scale_log2e) \
+                     : VS_CLOBBERS);                                                                 \
+        commit(n, sum0_, sum1_);                                                                     \
+    } while (0)
+#define VS_STEP_MASKED(ASM, n, kb, vb)                                                               \
+    do {                                                                                             \
+        float sum0_, sum1_;                                                                          \
+        const float ms0_ = (m_ref[0] == -INFINITY) ? 0.f : m_ref[0];                                 \
+        const float ms1_ = (m_ref[1] == -INFINITY) ? 0.f : m_ref[1];                                 \
+        const int d0_ = jmax[0] - (key0(n) + 4 * hi), d1_ = jmax[1] - (key0(n) + 4 * hi);            \
+        unsigned long long mk0_, mk1_;                                                               \
+        asm volatile(ASM                                                                             \
+                     : [sum0] "=&v"(sum0_), [sum1] "=&v"(sum1_), [mk0] "=&s"(mk0_), [mk1] "=&s"(mk1_) \
+                     : VS_ADDR(kb, vb), [ms0] "v"(ms0_), [ms1] "v"(ms1_), [scale] "s"(p.scale_log2e), \
+                       [d0] "v"(d0_), [d1] "v"(d1_)                                                  \
+                     : VS_CLOBBERS);                                                                 \
+        commit(n, sum0_, sum1_);                                                                     \
+    } while (0)
 
     const unsigned long long t_loop = p.dbg ? wall_clock64() : 0;
-    for (int step = 0; step < n_steps; ++step) {
-        const int tile = my_first + step * KVG;  // may lie past tile_end for the last step of a group
-        const int buf = step & 1;
-        __syncthreads();  // stage `buf` is complete; nobody reads the other stage any more
-        if (step + 1 < n_steps) {
-            VS_STAGE(buf ^ 1);
-            kreg0 = kreg1 = kreg2 = kreg3 = vreg0 = vreg1 = vreg2 = vreg3 = make_uint4(0, 0, 0, 0);
-            if (tile + 2 * KVG < tile_end) VS_FETCH(tile + 2 * KVG);
-        }
-        if (KVG > 1 && tile >= tile_end) continue;  // this group idles in the last step
-        const __bf16* Ks = reinterpret_cast<const __bf16*>(my_smem + buf * kStageBytes);
-        const __bf16* Vs = Ks + BN * KSTR;
-        const int j0 = tile * BN;
-        const bool masked = j0 + BN > L;  // the tile holds frame rows (causal) or runs past the end
-
-        // Two sub-blocks of 32 keys, ordered so that the exponentials of one (VALU) sit next to
-        // the matrix products of the other (MFMA):  QK(0) | QK(1) + exp(0) | PV(0) + exp(1) | PV(1)
-        f32x16 sa, sb;
-        qk(Ks, 0, sa);
-        if (masked) mask(j0, sa);
-        qk(Ks, 1, sb);
-        float rsa = expo(sa);
-        if (masked) mask(j0 + 32, sb);
-        if (stale(rsa, j0)) rsa = refresh(Ks, 0, j0, masked, sa);
-        float rsb = expo(sb);
-        pv(Vs, 0, sa);
-        if (stale(rsb, j0 + 32)) {
-            l_run += rsa;  // the refresh rescales l_run, so sub-block 0's sum goes in first
-            rsa = 0.f;
-            rsb = refresh(Ks, 1, j0 + 32, masked, sb);
-        }
-        pv(Vs, 1, sb);
-        l_run += rsa + rsb;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();                     // K(0), V(0), K(1) of every group are staged
+    if (n_my > 0) {
+        // sub-block 0: raw scores, then step 0 = QK(1) | SM(0) against the reference 0 (fine
+        // whenever the scaled scores are moderate; otherwise commit() redoes it exactly)
+        asm volatile(VS_ASM_QK0 : : VS_ADDR(k_tile(0), 0u) : VS_CLOBBERS);
+        m_ref[0] = m_ref[1] = 0.f;
+        if (key0(0) + 32 > L) VS_STEP_MASKED(VS_ASM_FIRST_MASKED, 0, k_tile(0), 0u);
+        else VS_STEP(VS_ASM_FIRST, 0, k_tile(0), 0u);
     }
-#undef VS_FETCH1
-#undef VS_FETCH
-#undef VS_STAGE1
-#undef VS_STAGE
+
+    unsigned long long* stamps = (p.dbg && blockIdx.x == 100 && tid == 0) ? p.dbg + 8192 : nullptr;
+    for (int s = 0; s < n_steps; ++s) {
+        // steps 2s+1 and 2s+2 of this group: they read K of tile s+1 and V of tile s
+        if (stamps) stamps[1 + 4 * s] = wall_clock64();
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of K(s+1), V(s) has landed
+        if (stamps) stamps[2 + 4 * s] = wall_clock64();
+        __syncthreads();                     // ... and everybody's; K slot s&1 and V slot (s+1)&1 are free
+        if (stamps) stamps[3 + 4 * s] = wall_clock64();
+        // tiles to stage now: K of tile s+2, V of tile s+1.  When both lie inside the cache rows
+        // the first block issues the loads itself, between its matrix instructions.
+        const bool loads_inside = s + 2 < n_my && (my_first + (s + 2) * NKG) * BN + BN <= L;
+        if (!loads_inside) {
+            issue(s + 2, false);
+            issue(s + 1, true);
+        }
+        if (stamps) stamps[4 + 4 * s] = wall_clock64();
+        if (NKG > 1 && s >= n_my) continue;  // this group idles in the last step
+        const unsigned kb = k_tile(s + 1), vb = v_tile(s);
+        const int n = 2 * s + 1;
+        if (s + 1 < n_my) {
+            // step 2s+1: QK(2s+2) | PV(2s) | SM(2s+1)
+            if (key0(n) + 32 > L) {
+                VS_STEP_MASKED(VS_ASM_ODD_MASKED, n, kb, vb);
+            } else if (loads_inside) {
+                // this wave's share: rows 32*rb .. 32*rb+31 of the two tiles, head g
+                unsigned long long ksrc = (unsigned long long)(reinterpret_cast<const char*>(p.kc) +
+                    ((int64_t)((my_first + (s + 2) * NKG) * BN + rb * 32) * p.Hkv + g) * kRowBytes);
+                unsigned long long vsrc = (unsigned long long)(reinterpret_cast<const char*>(p.vc) +
+                    ((int64_t)((my_first + (s + 1) * NKG) * BN + rb * 32) * p.Hkv + g) * kRowBytes);
+                unsigned ldsk = k_tile(s) + rb * (8 * 1024);
+                unsigned ldsv = v_tile(s + 1) + rb * (8 * 1024);
+                float sum0_, sum1_;
+                const float ms0_ = (m_ref[0] == -INFINITY) ? 0.f : m_ref[0];
+                const float ms1_ = (m_ref[1] == -INFINITY) ? 0.f : m_ref[1];
+                asm volatile(VS_ASM_ODD_LOADS
+                             : [sum0] "=&v"(sum0_), [sum1] "=&v"(sum1_),
+                               "+{s[88:89]}"(ksrc), "+{s[90:91]}"(vsrc), [ldsk] "+s"(ldsk), [ldsv] "+s"(ldsv)
+                             : VS_ADDR(kb, vb), [ms0] "v"(ms0_), [ms1] "v"(ms1_), [scale] "s"(p.scale_log2e),
+                               [kso0] "v"(k_src_off[0]), [kso1] "v"(k_src_off[1]), [kso2] "v"(k_src_off[2]), [kso3] "v"(k_src_off[3]),
+                               [vso] "v"(v_src_off), [stride] "s"(4 * (int)kv_row_bytes)
+                             : VS_CLOBBERS, "scc");
+                commit(n, sum0_, sum1_);
+            } else {
+                VS_STEP(VS_ASM_ODD, n, kb, vb);
+            }
+            // step 2s+2: QK(2s+3) | PV(2s+1) | SM(2s+2)
+            if (key0(n + 1) + 32 > L) VS_STEP_MASKED(VS_ASM_EVEN_MASKED, n + 1, kb, vb);
+            else VS_STEP(VS_ASM_EVEN, n + 1, kb, vb);
+        } else {
+            // the group's last tile: step 2s+1 = PV(2s) | SM(2s+1), then PV(2s+1)
+            if (key0(n) + 32 > L) VS_STEP_MASKED(VS_ASM_ODD_LAST_MASKED, n, kb, vb);
+            else VS_STEP(VS_ASM_ODD_LAST, n, kb, vb);
+            asm volatile(VS_ASM_TAIL : : VS_ADDR(kb, vb) : VS_CLOBBERS);
+        }
+    }
+#undef VS_ADDR
+#undef VS_CLOBBERS
+#undef VS_STEP
+#undef VS_STEP_MASKED
 
     const unsigned long long t_epi = p.dbg ? wall_clock64() : 0;
-    float l_tot = l_run + xhalf(l_run);
+    f32x16 o[2][4];
+    asm volatile(VS_ASM_READ_O
+                 : "={v[0:15]}"(o[0][0]), "={v[16:31]}"(o[0][1]), "={v[32:47]}"(o[0][2]), "={v[48:63]}"(o[0][3]),
+                   "={v[64:79]}"(o[1][0]), "={v[80:95]}"(o[1][1]), "={v[96:111]}"(o[1][2]), "={v[112:127]}"(o[1][3])
+                 :
+                 : VS_CLOB_ACC);
+    float l_tot[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) l_tot[r] = l_run[r] + xhalf(l_run[r]);
 
     // ---- merge the key groups through LDS: group 1 hands (reference, sum, accumulator) to
     //      group 0, which holds the same rows in the same lanes ----
-    if (KVG > 1) {
+    if (NKG > 1) {
         __syncthreads();  // all tiles consumed, the stage buffers are free
-        float* xo = reinterpret_cast<float*>(dyn_smem);  // [4 waves][16 x f32x4][64 lanes]
-        float* xml = xo + 4 * 16 * 64 * 4;               // [4 waves][32 rows][2]
+        float* xo = reinterpret_cast<float*>(dyn_smem);  // [2 waves][32 x f32x4][64 lanes]
+        float* xml = xo + 2 * 32 * 64 * 4;               // [2 waves][2 row groups][32 rows][2]
         if (kg == 1) {
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int r = 0; r < 2; ++r) {
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    f32x4 w;
+                for (int db = 0; db < 4; ++db)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) w[j] = o[db][4 * e4 + j];
-                    *reinterpret_cast<f32x4*>(&xo[((rg * 16 + db * 4 + e4) * 64 + lane) * 4]) = w;
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        f32x4 wv;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) wv[j] = o[r][db][4 * e4 + j];
+                        *reinterpret_cast<f32x4*>(&xo[(((rb * 2 + r) * 16 + db * 4 + e4) * 64 + lane) * 4]) = wv;
+                    }
+                if (hi == 0) {
+                    xml[((rb * 2 + r) * 32 + l32) * 2 + 0] = m_ref[r];
+                    xml[((rb * 2 + r) * 32 + l32) * 2 + 1] = l_tot[r];
                 }
-            if (hi == 0) {
-                xml[(rg * 32 + l32) * 2 + 0] = m_ref;
-                xml[(rg * 32 + l32) * 2 + 1] = l_tot;
             }
         }
         __syncthreads();
         if (kg == 1) return;
-        const float m1 = xml[(rg * 32 + l32) * 2 + 0], l1 = xml[(rg * 32 + l32) * 2 + 1];
-        const float m_new = fmaxf(m_ref, m1);
-        const float a0 = (m_ref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_ref - m_new);
-        const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - m_new);
-        m_ref = m_new;
-        l_tot = l_tot * a0 + l1 * a1;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                const f32x4 w = *reinterpret_cast<const f32x4*>(&xo[((rg * 16 + db * 4 + e4) * 64 + lane) * 4]);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) o[db][4 * e4 + j] = o[db][4 * e4 + j] * a0 + w[j] * a1;
-            }
-    }
-
-    // ---- output: lane (q = l32, hi) holds dims 32*db + 8*(e>>2) + 4*hi + (e&3) ----
-    const float inv = (l_tot > 0.f) ? 1.0f / l_tot : 0.f;
-    if (p.nsplit == 1) {
-        if (r_mine < p.M) {
-            const int t = r_mine / G, hl = r_mine - t * G;
-            __bf16* orow = p.out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
+        for (int r = 0; r < 2; ++r) {
+            const float m1 = xml[((rb * 2 + r) * 32 + l32) * 2 + 0], l1 = xml[((rb * 2 + r) * 32 + l32) * 2 + 1];
+            const float m_new = fmaxf(m_ref[r], m1);
+            const float a0 = (m_ref[r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_ref[r] - m_new);
+            const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - m_new);
+            m_ref[r] = m_new;
+            l_tot[r] = l_tot[r] * a0 + l1 * a1;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
-                    bf16x4 w;
+                    const f32x4 wv = *reinterpret_cast<const f32x4*>(&xo[(((rb * 2 + r) * 16 + db * 4 + e4) * 64 + lane) * 4]);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) w[j] = (__bf16)(o[db][4 * e4 + j] * inv);
-                    *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * e4 + 4 * hi) = w;
+                    for (int j = 0; j < 4; ++j) o[r][db][4 * e4 + j] = o[r][db][4 * e4 + j] * a0 + wv[j] * a1;
                 }
         }
-    } else {
-        // normalised partials in register order: every store instruction writes 1 KB contiguous
-        const int64_t unit = (int64_t)c * p.n_row_tiles + rt;
-        bf16x8* po = reinterpret_cast<bf16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane;
+    }
+
+    // ---- output: lane (q = l32, hi) holds dims 32*db + 8*(e>>2) + 4*hi + (e&3) ----
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+    for (int r = 0; r < 2; ++r) {
+        const float inv = (l_tot[r] > 0.f) ? 1.0f / l_tot[r] : 0.f;
+        const int rg = rb * 2 + r;  // 32-row group inside the row tile
+        if (p.nsplit == 1) {
+            if (r_mine[r] < p.M) {
+                const int t = r_mine[r] / G, hl = r_mine[r] - t * G;
+                __bf16* orow = p.out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
 #pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
-                bf16x8 w;
+                for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) w[j] = (__bf16)(o[db][8 * h2 + j] * inv);
-                po[(db * 2 + h2) * 64] = w;
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        bf16x4 wv;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) wv[j] = (__bf16)(o[r][db][4 * e4 + j] * inv);
+                        *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * e4 + 4 * hi) = wv;
+                    }
             }
-        if (hi == 0) {
-            const int64_t prow = (int64_t)c * p.m_pad + r_mine;
-            p.part_ml[prow * 2 + 0] = m_ref;
-            p.part_ml[prow * 2 + 1] = l_tot;
+        } else {
+            // normalised partials in register order: every store instruction writes 1 KB contiguous
+            const int64_t unit = (int64_t)c * p.n_row_tiles + rt;
+            bf16x8* po = reinterpret_cast<bf16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    bf16x8 wv;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) wv[j] = (__bf16)(o[r][db][8 * h2 + j] * inv);
+                    __builtin_nontemporal_store(wv, &po[(db * 2 + h2) * 64]);
+                }
+            if (hi == 0) {
+                const int64_t prow = (int64_t)c * p.m_pad + r_mine[r];
+                p.part_ml[prow * 2 + 0] = m_ref[r];
+                p.part_ml[prow * 2 + 1] = l_tot[r];
+            }
         }
     }
     if (p.dbg && tid == 0) {
@@ -460,7 +589,7 @@ Plan make_plan(const vs_shape& s, int n_tokens, int len) {
     pl.m_pad = pl.n_row_tiles * BM;
     const int units = pl.n_row_tiles * s.n_kv_heads;
     const int max_tiles = (len + n_tokens + BN - 1) / BN;
-    // 8-wave workgroups (two key groups) when there are enough key tiles to share out
+    // 4-wave workgroups (two key groups) when there are enough key tiles to share out
     pl.kvg = g_tune_prefill_kv_groups ? g_tune_prefill_kv_groups : (max_tiles >= 8 ? 2 : 1);
     int ns = (pl.kvg == 1 ? 512 : 256) / units;  // fill the chip in a single round
     if (ns > max_tiles / pl.kvg) ns = max_tiles / pl.kvg;
