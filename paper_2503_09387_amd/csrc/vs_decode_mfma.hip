@@ -2,9 +2,15 @@
 // Eq. 1 of Section 3.1): one query token per stream over that stream's retained rows.
 //
 // The step is bound by reading K and V once from HBM, so the work is cut by ROWS, not by
-// stream: every (stream, KV head, chunk of `chunk_rows` rows) is one workgroup, whatever
-// the stream's length.  Inside a workgroup each of the 4 wavefronts walks its own 32-row
-// tiles with no workgroup barrier in the loop:
+// stream: the 32-row tiles of all streams are laid end to end and every workgroup of the
+// launch takes an equal, contiguous share of them (a share that crosses from one stream into
+// the next is worked off as two segments).  A workgroup reads WHOLE rows: its wavefronts are
+// the KV heads (wavefront w walks the share for head w), so together they stream contiguous
+// memory, which HBM serves measurably faster than one head's 256 bytes out of every 1 KB.
+// (With fewer than 4 KV heads the spare wavefronts take sub-ranges of the share; with more,
+// blockIdx.y selects the group of 4 heads.)  The grid is at most two workgroups per compute
+// unit, so they all run at once and stream for the whole launch.  A wavefront works alone,
+// with no barrier anywhere in the kernel:
 //   * K rows go straight from global memory into the A operand of
 //     v_mfma_f32_16x16x32_bf16 (S^T = K Q^T; the G query heads of the KV head are the
 //     columns, padded to 16);
@@ -14,13 +20,13 @@
 //   * the softmax reference maximum is refreshed only when a score exceeds it by more than
 //     2^8, which needs one ballot per tile instead of two cross-lane reductions and one
 //     accumulator rescale.
-// The row appended in this step is read from k_new / v_new (never from the slab, which one
-// workgroup per KV head updates on the side).  Wave results are merged in LDS; chunk
-// results by a second small kernel.  (Merging inside the attention kernel, by the last
-// workgroup to arrive, was measured and rejected: partials must then be written through to
-// device-coherent memory or the L2 flushed per workgroup, because the 8 XCDs' L2 caches are
-// not coherent with each other inside a kernel, and either costs more than the 2.4 us of a
-// second launch.)
+// The row appended in this step is read from k_new / v_new (never from the slab, which the
+// wavefront that owns the stream's last tile updates on the side).  Every wavefront leaves a
+// normalised partial result (bf16) with its reference and sum; a second small kernel merges
+// them.  (Merging inside the attention kernel, by the last workgroup to arrive, was measured
+// and rejected: partials must then be written through to device-coherent memory or the L2
+// flushed per workgroup, because the 8 XCDs' L2 caches are not coherent with each other
+// inside a kernel, and either costs more than a second launch.)
 #include "vs_internal.h"
 
 namespace vs {
@@ -45,13 +51,23 @@ struct DecodeParams {
     const __bf16* k_new;  // may be null
     const __bf16* v_new;
     __bf16* out;
-    float* part_o;        // [stream][max_chunks][Hkv][G][D]
-    float* part_ml;       // [stream][max_chunks][Hkv][G][2]
+    __bf16* part_o;       // [slot][Hkv][nsub][G][D] normalised, slot = workgroup + stream of the segment
+    float* part_ml;       // [slot][Hkv][nsub][G][2]: reference (log2 units), sum
     int64_t stream_stride;   // elements between streams in the slabs
-    int n_streams, G, Hq, Hkv, chunk_rows, max_chunks;
+    int n_streams, G, Hq, Hkv;
+    int nh, nsub;            // KV heads per workgroup (min(Hkv, 4)) and sub-ranges per share (4 / nh)
+    int n_wg;                // workgroups along x
+    int total_tiles;         // tile_prefix[n_streams]
     float scale_log2e;
+    unsigned long long* dbg;  // tuning aid: per-workgroup timestamps, normally null
     LenTable lens;           // valid rows per stream, the appended row included
+    int tile_prefix[kMaxStreamsPerLaunch + 1];  // tiles of the streams before this one
 };
+
+// first flat tile of workgroup w (w = n_wg gives the end)
+__device__ __forceinline__ int wg_first_tile(const DecodeParams& p, int w) {
+    return (int)((int64_t)w * p.total_tiles / p.n_wg);
+}
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
@@ -136,46 +152,61 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
     } while (0)
 #define VS_TILE(R0, X) VS_TILE_COMPUTE(R0, k0##X, k1##X, k2##X, k3##X, k4##X, k5##X, k6##X, k7##X)
 
-// Grid (chunk, KV head, stream).  Partials go to slot = stream * max_chunks + chunk.
+// Grid (n_wg, Hkv / nh).
 template <int MODE, int DEPTH>
 __global__ __launch_bounds__(kThreads, DEPTH == 1 ? 3 : 2) void decode_mfma_kernel(DecodeParams p) {
-    __shared__ __attribute__((aligned(16))) char smem[kWaves * TR * VSTR * 2];       // per-wave V tiles
-    __shared__ __attribute__((aligned(16))) float sm_o[kWaves * kMaxGroup * D];        // wave results
-    __shared__ float sm_ml[kWaves * kMaxGroup * 2];
+    __shared__ __attribute__((aligned(16))) char smem[kWaves * TR * VSTR * 2];  // per-wave V tiles
 
-    const int chunk = blockIdx.x, g = blockIdx.y, s = blockIdx.z;
-    const int len = p.lens.v[s];
-    const int row_begin = chunk * p.chunk_rows;
-    if (row_begin >= len) return;  // this stream has fewer chunks than the longest one
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const unsigned long long t_start = p.dbg ? wall_clock64() : 0;
+    unsigned long long t_first = 0, t_loop = 0;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i16 = lane & 15, kq = lane >> 4;
-    const int n_chunks = (len + p.chunk_rows - 1) / p.chunk_rows;
-    const int row_end = min(len, row_begin + p.chunk_rows);
-    const int n_tiles = (row_end - row_begin + TR - 1) / TR;
-    const int last = row_end - 1;
-    const int new_row = p.k_new ? len - 1 : -1;
+    const int g = blockIdx.y * p.nh + wave % p.nh;  // this wavefront's KV head
+    const int sub = wave / p.nh;                     // and its sub-range of every segment
     const int64_t row_stride = (int64_t)p.Hkv * D;
+    const int flat_end = wg_first_tile(p, blockIdx.x + 1);
+    int flat = wg_first_tile(p, blockIdx.x);
+    // stream of the first tile: the number of streams that end at or before it
+    int s = __builtin_popcountll(__ballot(p.tile_prefix[lane + 1] <= flat));
+    __bf16* vs_w = reinterpret_cast<__bf16*>(smem) + wave * (TR * VSTR);
+    const __bf16* vrd = &vs_w[(4 * kq + (i16 >> 2)) * VSTR + 4 * (i16 & 3)];
+
+  for (bool first_segment = true; flat < flat_end; first_segment = false, ++s) {
+    // ---- one segment: tiles [seg_a, seg_b) of stream s; this wavefront takes the sub-range
+    //      [tile_a, tile_b) of it for head g ----
+    const int len = p.lens.v[s];
+    const int stream_tiles = p.tile_prefix[s + 1] - p.tile_prefix[s];
+    const int seg_a = flat - p.tile_prefix[s];
+    const int seg_b = min(stream_tiles, flat_end - p.tile_prefix[s]);
+    const bool whole_stream = seg_a == 0 && seg_b == stream_tiles && p.nsub == 1;
+    const int tile_a = seg_a + (seg_b - seg_a) * sub / p.nsub;
+    const int tile_b = seg_a + (seg_b - seg_a) * (sub + 1) / p.nsub;
+    const int row_begin = tile_a * TR;
+    const int row_end = min(len, tile_b * TR);
+    const int n_tiles = tile_b - tile_a;
+    const int last = max(row_end - 1, 0);
+    const int new_row = p.k_new ? len - 1 : -1;
     __bf16* kslab = p.k_slab + (int64_t)s * p.stream_stride + (int64_t)g * D;
     __bf16* vslab = p.v_slab + (int64_t)s * p.stream_stride + (int64_t)g * D;
     const __bf16* knew = p.k_new ? p.k_new + ((int64_t)s * p.Hkv + g) * D : nullptr;
     const __bf16* vnew = p.v_new ? p.v_new + ((int64_t)s * p.Hkv + g) * D : nullptr;
-    __bf16* vs_w = reinterpret_cast<__bf16*>(smem) + wave * (TR * VSTR);
-    const __bf16* vrd = &vs_w[(4 * kq + (i16 >> 2)) * VSTR + 4 * (i16 & 3)];
 
-    // two tiles per wave are requested before anything else happens
+    // two tiles are requested before anything else happens
     const uint4 zz = make_uint4(0, 0, 0, 0);
     uint4 k0a = zz, k1a = zz, k2a = zz, k3a = zz, k4a = zz, k5a = zz, k6a = zz, k7a = zz;
     uint4 v0a = zz, v1a = zz, v2a = zz, v3a = zz, v4a = zz, v5a = zz, v6a = zz, v7a = zz;
     uint4 k0b = zz, k1b = zz, k2b = zz, k3b = zz, k4b = zz, k5b = zz, k6b = zz, k7b = zz;
     uint4 v0b = zz, v1b = zz, v2b = zz, v3b = zz, v4b = zz, v5b = zz, v6b = zz, v7b = zz;
-    if (wave < n_tiles) VS_FETCH(wave, a);
-    if (DEPTH == 2 && wave + kWaves < n_tiles) VS_FETCH(wave + kWaves, b);
+    if (0 < n_tiles) VS_FETCH(0, a);
+    if (DEPTH == 2 && 1 < n_tiles) VS_FETCH(1, b);
 
-    // the step's new row also goes into the slab (nobody reads it from there in this launch)
-    if (new_row >= 0 && chunk == n_chunks - 1 && tid < 32) {
-        const int c = tid & 15;
-        const uint4* src = reinterpret_cast<const uint4*>(tid < 16 ? knew : vnew) + c;
-        uint4* dst = reinterpret_cast<uint4*>((tid < 16 ? kslab : vslab) + (int64_t)new_row * row_stride) + c;
+    // the step's new row also goes into the slab (nobody reads it from there in this launch):
+    // done by the wavefront whose range ends with the stream's last tile
+    if (new_row >= 0 && n_tiles > 0 && tile_b == stream_tiles && lane < 32) {
+        const int c = lane & 15;
+        const uint4* src = reinterpret_cast<const uint4*>(lane < 16 ? knew : vnew) + c;
+        uint4* dst = reinterpret_cast<uint4*>((lane < 16 ? kslab : vslab) + (int64_t)new_row * row_stride) + c;
         *dst = *src;
     }
 
@@ -198,90 +229,67 @@ __global__ __launch_bounds__(kThreads, DEPTH == 1 ? 3 : 2) void decode_mfma_kern
     f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = o0, o2 = o0, o3 = o0, o4 = o0, o5 = o0, o6 = o0, o7 = o0;
     float m_ref = -INFINITY, l_run = 0.f;  // m_ref: softmax reference (log2 units), uniform per head column
 
-    // no workgroup barrier in this loop: the LDS buffer is private to the wave, whose LDS
-    // operations execute in program order
-    for (int t = wave; t < n_tiles; t += DEPTH * kWaves) {
+    if (p.dbg && first_segment) t_first = wall_clock64();
+    // the LDS buffer is private to the wave, whose LDS operations execute in program order
+    for (int t = 0; t < n_tiles; t += DEPTH) {
         if (DEPTH == 1) {
             VS_PARK(a);
             VS_TILE(row_begin + t * TR, a);
-            if (t + kWaves < n_tiles) VS_FETCH(t + kWaves, a);
+            if (t + 1 < n_tiles) VS_FETCH(t + 1, a);
             continue;
         }
         if (MODE == 1) {  // experiment: consume the loads without computing
             o0[0] += __builtin_bit_cast(float, k0a.x ^ k1a.x ^ k2a.x ^ k3a.x ^ k4a.x ^ k5a.x ^ k6a.x ^ k7a.x ^ v0a.x ^ v1a.x ^ v2a.x ^ v3a.x ^ v4a.x ^ v5a.x ^ v6a.x ^ v7a.x);
-            if (t + 2 * kWaves < n_tiles) VS_FETCH(t + 2 * kWaves, a);
-            if (t + kWaves < n_tiles) {
+            if (t + 2 < n_tiles) VS_FETCH(t + 2, a);
+            if (t + 1 < n_tiles) {
                 o1[0] += __builtin_bit_cast(float, k0b.x ^ k1b.x ^ k2b.x ^ k3b.x ^ k4b.x ^ k5b.x ^ k6b.x ^ k7b.x ^ v0b.x ^ v1b.x ^ v2b.x ^ v3b.x ^ v4b.x ^ v5b.x ^ v6b.x ^ v7b.x);
-                if (t + 3 * kWaves < n_tiles) VS_FETCH(t + 3 * kWaves, b);
+                if (t + 3 < n_tiles) VS_FETCH(t + 3, b);
             }
             continue;
         }
         VS_PARK(a);
         VS_TILE(row_begin + t * TR, a);
-        if (t + 2 * kWaves < n_tiles) VS_FETCH(t + 2 * kWaves, a);
-        if (t + kWaves < n_tiles) {
+        if (t + 2 < n_tiles) VS_FETCH(t + 2, a);
+        if (t + 1 < n_tiles) {
             VS_PARK(b);
-            VS_TILE(row_begin + (t + kWaves) * TR, b);
-            if (t + 3 * kWaves < n_tiles) VS_FETCH(t + 3 * kWaves, b);
+            VS_TILE(row_begin + (t + 1) * TR, b);
+            if (t + 3 < n_tiles) VS_FETCH(t + 3, b);
         }
     }
+    if (p.dbg) t_loop = wall_clock64();
 
-    if (MODE == 2) {  // experiment: no merge, minimal output
-        if (o0[0] + l_run == 123.f) p.out[0] = (__bf16)o0[1];
-        return;
-    }
-    // ---- merge the 4 waves (one barrier: the merge buffer does not alias the V tiles).
-    //      lane (head = i16, kq) holds dims 16*db + 4*kq + e ----
+    // ---- this wavefront's result: lane (head = i16, kq) holds dims 16*db + 4*kq + e ----
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     if (i16 < p.G) {
-        float* dst = &sm_o[(wave * kMaxGroup + i16) * D + 4 * kq];
-        *reinterpret_cast<f32x4*>(dst + 0) = o0;
-        *reinterpret_cast<f32x4*>(dst + 16) = o1;
-        *reinterpret_cast<f32x4*>(dst + 32) = o2;
-        *reinterpret_cast<f32x4*>(dst + 48) = o3;
-        *reinterpret_cast<f32x4*>(dst + 64) = o4;
-        *reinterpret_cast<f32x4*>(dst + 80) = o5;
-        *reinterpret_cast<f32x4*>(dst + 96) = o6;
-        *reinterpret_cast<f32x4*>(dst + 112) = o7;
-        if (kq == 0) {
-            sm_ml[(wave * kMaxGroup + i16) * 2 + 0] = m_ref;
-            sm_ml[(wave * kMaxGroup + i16) * 2 + 1] = l_run;
-        }
-    }
-    __syncthreads();
-    const int64_t slot = (int64_t)s * p.max_chunks + chunk;
-    if (tid < p.G * (D / 4)) {  // one thread per (head, 4 dims)
-        const int h = tid / (D / 4), d4 = (tid - h * (D / 4)) * 4;
-        float mw[kWaves], mstar = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            mw[w] = sm_ml[(w * kMaxGroup + h) * 2];
-            mstar = fmaxf(mstar, mw[w]);
-        }
-        f32x4 num = {0.f, 0.f, 0.f, 0.f};
-        float den = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float wt = (mw[w] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw[w] - mstar);
-            num += *reinterpret_cast<const f32x4*>(&sm_o[(w * kMaxGroup + h) * D + d4]) * wt;
-            den += wt * sm_ml[(w * kMaxGroup + h) * 2 + 1];
-        }
-        if (n_chunks == 1) {
-            const float inv = 1.0f / den;
-            bf16x4 r;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) r[j] = (__bf16)(num[j] * inv);
-            *reinterpret_cast<bf16x4*>(&p.out[((int64_t)s * p.Hq + (int64_t)g * p.G + h) * D + d4]) = r;
+        const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
+        __bf16* dst;
+        if (whole_stream) {
+            dst = p.out + ((int64_t)s * p.Hq + (int64_t)g * p.G + i16) * D + 4 * kq;
         } else {
-            const int64_t pr = (slot * p.Hkv + g) * p.G + h;
-            *reinterpret_cast<f32x4*>(&p.part_o[pr * D + d4]) = num;
-            if (d4 == 0) {
-                p.part_ml[pr * 2 + 0] = mstar;
-                p.part_ml[pr * 2 + 1] = den;
+            const int64_t pr = ((((int64_t)blockIdx.x + s) * p.Hkv + g) * p.nsub + sub) * p.G + i16;
+            dst = p.part_o + pr * D + 4 * kq;
+            if (kq == 0) {
+                p.part_ml[pr * 2 + 0] = m_ref;
+                p.part_ml[pr * 2 + 1] = l_run;
             }
         }
+#define VS_OUT(ACC, DB)                                                                  \
+        do {                                                                             \
+            bf16x4 r_;                                                                   \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) r_[j] = (__bf16)(ACC[j] * inv); \
+            *reinterpret_cast<bf16x4*>(dst + 16 * (DB)) = r_;                            \
+        } while (0)
+        VS_OUT(o0, 0); VS_OUT(o1, 1); VS_OUT(o2, 2); VS_OUT(o3, 3);
+        VS_OUT(o4, 4); VS_OUT(o5, 5); VS_OUT(o6, 6); VS_OUT(o7, 7);
+#undef VS_OUT
     }
+    if (p.dbg && tid == 0) {
+        unsigned long long* d = p.dbg + (size_t)blockIdx.x * 4;
+        d[0] = t_start; d[1] = t_first; d[2] = t_loop; d[3] = wall_clock64();
+    }
+    flat = p.tile_prefix[s] + seg_b;  // next segment: the next stream
+  }
 }
 #undef VS_TILE_COMPUTE
 #undef VS_PV
@@ -293,70 +301,103 @@ __global__ __launch_bounds__(kThreads, DEPTH == 1 ? 3 : 2) void decode_mfma_kern
 #undef VS_PARK_ROW
 #undef VS_TILE
 
-// Merge of a stream's chunk partials (streams with a single chunk were written directly).
-// Grid (streams, query heads); thread = output dim.  The chunk loop is unrolled by 4 with all
-// loads issued before they are used, so the latency of one round trip covers four chunks.
-__global__ __launch_bounds__(D) void decode_combine_kernel(DecodeParams p) {
-    const int s = blockIdx.x, hq = blockIdx.y, d = threadIdx.x;
-    const int len = p.lens.v[s];
-    const int n_chunks = (len + p.chunk_rows - 1) / p.chunk_rows;
-    if (n_chunks == 1) return;
+// Merge of a stream's partials (a stream that one wavefront per head covered alone was written
+// directly).  Grid (streams, query heads), 128 threads = 8 groups x 16: a thread owns 8 output
+// dims and the partials group, group + 8, ..., all of them requested at once; the groups are
+// then merged through LDS.
+constexpr int kCombineGroups = 8, kCombineDepth = 8;
+__global__ __launch_bounds__(16 * kCombineGroups) void decode_combine_kernel(DecodeParams p) {
+    const int s = blockIdx.x, hq = blockIdx.y;
     const int g = hq / p.G, h = hq - g * p.G;
-    const int64_t cstride = (int64_t)p.Hkv * p.G;  // partial rows between consecutive chunks
-    const int64_t base = ((int64_t)s * p.max_chunks * p.Hkv + g) * p.G + h;
-    __shared__ float red[D / 64];
-    float mx = -INFINITY;
-    for (int c = d; c < n_chunks; c += D) mx = fmaxf(mx, p.part_ml[(base + c * cstride) * 2]);
+    const int tid = threadIdx.x, pg = tid >> 4, t = tid & 15, d8 = t * 8;
+    // largest w with wg_first_tile(w) <= tile
+    auto owner = [&](int tile) {
+        int w = (int)(((int64_t)tile * p.n_wg) / p.total_tiles);
+        while (w + 1 < p.n_wg && wg_first_tile(p, w + 1) <= tile) ++w;
+        while (w > 0 && wg_first_tile(p, w) > tile) --w;
+        return w;
+    };
+    const int w_first = owner(p.tile_prefix[s]), w_last = owner(p.tile_prefix[s + 1] - 1);
+    if (w_first == w_last && p.nsub == 1) return;
+    const int n_parts = (w_last - w_first + 1) * p.nsub;
+    // partial c of the stream: workgroup w_first + c / nsub, sub-range c % nsub
+    auto row_of = [&](int c) {
+        const int w = w_first + c / p.nsub, sub = c - (c / p.nsub) * p.nsub;
+        return ((((int64_t)w + s) * p.Hkv + g) * p.nsub + sub) * p.G + h;
+    };
+    float acc[8], den = 0.f, mref = -INFINITY;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    if ((d & 63) == 0) red[d >> 6] = mx;
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    for (int c0 = pg; c0 < n_parts; c0 += kCombineGroups * kCombineDepth) {
+        float m[kCombineDepth], l[kCombineDepth];
+        bf16x8 o[kCombineDepth];
+#pragma unroll
+        for (int u = 0; u < kCombineDepth; ++u) {
+            const int c = c0 + kCombineGroups * u;
+            m[u] = -INFINITY;
+            l[u] = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[u][j] = (__bf16)0.f;
+            if (c < n_parts) {
+                const int64_t pr = row_of(c);
+                m[u] = p.part_ml[pr * 2];
+                l[u] = p.part_ml[pr * 2 + 1];
+                o[u] = *reinterpret_cast<const bf16x8*>(p.part_o + pr * D + d8);
+            }
+        }
+        float mx = mref;
+#pragma unroll
+        for (int u = 0; u < kCombineDepth; ++u) mx = fmaxf(mx, m[u]);
+        if (mx == -INFINITY) continue;
+        const float sc = (mref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mref - mx);
+        den *= sc;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] *= sc;
+        mref = mx;
+#pragma unroll
+        for (int u = 0; u < kCombineDepth; ++u) {
+            const float wt = (m[u] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[u] - mx) * l[u];
+            den += wt;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += wt * (float)o[u][j];
+        }
+    }
+    __shared__ float sm_acc[kCombineGroups][16][8];
+    __shared__ float sm_md[kCombineGroups][16][2];
+    sm_md[pg][t][0] = mref;
+    sm_md[pg][t][1] = den;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm_acc[pg][t][j] = acc[j];
     __syncthreads();
-    const float mstar = fmaxf(red[0], red[1]);
-    float num = 0.f, den = 0.f;
-    int c = 0;
-    for (; c + 4 <= n_chunks; c += 4) {
-        float m4[4], l4[4], o4[4];
+    if (pg != 0) return;
+    float mstar = -INFINITY;
+    for (int i = 0; i < kCombineGroups; ++i) mstar = fmaxf(mstar, sm_md[i][t][0]);
+    float tot[8], dtot = 0.f;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t pr = base + (c + u) * cstride;
-            m4[u] = p.part_ml[pr * 2];
-            l4[u] = p.part_ml[pr * 2 + 1];
-            o4[u] = p.part_o[pr * D + d];
-        }
+    for (int j = 0; j < 8; ++j) tot[j] = 0.f;
+    for (int i = 0; i < kCombineGroups; ++i) {
+        const float mi = sm_md[i][t][0];
+        const float wt = (mi == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mi - mstar);
+        dtot += wt * sm_md[i][t][1];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float wt = __builtin_amdgcn_exp2f(m4[u] - mstar);
-            num += wt * o4[u];
-            den += wt * l4[u];
-        }
+        for (int j = 0; j < 8; ++j) tot[j] += wt * sm_acc[i][t][j];
     }
-    for (; c < n_chunks; ++c) {
-        const int64_t pr = base + c * cstride;
-        const float wt = __builtin_amdgcn_exp2f(p.part_ml[pr * 2] - mstar);
-        num += wt * p.part_o[pr * D + d];
-        den += wt * p.part_ml[pr * 2 + 1];
-    }
-    p.out[((int64_t)s * p.Hq + hq) * D + d] = (__bf16)(num / den);
+    const float inv = 1.0f / dtot;
+    bf16x8 r;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = (__bf16)(tot[j] * inv);
+    *reinterpret_cast<bf16x8*>(p.out + ((int64_t)s * p.Hq + hq) * D + d8) = r;
 }
 
-int pick_chunk_rows(const vs_shape& s, int n_streams, const LenTable& lens) {
-    if (g_tune_decode_chunk_rows) return g_tune_decode_chunk_rows;
-    int64_t total = 0;
-    for (int i = 0; i < n_streams; ++i) total += lens.v[i];
-    const int64_t target_groups = 1024;  // about four workgroups per compute unit
-    int64_t rows = (total * s.n_kv_heads) / target_groups;
-    rows -= rows % (TR * kWaves);
-    if (rows < TR * kWaves) rows = TR * kWaves;
-    if (rows > 4 * TR * kWaves) rows = 4 * TR * kWaves;
-    return (int)rows;
-}
+constexpr int kDecodeMaxWorkgroups = 1024;
 
 }  // namespace
 
-size_t decode_mfma_workspace_bytes(const vs_shape& s, int32_t n_streams, int32_t max_rows) {
-    const int64_t chunks_per_stream = (int64_t)max_rows / (TR * kWaves) + 1;
-    const int64_t slots = chunks_per_stream * n_streams;
-    return (size_t)(slots * s.n_q_heads * (D + 2) * sizeof(float));
+size_t decode_mfma_workspace_bytes(const vs_shape& s, int32_t n_streams, int32_t /*max_rows*/) {
+    const int G = s.n_q_heads / s.n_kv_heads;
+    const int per_slot = s.n_kv_heads < kWaves ? kWaves : s.n_kv_heads;  // Hkv * nsub
+    const int64_t rows = ((int64_t)kDecodeMaxWorkgroups + n_streams) * per_slot * G;
+    return (size_t)(rows * (D * sizeof(__bf16) + 2 * sizeof(float)));
 }
 
 hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab, void* v_slab,
@@ -375,22 +416,38 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     p.G = s.n_q_heads / s.n_kv_heads;
     p.Hq = s.n_q_heads;
     p.Hkv = s.n_kv_heads;
-    p.chunk_rows = pick_chunk_rows(s, n_streams, lens);
+    p.nh = s.n_kv_heads < kWaves ? s.n_kv_heads : kWaves;
+    while (kWaves % p.nh != 0) --p.nh;  // 1, 2 or 4 heads per workgroup
+    if (s.n_kv_heads % p.nh != 0) p.nh = 1;
+    p.nsub = kWaves / p.nh;
     p.scale_log2e = s.softmax_scale * kLog2e;
     p.lens = lens;
-    int max_len = 1;
-    for (int i = 0; i < n_streams; ++i) max_len = lens.v[i] > max_len ? lens.v[i] : max_len;
-    p.max_chunks = (max_len + p.chunk_rows - 1) / p.chunk_rows;
-    p.part_o = (float*)workspace;
-    p.part_ml = p.part_o + (int64_t)n_streams * p.max_chunks * s.n_q_heads * D;
-    const dim3 grid(p.max_chunks, s.n_kv_heads, n_streams);
+    p.tile_prefix[0] = 0;
+    for (int i = 0; i < n_streams; ++i) p.tile_prefix[i + 1] = p.tile_prefix[i] + (lens.v[i] + TR - 1) / TR;
+    for (int i = n_streams; i < kMaxStreamsPerLaunch; ++i) p.tile_prefix[i + 1] = 0x7fffffff;  // never "before" a tile
+    p.total_tiles = p.tile_prefix[n_streams];
+    // Shares of equal size in tiles, at most two workgroups per compute unit along x; the tuning
+    // knob gives the rows per share instead.
+    const int groups_y = s.n_kv_heads / p.nh;
+    const int max_x = 512 / groups_y;
+    int64_t tiles_per_wg = g_tune_decode_chunk_rows ? g_tune_decode_chunk_rows / TR : (p.total_tiles + max_x - 1) / max_x;
+    if (tiles_per_wg < p.nsub) tiles_per_wg = p.nsub;
+    int64_t n_wg = (p.total_tiles + tiles_per_wg - 1) / tiles_per_wg;
+    if (n_wg > kDecodeMaxWorkgroups) n_wg = kDecodeMaxWorkgroups;
+    if (n_wg < 1) n_wg = 1;
+    p.n_wg = (int)n_wg;
+    const int per_slot = s.n_kv_heads < kWaves ? kWaves : s.n_kv_heads;
+    const int64_t rows = ((int64_t)kDecodeMaxWorkgroups + n_streams) * per_slot * p.G;
+    p.part_ml = (float*)workspace;
+    p.part_o = (__bf16*)(p.part_ml + rows * 2);
+    p.dbg = g_tune_debug_mode == 7 ? (unsigned long long*)((char*)workspace + (12u << 20)) : nullptr;
+    const dim3 grid(p.n_wg, groups_y);
     if (g_tune_debug_mode == 1) decode_mfma_kernel<1, 2><<<grid, kThreads, 0, st>>>(p);
-    else if (g_tune_debug_mode == 2) decode_mfma_kernel<2, 2><<<grid, kThreads, 0, st>>>(p);
     else if (g_tune_debug_mode == 3) decode_mfma_kernel<0, 1><<<grid, kThreads, 0, st>>>(p);
     else decode_mfma_kernel<0, 2><<<grid, kThreads, 0, st>>>(p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.max_chunks == 1 || g_tune_skip_merge) return e;
-    decode_combine_kernel<<<dim3(n_streams, s.n_q_heads), D, 0, st>>>(p);
+    if (e != hipSuccess || g_tune_skip_merge) return e;
+    decode_combine_kernel<<<dim3(n_streams, s.n_q_heads), 16 * kCombineGroups, 0, st>>>(p);
     return hipGetLastError();
 }
 
