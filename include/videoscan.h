@@ -176,7 +176,7 @@ vs_status vs_carrier_mean_pool(const void *e, int32_t n, int32_t d, int32_t dtyp
  * the library's own choice.  Unknown knobs or out-of-range values: VS_ERR_SHAPE.
  *   VS_TUNE_PREFILL_SPLITS    workgroups sharing one row tile's keys, 1..32
  *   VS_TUNE_PREFILL_KV_GROUPS  key groups (sets of 4 wavefronts) per prefill workgroup, 1 or 2
- *   VS_TUNE_DECODE_CHUNK_ROWS rows per decode workgroup, a multiple of 128
+ *   VS_TUNE_DECODE_CHUNK_ROWS rows of a stream per decode workgroup share, a multiple of 32
  *   VS_TUNE_SKIP_MERGE        1 = do not launch the kernels that merge split results, so that
  *                             the attention kernels can be timed alone; outputs of calls whose
  *                             keys were split are then NOT written.  Measurement only.

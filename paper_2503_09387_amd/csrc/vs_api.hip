@@ -300,7 +300,7 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
             g_tune_prefill_kv_groups = value;
             return VS_OK;
         case VS_TUNE_DECODE_CHUNK_ROWS:
-            if (value % 128 != 0) return VS_ERR_SHAPE;
+            if (value % 32 != 0) return VS_ERR_SHAPE;
             g_tune_decode_chunk_rows = value;
             return VS_OK;
         case VS_TUNE_SKIP_MERGE:

@@ -252,21 +252,19 @@ void prefill_mfma_kernel(PrefillParams p) {
     // product has not been issued.  Commit its row sums, or, if a probability came out above
     // 2^8 (or overflowed), redo it exactly from the raw scores: reference refreshed from their
     // maximum, accumulators and sums rescaled, probabilities rebuilt.
-    // Sub-block 0 ran against the made-up reference 0: there an underflow (a lane that can see
-    // a key but whose sum vanished) also sends it to the exact pass, which then starts from no
-    // reference at all.
+    // A row that has accumulated nothing yet runs against the made-up reference 0: there an
+    // underflow (a lane that can see a key of the sub-block but whose sum vanished) also sends
+    // the sub-block to the exact pass, which treats such a row as having no reference at all.
     auto commit = [&](int n, float sum0, float sum1) {
-        bool redo = !(sum0 <= 256.f) || !(sum1 <= 256.f);
-        if (n == 0) {
-            const int jl = key0(0) + 4 * hi;  // this lane's smallest key
-            redo = redo || (jl <= jmax[0] && sum0 < 0x1p-40f) || (jl <= jmax[1] && sum1 < 0x1p-40f);
-        }
+        const int jl = key0(n) + 4 * hi;  // this lane's smallest key in the sub-block
+        const bool redo = !(sum0 <= 256.f) || !(sum1 <= 256.f) ||
+                          (l_run[0] == 0.f && jl <= jmax[0] && sum0 < 0x1p-40f) ||
+                          (l_run[1] == 0.f && jl <= jmax[1] && sum1 < 0x1p-40f);
         if (!__any(redo)) {
             l_run[0] += sum0;
             l_run[1] += sum1;
             return;
         }
-        if (n == 0) m_ref[0] = m_ref[1] = -INFINITY;
         const int par = n & 1, j0 = key0(n);
         float alpha[2];
 #pragma unroll
@@ -285,8 +283,9 @@ void prefill_mfma_kernel(PrefillParams p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) mx = fmaxf(mx, x[e]);
             mx = fmaxf(mx, xhalf(mx)) * p.scale_log2e;
-            const float m_new = fmaxf(m_ref[r], mx);
-            alpha[r] = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref[r] - m_new);
+            const float m_old = (l_run[r] + xhalf(l_run[r]) > 0.f) ? m_ref[r] : -INFINITY;  // the row's history
+            const float m_new = fmaxf(m_old, mx);
+            alpha[r] = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_old - m_new);
             m_ref[r] = m_new;
             const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;
             float sum = 0.f;
@@ -419,6 +418,7 @@ void prefill_mfma_kernel(PrefillParams p) {
 #undef VS_STEP
 #undef VS_STEP_MASKED
 
+    asm volatile("; pipeline registers free");  // marker for the listing check of the build
     const unsigned long long t_epi = p.dbg ? wall_clock64() : 0;
     f32x16 o[2][4];
     asm volatile(VS_ASM_READ_O
@@ -428,7 +428,10 @@ void prefill_mfma_kernel(PrefillParams p) {
                  : VS_CLOB_ACC);
     float l_tot[2];
 #pragma unroll
-    for (int r = 0; r < 2; ++r) l_tot[r] = l_run[r] + xhalf(l_run[r]);
+    for (int r = 0; r < 2; ++r) {
+        l_tot[r] = l_run[r] + xhalf(l_run[r]);
+        if (!(l_tot[r] > 0.f)) m_ref[r] = -INFINITY;  // nothing accumulated: the made-up reference must not count
+    }
 
     // ---- merge the key groups through LDS: group 1 hands (reference, sum, accumulator) to
     //      group 0, which holds the same rows in the same lanes ----

@@ -241,6 +241,28 @@ def test_prefill_result_does_not_depend_on_the_split(kv_groups):
         assert (o - outs[0]).abs().max().item() <= 2 ** -7 * outs[0].abs().max().item()
 
 
+@pytest.mark.parametrize("L", [130, 1500])
+@pytest.mark.parametrize("mode", ["all_low", "all_high", "rising", "falling", "jump"])
+def test_prefill_extreme_score_ranges(mode, L):
+    """Scaled scores far from 0 (in log2 units: around -400, around +400, climbing or falling by
+    400 along the keys, or jumping by 60 in the middle): the speculative softmax reference has to
+    be dropped and rebuilt, at the first sub-block and later ones, with the accumulators rescaled."""
+    s = QW
+    T = 170
+    hk, hv = cache_rows(21, s, L, 0.5)
+    q, kf, vf = frame_inputs(21, s, T, 0.5)
+    n = L + T
+    ramp = torch.arange(n, dtype=torch.float32) / n
+    a = {"all_low": torch.full((n,), -10.0), "all_high": torch.full((n,), 10.0), "rising": 10.0 * ramp,
+         "falling": -10.0 * ramp, "jump": 1.5 * (ramp > 0.5).float()}[mode]
+    # k_j += a_j * u, q += 10 * u with u = 0.5 * ones: score_j moves by 0.1275 * 10 * a_j * 32 log2 units
+    hk = (hk.float() + 0.5 * a[:L, None, None]).to(torch.bfloat16)
+    kf = (kf.float() + 0.5 * a[L:, None, None]).to(torch.bfloat16)
+    q = (q.float() + 5.0).to(torch.bfloat16)
+    out, _, _ = run_prefill(s, hk, hv, L, q, kf, vf)
+    check_close(out, oracle_prefill_rows(s, q, hk, hv, L, kf, vf), "bf16", f"{mode} L={L}")
+
+
 def test_prefill_uniform_scores_is_running_mean_at_full_size():
     """Q = 0: every row is the mean of its visible V rows (closed form, any size)."""
     s = QW
