@@ -26,7 +26,6 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-SLEEP_CYCLES = 20_000_000   # ~10 ms spin kernel that lets the host queue a batch of launches behind it
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark's
 # kernels (profiles/*.md), scaled by what the same counters read for a plain 1 GiB copy
@@ -145,25 +144,14 @@ def main():
         st = vs.current_stream_handle()
         frames_in = [[(qp[f, l], kp[f, l], vp[f, l]) for l in range(NL)] for f in range(POOL_FRAMES)]
 
-        def run_frames(n, timed_calls=None):
+        def run_frames(n, pool=True):
             for f in range(n):
                 fin = frames_in[f % POOL_FRAMES]
-                timed = timed_calls is not None and (f % 8 == 0)
-                if timed:
-                    # keep the GPU busy while this frame's launches and events are queued, so that
-                    # the events bracket kernel execution and not the host's launch latency
-                    torch.cuda._sleep(SLEEP_CYCLES)
-                vs.carrier_mean_pool(ep[f % POOL_FRAMES], carrier_emb, "bf16", stream=st)
+                if pool:
+                    vs.carrier_mean_pool(ep[f % POOL_FRAMES], carrier_emb, "bf16", stream=st)
                 for l in range(NL):
                     q_, k_, v_ = fin[l]
-                    if timed:
-                        a, b = event_pair()
-                        a.record()
-                        vs.frame_prefill_compact(sh, caches[l], q_, k_, v_, out, ws, stream=st)
-                        b.record()
-                        timed_calls.append((a, b, caches[l].len - 1))
-                    else:
-                        vs.frame_prefill_compact(sh, caches[l], q_, k_, v_, out, ws, stream=st)
+                    vs.frame_prefill_compact(sh, caches[l], q_, k_, v_, out, ws, stream=st)
 
         def reset():
             for cch in caches:
@@ -182,38 +170,43 @@ def main():
         wall = time.perf_counter() - t0
         gpu_ms = ev0.elapsed_time(ev1)
         assert all(cch.len == P0 + K for cch in caches)
-        # second and third pass: HIP events (on the launch stream) around every call of every 8th
-        # frame; first the whole call, then with the split-merge kernel switched off so that the
-        # events bracket the attention kernel alone (what rocprofv3 reports per kernel)
-        reset()
-        calls = []
-        run_frames(K, calls)
-        torch.cuda.synchronize()
-        call_durs = np.array([a.elapsed_time(b) * 1e-3 for a, b, _ in calls])
+        # Second pass, for the roofline of the dominant kernel: the same K x 28 launches with the
+        # split-merge kernel and the mean pool switched off, so that the stream holds nothing but
+        # attention kernels back to back; HIP events on the launch stream around the whole run,
+        # divided by the number of launches.  (Events around single launches read 3-6 us more
+        # than the kernel's own start-to-end time; a run of launches back to back reads what
+        # rocprofv3 --kernel-trace reports as the average duration, plus the dispatch gap.)
         vs.set_tuning(vs.TUNE_SKIP_MERGE, 1)
         reset()
-        calls = []
-        run_frames(K, calls)
+        run_frames(min(W, 4), pool=False)
+        reset()
+        ka, kb = event_pair()
+        torch.cuda.synchronize()
+        ka.record()
+        run_frames(K, pool=False)
+        kb.record()
         torch.cuda.synchronize()
         vs.set_tuning(vs.TUNE_SKIP_MERGE, 0)
-        durs = np.array([a.elapsed_time(b) * 1e-3 for a, b, _ in calls])
-        fl = np.array([prefill_flops(s, L, T) for _, _, L in calls], dtype=np.float64)
-        by = np.array([prefill_bytes(s, L, T) for _, _, L in calls], dtype=np.float64)
-        achieved = float(fl.sum() / durs.sum() / 1e12)
+        n_launch = K * NL
+        launch_s = ka.elapsed_time(kb) * 1e-3 / n_launch
+        fl = np.array([prefill_flops(s, P0 + f, T) for f in range(K)], dtype=np.float64)
+        by = np.array([prefill_bytes(s, P0 + f, T) for f in range(K)], dtype=np.float64)
+        achieved = float(fl.mean() / launch_s / 1e12)
         stream_out = dict(
             value=K / wall, ms_per_step=wall * 1e3 / K, gpu_ms_per_step=gpu_ms / K,
             roofline=dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                           frac=achieved / PEAK_BF16_TFLOPS,
                           traffic=TRAFFIC.get("prefill_mfma_kernel"),
-                          kernel="prefill_mfma_kernel<2> (attention + fused carrier compaction), timed alone",
-                          avg_launch_us=float(durs.mean() * 1e6), launches_timed=len(calls),
-                          whole_call_us=float(call_durs.mean() * 1e6),
-                          whole_call_tflops=float(fl.sum() / call_durs.sum() / 1e12),
+                          kernel="prefill_mfma_kernel<2> (attention + fused carrier compaction)",
+                          avg_launch_us=float(launch_s * 1e6), launches_timed=n_launch,
+                          timing="HIP events on the launch stream around K x 28 attention launches back to back "
+                                 "(merge kernel and mean pool off), divided by the number of launches",
+                          layer_period_us=float(gpu_ms * 1e3 / n_launch),
                           algorithmic_gflop_per_launch=float(fl.mean() / 1e9),
                           algorithmic_mbytes_per_launch=float(by.mean() / 1e6)))
-        log(f"[bench] cfg3: {K / wall:.1f} frames/s, {wall * 1e3 / K:.3f} ms/frame; attention kernel "
-            f"{durs.mean() * 1e6:.1f} us = {achieved:.1f} TFLOP/s ({100 * achieved / PEAK_BF16_TFLOPS:.1f}% of bf16 "
-            f"peak); whole call {call_durs.mean() * 1e6:.1f} us")
+        log(f"[bench] cfg3: {K / wall:.1f} frames/s, {wall * 1e3 / K:.3f} ms/frame ({gpu_ms * 1e3 / n_launch:.1f} us per "
+            f"layer); attention kernel {launch_s * 1e6:.1f} us = {achieved:.1f} TFLOP/s "
+            f"({100 * achieved / PEAK_BF16_TFLOPS:.1f}% of bf16 peak)")
         del qp, kp, vp
 
     # ------------------------------------------------------------------ CPU baseline (oracle)
@@ -273,43 +266,38 @@ def main():
         st4 = vs.current_stream_handle()
         steps_in = [[(dq[t, l], dk[t, l], dv[t, l]) for l in range(NL4)] for t in range(steps)]
 
-        def run_decode(n, lens, timed_calls=None):
+        def run_decode(n, lens):
             for t in range(n):
-                timed = timed_calls is not None and (t % 4 == 0)
-                if timed:
-                    torch.cuda._sleep(SLEEP_CYCLES)
                 for l in range(NL4):
                     q_, k_, v_ = steps_in[t][l]
-                    if timed:
-                        a, b = event_pair()
-                        a.record()
-                        vs.decode_attn(sh4, slabs[l][0], slabs[l][1], lens[l], q_, k_, v_, dout, ws4, stream=st4)
-                        b.record()
-                        timed_calls.append((a, b, list(lens[l])))
-                    else:
-                        vs.decode_attn(sh4, slabs[l][0], slabs[l][1], lens[l], q_, k_, v_, dout, ws4, stream=st4)
+                    vs.decode_attn(sh4, slabs[l][0], slabs[l][1], lens[l], q_, k_, v_, dout, ws4, stream=st4)
 
         run_decode(min(4, steps), fresh_lens())
         torch.cuda.synchronize()
         lens = fresh_lens()
+        ev0, ev1 = event_pair()
         t0 = time.perf_counter()
+        ev0.record()
         run_decode(steps, lens)
+        ev1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        gpu_ms4 = ev0.elapsed_time(ev1)
         assert all(list(lens[l]) == [n + steps for n in lens0] for l in range(NL4))
-        calls = []
-        run_decode(steps, fresh_lens(), calls)
-        torch.cuda.synchronize()
-        call_durs = np.array([a.elapsed_time(b) * 1e-3 for a, b, _ in calls])
-        # restore the slabs' appended rows do not matter for timing; time the attention kernel alone
+        # roofline pass: the same launches with the merge kernel off, attention kernels back to back
         vs.set_tuning(vs.TUNE_SKIP_MERGE, 1)
-        calls = []
-        run_decode(steps, fresh_lens(), calls)
+        run_decode(min(4, steps), fresh_lens())
+        ka, kb = event_pair()
+        torch.cuda.synchronize()
+        ka.record()
+        run_decode(steps, fresh_lens())
+        kb.record()
         torch.cuda.synchronize()
         vs.set_tuning(vs.TUNE_SKIP_MERGE, 0)
-        durs = np.array([a.elapsed_time(b) * 1e-3 for a, b, _ in calls])
-        by = np.array([decode_bytes(s4, la) for _, _, la in calls], dtype=np.float64)
-        gbs = float(by.sum() / durs.sum() / 1e9)
+        n_launch4 = steps * NL4
+        launch_s4 = ka.elapsed_time(kb) * 1e-3 / n_launch4
+        by = np.array([decode_bytes(s4, [n + t + 1 for n in lens0]) for t in range(steps)], dtype=np.float64)
+        gbs = float(by.mean() / launch_s4 / 1e9)
         decode_out = dict(
             metric="decode tokens/sec (16 ragged streams x 28 layers)", value=S * steps / wall, unit="tok/s",
             ms_per_step=wall * 1e3 / steps, steps=steps,
@@ -317,14 +305,15 @@ def main():
                                 "4 distinct layer slabs drawn on the host, copied to the 28 layers"},
             roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS,
                           traffic=TRAFFIC.get("decode_mfma_kernel"),
-                          kernel="decode_mfma_kernel (attention + fused append of the new row), timed alone",
-                          avg_launch_us=float(durs.mean() * 1e6), launches_timed=len(calls),
-                          whole_call_us=float(call_durs.mean() * 1e6),
-                          whole_call_gbs=float(by.sum() / call_durs.sum() / 1e9),
+                          kernel="decode_mfma_kernel (attention + fused append of the new row)",
+                          avg_launch_us=float(launch_s4 * 1e6), launches_timed=n_launch4,
+                          timing="HIP events on the launch stream around steps x 28 attention launches back to "
+                                 "back (merge kernel off), divided by the number of launches",
+                          layer_period_us=float(gpu_ms4 * 1e3 / n_launch4),
                           algorithmic_mbytes_per_launch=float(by.mean() / 1e6)))
-        log(f"[bench] cfg4: {S * steps / wall:.0f} tok/s, {wall * 1e3 / steps:.3f} ms/step; attention kernel "
-            f"{durs.mean() * 1e6:.1f} us = {gbs:.0f} GB/s ({100 * gbs / PEAK_HBM_GBS:.1f}% of HBM peak); whole call "
-            f"{call_durs.mean() * 1e6:.1f} us")
+        log(f"[bench] cfg4: {S * steps / wall:.0f} tok/s, {wall * 1e3 / steps:.3f} ms/step ({gpu_ms4 * 1e3 / n_launch4:.1f} us "
+            f"per layer); attention kernel {launch_s4 * 1e6:.1f} us = {gbs:.0f} GB/s "
+            f"({100 * gbs / PEAK_HBM_GBS:.1f}% of HBM peak)")
         if "cpu" in parts:
             import oracle
             t_tot = 0.0

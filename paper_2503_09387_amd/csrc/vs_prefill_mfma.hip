@@ -207,6 +207,7 @@ void prefill_mfma_kernel(PrefillParams p) {
             for (int kk = 0; kk < 8; ++kk)
                 qf[r][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * hi);
         }
+        asm volatile(VS_ASM_INIT_O : : : VS_CLOB_ACC);  // while the loads above are under way
         asm volatile(VS_ASM_LOAD_Q
                      :
                      : "{v[128:131]}"(qf[0][0]), "{v[132:135]}"(qf[0][1]), "{v[136:139]}"(qf[0][2]), "{v[140:143]}"(qf[0][3]),
@@ -215,7 +216,6 @@ void prefill_mfma_kernel(PrefillParams p) {
                        "{v[176:179]}"(qf[1][4]), "{v[180:183]}"(qf[1][5]), "{v[184:187]}"(qf[1][6]), "{v[188:191]}"(qf[1][7])
                      : VS_CLOB_ACC);
     }
-    asm volatile(VS_ASM_INIT_O : : : VS_CLOB_ACC);
 
     float m_ref[2] = {-INFINITY, -INFINITY};  // softmax reference (log2 units)
     float l_run[2] = {0.f, 0.f};              // this lane's share of the row sum
@@ -433,55 +433,9 @@ void prefill_mfma_kernel(PrefillParams p) {
         if (!(l_tot[r] > 0.f)) m_ref[r] = -INFINITY;  // nothing accumulated: the made-up reference must not count
     }
 
-    // ---- merge the key groups through LDS: group 1 hands (reference, sum, accumulator) to
-    //      group 0, which holds the same rows in the same lanes ----
-    if (NKG > 1) {
-        __syncthreads();  // all tiles consumed, the stage buffers are free
-        float* xo = reinterpret_cast<float*>(dyn_smem);  // [2 waves][32 x f32x4][64 lanes]
-        float* xml = xo + 2 * 32 * 64 * 4;               // [2 waves][2 row groups][32 rows][2]
-        if (kg == 1) {
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int e4 = 0; e4 < 4; ++e4) {
-                        f32x4 wv;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) wv[j] = o[r][db][4 * e4 + j];
-                        *reinterpret_cast<f32x4*>(&xo[(((rb * 2 + r) * 16 + db * 4 + e4) * 64 + lane) * 4]) = wv;
-                    }
-                if (hi == 0) {
-                    xml[((rb * 2 + r) * 32 + l32) * 2 + 0] = m_ref[r];
-                    xml[((rb * 2 + r) * 32 + l32) * 2 + 1] = l_tot[r];
-                }
-            }
-        }
-        __syncthreads();
-        if (kg == 1) return;
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const float m1 = xml[((rb * 2 + r) * 32 + l32) * 2 + 0], l1 = xml[((rb * 2 + r) * 32 + l32) * 2 + 1];
-            const float m_new = fmaxf(m_ref[r], m1);
-            const float a0 = (m_ref[r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_ref[r] - m_new);
-            const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - m_new);
-            m_ref[r] = m_new;
-            l_tot[r] = l_tot[r] * a0 + l1 * a1;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const f32x4 wv = *reinterpret_cast<const f32x4*>(&xo[(((rb * 2 + r) * 16 + db * 4 + e4) * 64 + lane) * 4]);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) o[r][db][4 * e4 + j] = o[r][db][4 * e4 + j] * a0 + wv[j] * a1;
-                }
-        }
-    }
-
-    // ---- output: lane (q = l32, hi) holds dims 32*db + 8*(e>>2) + 4*hi + (e&3) ----
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        const float inv = (l_tot[r] > 0.f) ? 1.0f / l_tot[r] : 0.f;
+    // ---- output of one row group: lane (q = l32, hi) holds dims 32*db + 8*(e>>2) + 4*hi + (e&3) ----
+    auto emit = [&](int r, const f32x16 (&oo)[4], float m_row, float l_row) {
+        const float inv = (l_row > 0.f) ? 1.0f / l_row : 0.f;
         const int rg = rb * 2 + r;  // 32-row group inside the row tile
         if (p.nsplit == 1) {
             if (r_mine[r] < p.M) {
@@ -493,7 +447,7 @@ void prefill_mfma_kernel(PrefillParams p) {
                     for (int e4 = 0; e4 < 4; ++e4) {
                         bf16x4 wv;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) wv[j] = (__bf16)(o[r][db][4 * e4 + j] * inv);
+                        for (int j = 0; j < 4; ++j) wv[j] = (__bf16)(oo[db][4 * e4 + j] * inv);
                         *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * e4 + 4 * hi) = wv;
                     }
             }
@@ -507,15 +461,61 @@ void prefill_mfma_kernel(PrefillParams p) {
                 for (int h2 = 0; h2 < 2; ++h2) {
                     bf16x8 wv;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) wv[j] = (__bf16)(o[r][db][8 * h2 + j] * inv);
+                    for (int j = 0; j < 8; ++j) wv[j] = (__bf16)(oo[db][8 * h2 + j] * inv);
                     __builtin_nontemporal_store(wv, &po[(db * 2 + h2) * 64]);
                 }
             if (hi == 0) {
                 const int64_t prow = (int64_t)c * p.m_pad + r_mine[r];
-                p.part_ml[prow * 2 + 0] = m_ref[r];
-                p.part_ml[prow * 2 + 1] = l_tot[r];
+                p.part_ml[prow * 2 + 0] = m_row;
+                p.part_ml[prow * 2 + 1] = l_row;
             }
         }
+    };
+
+    if (NKG == 1) {
+        emit(0, o[0], m_ref[0], l_tot[0]);
+        emit(1, o[1], m_ref[1], l_tot[1]);
+    } else {
+        // ---- merge the key groups through LDS.  The two wavefronts that hold the same 64 rows
+        //      (same lanes) swap halves: the wavefront of key group kg keeps row group kg, hands
+        //      the other one over, and finishes its own, so the closing work is shared. ----
+        __syncthreads();  // all tiles consumed, the stage buffers are free
+        float* xo = reinterpret_cast<float*>(dyn_smem);  // [4 waves][16 x f32x4][64 lanes]
+        float* xml = xo + 4 * 16 * 64 * 4;               // [4 waves][32 rows][2]
+        auto hand_over = [&](int r) {
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    f32x4 wv;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) wv[j] = o[r][db][4 * e4 + j];
+                    *reinterpret_cast<f32x4*>(&xo[((w * 16 + db * 4 + e4) * 64 + lane) * 4]) = wv;
+                }
+            if (hi == 0) {
+                xml[(w * 32 + l32) * 2 + 0] = m_ref[r];
+                xml[(w * 32 + l32) * 2 + 1] = l_tot[r];
+            }
+        };
+        auto take_over = [&](int r) {
+            const int pw = w ^ 2;  // the partner: same rows, other key group
+            const float m1 = xml[(pw * 32 + l32) * 2 + 0], l1 = xml[(pw * 32 + l32) * 2 + 1];
+            const float m_new = fmaxf(m_ref[r], m1);
+            const float a0 = (m_ref[r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_ref[r] - m_new);
+            const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - m_new);
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const f32x4 wv = *reinterpret_cast<const f32x4*>(&xo[((pw * 16 + db * 4 + e4) * 64 + lane) * 4]);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) o[r][db][4 * e4 + j] = o[r][db][4 * e4 + j] * a0 + wv[j] * a1;
+                }
+            emit(r, o[r], m_new, l_tot[r] * a0 + l1 * a1);
+        };
+        if (kg == 0) hand_over(1); else hand_over(0);
+        __syncthreads();
+        if (kg == 0) take_over(0); else take_over(1);
     }
     if (p.dbg && tid == 0) {
         unsigned long long* d = p.dbg + (size_t)blockIdx.x * 4;
