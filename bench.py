@@ -31,9 +31,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # kernels (profiles/*.md), scaled by what the same counters read for a plain 1 GiB copy
 # (FETCH_SIZE x2.0, WRITE_SIZE x1.0).  Static because counters cannot be read inside a timed run.
 TRAFFIC = {
-    "prefill_mfma_kernel": None,
-    "decode_mfma_kernel": {"fetch_bytes": 159.2e6, "write_bytes": 4.56e6,
-                           "note": "cfg4 launch shape, algorithmic 159.4e6 bytes"},
+    "prefill_mfma_kernel": {"fetch_bytes": 13.63e6, "write_bytes": 8.11e6,
+                            "note": "cfg3 launch shape; algorithmic 11.84e6 bytes; the writes are the bf16 "
+                                    "partial results of the 6 key splits (7.9e6), merged by the second kernel"},
+    "decode_mfma_kernel": {"fetch_bytes": 159.5e6, "write_bytes": 3.72e6,
+                           "note": "cfg4 launch shape; algorithmic 159.4e6 bytes; the writes are the bf16 "
+                                   "partial results of the wavefronts and the appended rows"},
 }
 
 
@@ -84,7 +87,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--decode-steps", type=int, default=64)
     ap.add_argument("--parts", default="all",
-                    help="comma list of: stream,decode,cfg2,cfg5,compaction,cpu (default all)")
+                    help="comma list of: stream,decode,cfg2,cfg5,compaction,cpu (default all); "
+                         "calib = only a 1 GiB device copy, the known-size kernel that the HBM "
+                         "counters of a rocprofv3 --pmc run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -102,6 +107,16 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     result = {}
+
+    if "calib" in parts:
+        n = 1 << 30
+        a = torch.full((n,), 1, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(4):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calib": "4 device copies of 1 GiB (read 1 GiB, write 1 GiB each)"}))
+        return
 
     def shape_of(s):
         return vs.Shape.make(s.n_q_heads, s.n_kv_heads, s.head_dim, s.dtype, s.scale)
