@@ -9,11 +9,13 @@ instruction from hand-scheduled blocks of inline assembly:
               (the compiler never sees these two as values; every block lists them as
               clobbered, which keeps it from holding anything of its own there across a block)
   v[128:191]  raw scores S[parity][row_group], 16 registers each: sub-block n (32 keys) of a
-              key group uses parity n & 1; passed in and out of the blocks as pinned operands
+              key group uses parity n & 1; hidden from the compiler like the accumulators (the
+              blocks list them as clobbered; the rare exact redo of a sub-block fetches them
+              through an empty asm statement with a pinned output)
   v[192:207]  four buffers for K / V^T fragments read from LDS
   v[208:215]  temporaries and constants
-  v[216:247]  packed bf16 probabilities P[parity][row_group][step], 4 registers each, pinned
-              operands like S
+  v[216:247]  packed bf16 probabilities P[parity][row_group][step], 4 registers each, hidden
+              state like S
 
 Everything else (addresses, softmax reference, scale, row sums) reaches a block as an ordinary
 named operand.

@@ -4,25 +4,35 @@
 // Work layout
 //   * The G = Hq/Hkv query heads of one KV head are packed into one row dimension:
 //     packed row r = t*G + hl (token-major), M = T*G rows per KV head.  A row tile is
-//     BM = 128 rows: 4 wavefronts ("row group"), 32 rows each.
+//     BM = 128 rows: two wavefronts of 64 rows each (two "row groups" of 32 per wavefront,
+//     so that every K / V^T fragment read from LDS feeds two matrix instructions).
 //   * Keys are the virtual sequence [len cache rows | T frame rows]; row t sees keys
-//     j <= len + t.  The sequence is walked in tiles of 64 keys staged through LDS,
-//     double-buffered (one barrier per tile) with the next tile's global loads in flight in
-//     registers.
+//     j <= len + t.  The sequence is walked in tiles of 64 keys.  A tile goes from global
+//     memory straight into LDS (global_load_lds_dwordx4, no registers in between) into a ring
+//     of two K and two V tiles per key group; the 16-byte pieces of a row are stored at a
+//     slot permuted by the row number so that both the row-wise K reads and the transposing
+//     V reads are free of bank conflicts without padding.  One barrier per tile.
 //   * Too few rows exist to fill 256 compute units, so the key tiles a row tile can see are
-//     split twice: across `nsplit` workgroups, and inside a workgroup across KVG "key
-//     groups" of 4 wavefronts each that take alternate tiles and are merged through LDS at
-//     the end.  With KVG = 2 a workgroup has 8 wavefronts (2 per SIMD) and the number of
-//     partial results that must travel through memory halves.  The per-workgroup partials
-//     (reference, sum, normalised accumulator in bf16) are merged by a second small kernel.
+//     split twice: across `nsplit` workgroups (shares weighted by cost: a tile with frame
+//     rows counts double), and inside a workgroup across NKG "key groups" of two wavefronts
+//     that take alternate tiles and are merged through LDS at the end (each group closes one
+//     half of the rows).  One wavefront per SIMD: it owns all 512 registers.  The
+//     per-workgroup partials (reference, sum, normalised accumulator in bf16) are merged by
+//     a second small kernel.
 //   * Scores are computed transposed, S^T = K Q^T (v_mfma_f32_32x32x16_bf16), so that a
 //     lane owns one query column: softmax statistics stay in the lane, and the
 //     probabilities are already laid out as the B operand of O^T += V^T P^T.  V^T comes
 //     out of row-major LDS through the transposing read ds_read_b64_tr_b16.
-//   * Softmax uses a stale reference: probabilities are first computed against the reference
-//     left by earlier tiles (no maximum, no rescale); only if one of them comes out above
-//     2^8, or a row has no reference yet, are the scores recomputed, the true maximum taken
-//     and the accumulators rescaled.  After the first tile that is rare.
+//   * The matrix instructions, the LDS reads that feed them and the softmax arithmetic are
+//     issued from generated blocks of inline assembly over fixed registers, as a software
+//     pipeline over sub-blocks of 32 keys: scores of sub-block n+1, value product of n-1 and
+//     softmax of n in one block, the ordinary instructions dealt out one by one behind the
+//     matrix instructions (gen_prefill_asm.py documents registers and hazards).
+//   * Softmax uses a stale reference: probabilities are computed against the reference
+//     left by earlier sub-blocks (for the first: against 0); no maximum, no rescale.  Only if
+//     a row sum comes out above 2^8, or a row without history underflows, is the sub-block
+//     redone exactly from its raw scores (true maximum, accumulators rescaled).  After the
+//     first sub-block that is rare.
 //   * Workgroup id = row_tile * (nsplit*Hkv) + (split*Hkv + kv_head): with nsplit*Hkv a
 //     multiple of 8, all workgroups that read one K/V slice run on one XCD (ids are
 //     dealt round-robin to the 8 XCDs) and share its L2.

@@ -20,9 +20,10 @@ DEV = "cuda:0"
 #     on average   mean|err| <= 5e-3 rms(ref)
 #   Error model behind them.  Three roundings to bf16 (8 significand bits, uniform in
 #   +-2^-9 |x|, std 1.13e-3 |x|) touch every output: (1) the output itself; (2) P before
-#   P.V, while the softmax denominator sums the unrounded P: as noise ~1.1e-3 rms, and when
-#   the probabilities are nearly equal their roundings line up and shift the row by up to
-#   2^-9 |x|; (3) when the keys are split over workgroups, each normalised partial result
+#   P.V (the prefill kernel sums the rounded P for the denominator, the decode kernel the
+#   unrounded P): as noise ~1.1e-3 rms, and when the probabilities are nearly equal their
+#   roundings line up and, where the denominator does not share them, shift the row by up
+#   to 2^-9 |x|; (3) when the keys are split over workgroups, each normalised partial result
 #   on its way through memory: nsplit independent terms, each weighted ~1/nsplit but
 #   ~sqrt(nsplit) larger than the final output, together again ~1.1e-3 rms.  Sum: a
 #   systematic part <= 2^-8 |x| and noise of std ~2e-3..2.5e-3 rms (measured mean|err| =
