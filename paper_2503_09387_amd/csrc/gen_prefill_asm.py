@@ -34,6 +34,8 @@ Scheduling rules the blocks obey (gfx950, one wavefront per SIMD):
     before its pair (LDS returns in order; a block starts with lgkmcnt(0));
   * ordinary instructions never read a matrix result inside the block that computes it, except
     after an explicit run of s_nop (an 8-pass instruction needs 11 idle issue slots);
+  * a memory instruction reads a scalar register no earlier than five issue slots after a scalar
+    instruction wrote it (the staging loads step their base address in s[88:91]);
   * a transcendental result is not read by the next instruction; a mask written by a compare
     is not read by the next two; a dot-product result is read by other kinds of instruction no
     earlier than three instructions later; M0 is not used by the instruction after the one that
@@ -87,8 +89,27 @@ class Block:
         return " \\\n".join('    "' + l + '\\n\\t"' for l in self.lines)
 
 
-def step(p, qk, pv, sm, masked=False, loads=False):
-    """One pipeline step of parity p: any of QK(n+1), PV(n-1), SM(n)."""
+def emit_stage_load(b, u, settle=False):
+    """Staging load of this wave: chunk u of a K tile (u < 8) or chunk u-8 of a V tile, 16 bytes per
+    lane straight into LDS; s[88:89] / s[90:91] walk the global rows (4 rows per chunk), M0 holds
+    the LDS destination.  A memory instruction must not read a scalar register earlier than five
+    issue slots after a scalar instruction wrote it: inside the pipeline blocks the matrix and
+    softmax instructions between two loads provide that, elsewhere `settle` adds the idle slots."""
+    which, base = ("k", 88) if u < 8 else ("v", 90)
+    b.emit(f"s_mov_b32 m0, %[lds{which}]")
+    b.emit(f"s_add_u32 %[lds{which}], %[lds{which}], 0x400")
+    if settle:
+        b.emit("s_nop 3")
+    off = f"%[kso{u & 3}]" if which == "k" else "%[vso]"
+    b.emit(f"global_load_lds_dwordx4 {off}, s[{base}:{base + 1}]")
+    b.emit(f"s_add_u32 s{base}, s{base}, %[stride]")
+    b.emit(f"s_addc_u32 s{base + 1}, s{base + 1}, 0")
+
+
+def step(p, qk, pv, sm, masked=False, loads=()):
+    """One pipeline step of parity p: any of QK(n+1), PV(n-1), SM(n).  `loads` lists the staging
+    chunks this wave requests on the way, one behind each of the first pairs of matrix
+    instructions."""
     b = Block()
     b.emit("s_waitcnt lgkmcnt(0)")
     half = 1 - p  # both matrix products work on half 1-p of their staged tiles
@@ -158,17 +179,8 @@ def step(p, qk, pv, sm, masked=False, loads=False):
             t, j = divmod(e, 8)
             b.emit(f"v_dot2c_f32_bf16_e32 %[sum{r}], v{P(p, r, t) + j // 2}, v{ONES}")
 
-    # ---- staging loads of this wave: chunk u of the K tile (u < 8) or chunk u-8 of the V tile,
-    # 16 bytes per lane straight into LDS; s[88:89] / s[90:91] walk the global rows (4 rows per
-    # chunk), M0 holds the LDS destination
     def stage_load(u):
-        which, base = ("k", 88) if u < 8 else ("v", 90)
-        b.emit(f"s_mov_b32 m0, %[lds{which}]")
-        b.emit(f"s_add_u32 %[lds{which}], %[lds{which}], 0x400")
-        off = f"%[kso{u & 3}]" if which == "k" else "%[vso]"
-        b.emit(f"global_load_lds_dwordx4 {off}, s[{base}:{base + 1}]")
-        b.emit(f"s_add_u32 s{base}, s{base}, %[stride]")
-        b.emit(f"s_addc_u32 s{base + 1}, s{base + 1}, 0")
+        emit_stage_load(b, u, settle=not sm)  # without softmax work the loads follow each other closely
 
     # ---- schedule
     n_pairs = len(plan)
@@ -207,8 +219,8 @@ def step(p, qk, pv, sm, masked=False, loads=False):
             if r == 0 and issued < n_pairs:
                 cnt[issued] = frag_read(issued)
                 issued += 1
-            if r == 1 and loads and j < 16:
-                stage_load(j)
+            if r == 1 and j < len(loads):
+                stage_load(loads[j])
             q = 2 * j + r
             b.lines += stream[pos:pos + take[q]]
             pos += take[q]
@@ -223,16 +235,24 @@ def step(p, qk, pv, sm, masked=False, loads=False):
 
 
 def init_o():
+    """O = 0: eight matrix instructions with zero operands write the 128 accumulator registers."""
     b = Block()
-    for i in range(128):
-        b.emit(f"v_accvgpr_write_b32 a{i}, 0")
+    for k in range(4):
+        b.emit(f"v_mov_b32_e32 v{TMP + k}, 0")
+    b.emit("s_nop 1")
+    for i in range(8):
+        b.emit(f"{MFMA} a[{16 * i}:{16 * i + 15}], {vr(TMP, 4)}, {vr(TMP, 4)}, 0")
     return b
 
 
 def load_q():
+    """Query fragments straight from global memory into a[128:191]: per row group one address
+    (row, 8*hi elements in), fragment kk lies 32*kk bytes further."""
     b = Block()
-    for i in range(64):
-        b.emit(f"v_accvgpr_write_b32 a{128 + i}, v{128 + i}")
+    for r in range(2):
+        for kk in range(8):
+            i = 128 + 4 * (8 * r + kk)
+            b.emit(f"global_load_dwordx4 a[{i}:{i + 3}], %[qa{r}], off offset:{32 * kk}")
     return b
 
 
@@ -271,11 +291,13 @@ def main(out_path):
     blocks = {
         # name: step(parity, qk, pv, sm, masked, loads)
         "VS_ASM_QK0": step(1, True, False, False),                 # QK into S[0] (a group's first sub-block)
+        "VS_ASM_QK0_LOADS": step(1, True, False, False, loads=range(8)),      # ... requesting a K tile
         "VS_ASM_FIRST": step(0, True, False, True),                # step 0: QK(1), SM(0)
+        "VS_ASM_FIRST_LOADS": step(0, True, False, True, loads=range(8, 16)),  # ... requesting a V tile
         "VS_ASM_FIRST_MASKED": step(0, True, False, True, masked=True),
         "VS_ASM_ODD": step(1, True, True, True),                   # step 2t+1 with a next tile
         "VS_ASM_ODD_MASKED": step(1, True, True, True, masked=True),
-        "VS_ASM_ODD_LOADS": step(1, True, True, True, loads=True),
+        "VS_ASM_ODD_LOADS": step(1, True, True, True, loads=range(16)),
         "VS_ASM_ODD_LAST": step(1, False, True, True),             # step 2t+1 of the last tile
         "VS_ASM_ODD_LAST_MASKED": step(1, False, True, True, masked=True),
         "VS_ASM_EVEN": step(0, True, True, True),                  # step 2t+2

@@ -59,7 +59,6 @@ constexpr int kStageBytes = 2 * kTileBytes;    // K tile then V tile
 constexpr int kGroupLds = 2 * kStageBytes;     // two stages per key group
 constexpr int kGroupThreads = 128;             // two wavefronts per key group
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kFrameTileCost = 2;              // load-balancing weight of a tile with frame rows
 
 struct PrefillParams {
     const __bf16* kc;
@@ -77,6 +76,7 @@ struct PrefillParams {
     int L, T, G, Hq, Hkv;
     int M, m_pad, nsplit, n_row_tiles;
     float scale_log2e;
+    float inv_G, inv_nsplit;  // reciprocals for the index arithmetic of the prologue
     unsigned long long* dbg;  // tuning aid: per-workgroup timestamps, normally null
 };
 
@@ -97,6 +97,16 @@ __device__ __forceinline__ void load_to_lds16(const char* src, char* dst) {
     __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)dst, 16, 0, 0);
 }
 
+// floor(x / d) for 0 <= x < 2^22 and d >= 1, given inv_d = 1.0f / d: the float product is within
+// one of the quotient, two corrections make it exact.  (A 32-bit integer division costs some
+// twenty instructions here, and the prologue of this kernel is on the critical path.)
+__device__ __forceinline__ int div_small(int x, int d, float inv_d) {
+    int qd = (int)((float)x * inv_d);
+    if (qd * d > x) --qd;
+    if ((qd + 1) * d <= x) ++qd;
+    return qd;
+}
+
 // The matrix instructions are issued from hand-scheduled blocks of inline assembly
 // (vs_prefill_asm.inc, written by gen_prefill_asm.py, which also documents the register plan):
 // output accumulators and query fragments live in a[0:191] for the whole kernel and are never
@@ -108,6 +118,17 @@ __global__ __launch_bounds__(kGroupThreads * NKG) __attribute__((amdgpu_waves_pe
 void prefill_mfma_kernel(PrefillParams p) {
     extern __shared__ __attribute__((aligned(1024))) char dyn_smem[];  // per key group: two K tiles, two V tiles
 
+    // All arguments the prologue needs are fetched here, at once (left to itself the compiler
+    // fetches each one where it is first used, and waits there).
+    const char* const kc = reinterpret_cast<const char*>(p.kc);
+    const char* const vc = reinterpret_cast<const char*>(p.vc);
+    const char* const kf = reinterpret_cast<const char*>(p.kf);
+    const char* const vf = reinterpret_cast<const char*>(p.vf);
+    const char* const qbase = reinterpret_cast<const char*>(p.q);
+    const int L = p.L, T = p.T, G = p.G, M = p.M, Hkv = p.Hkv, nsplit = p.nsplit;
+    const float inv_G = p.inv_G, inv_nsplit = p.inv_nsplit;
+    asm volatile("" : : "s"(kc), "s"(vc), "s"(kf), "s"(vf), "s"(qbase), "s"(L), "s"(T), "s"(G), "s"(M), "s"(Hkv),
+                 "s"(nsplit), "s"(inv_G), "s"(inv_nsplit), "s"(p.Hq), "s"(p.scale_log2e), "s"(p.dbg));
     const unsigned long long t_start = p.dbg ? wall_clock64() : 0;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -115,36 +136,47 @@ void prefill_mfma_kernel(PrefillParams p) {
     const int rb = w & 1;   // which 64 rows of the tile
     const int kg = w >> 1;  // key group of this wave
     const int l32 = lane & 31, hi = lane >> 5;
-    const int C = p.nsplit * p.Hkv;
-    const int rt = blockIdx.x / C;
-    const int c = blockIdx.x % C;
-    const int split = c / p.Hkv, g = c % p.Hkv;
-    const int L = p.L, T = p.T, G = p.G;
-    const int64_t kv_row_bytes = (int64_t)p.Hkv * kRowBytes;
+    // grid (Hkv, nsplit, row tiles): x runs fastest in dispatch order
+    const int g = blockIdx.x, split = blockIdx.y, rt = blockIdx.z;
+    const int c = split * Hkv + g;  // which partial result
+    const int wg_id = rt * (nsplit * Hkv) + c;
+    const int kv_row_bytes = Hkv * kRowBytes;
     char* const k_ring = dyn_smem + kg * kGroupLds;
     char* const v_ring = k_ring + 2 * kTileBytes;
 
     const int row0 = rt * BM;
     const int wrow0 = row0 + rb * 64;
-    const int last_row = min(row0 + BM, p.M) - 1;
-    const int tmax = last_row / G;                        // < T
-    const int n_tiles = (L + tmax + 1 + BN - 1) / BN;     // key tiles this row tile can see
-    // The tiles are shared out by cost: a tile that holds frame rows (causal mask, staging
-    // through the slower path) counts kFrameTileCost plain tiles.  cum(t) = cost of tiles 0..t-1;
-    // split i takes the tiles whose cum lies in [i, i+1) * total / nsplit.
-    const int n_plain = min(L / BN, n_tiles);
-    const int total_cost = n_plain + kFrameTileCost * (n_tiles - n_plain);
-    auto first_tile_at = [&](int i) {  // smallest t with cum(t) >= i * total / nsplit
-        const int target = (int)(((int64_t)total_cost * i + p.nsplit - 1) / p.nsplit);
-        return target <= n_plain ? target : n_plain + (target - n_plain + kFrameTileCost - 1) / kFrameTileCost;
-    };
-    const int tile_begin = first_tile_at(split);
-    const int tile_end = split + 1 == p.nsplit ? n_tiles : first_tile_at(split + 1);
-    // key group kg takes tiles tile_begin + kg, + NKG, ...: its tile number s is tile
-    // my_first + s*NKG; every group runs n_steps barriers
-    const int n_steps = (tile_end - tile_begin + NKG - 1) / NKG;
-    const int my_first = tile_begin + kg;
-    const int n_my = (tile_end - my_first + NKG - 1) / NKG;  // tiles of this group (<= n_steps)
+    const int last_row = min(row0 + BM, M) - 1;
+    const int tmax = div_small(last_row, G, inv_G);       // < T
+    const int n_tiles = (L + tmax + BN) / BN;             // key tiles this row tile can see
+    // The tiles are dealt to lanes = (split, key group) pairs, lane = split*NKG + kg.  Every lane
+    // takes q or q+1 tiles (the first lanes one more), a contiguous run of plain cache tiles.
+    // Tiles with frame rows cost more (causal mask, staging through the slower path), so they
+    // are not left in one lane: they are handed out one at a time from the last lane backwards
+    // and replace plain tiles there.  (With fewer tiles than that takes, every lane simply has
+    // its contiguous run of whatever tiles fall into it.)  Tile number s of this lane:
+    //     s < n_rest ? rest_first + s : run_first + (s - n_rest)
+    // (frame tiles first: their slower staging then falls into the prologue, and the steady
+    // state of the pipeline sees plain tiles only.)
+    const int n_lanes = nsplit * NKG;
+    const float inv_lanes = NKG == 1 ? inv_nsplit : 0.5f * inv_nsplit;
+    const int n_plain = L / BN;             // tiles of cache rows only (<= n_tiles)
+    const int n_frame = n_tiles - n_plain;
+    const bool small = n_tiles < (1 << 22);
+    const int q_all = small ? div_small(n_tiles, n_lanes, inv_lanes) : n_tiles / n_lanes;
+    const int r_all = n_tiles - q_all * n_lanes;
+    const int q_fr = small ? div_small(n_frame, n_lanes, inv_lanes) : n_frame / n_lanes;
+    const int r_fr = n_frame - q_fr * n_lanes;
+    const bool dealt = q_fr < q_all;        // every lane has room for its frame tiles
+    auto tiles_before = [&](int i) { return i * q_all + min(i, r_all); };
+    auto frame_before = [&](int i) { return i * q_fr + max(0, i - (n_lanes - r_fr)); };
+    const int my_lane = split * NKG + kg;
+    const int n_my = tiles_before(my_lane + 1) - tiles_before(my_lane);  // tiles of this lane
+    const int n_steps = tiles_before(split * NKG + 1) - tiles_before(split * NKG);  // the workgroup's longest lane
+    const int n_rest = dealt ? frame_before(my_lane + 1) - frame_before(my_lane) : 0;
+    const int run_first = tiles_before(my_lane) - (dealt ? frame_before(my_lane) : 0);
+    const int rest_first = n_plain + frame_before(my_lane);
+    auto tile_of = [&](int s) { return s < n_rest ? rest_first + s : run_first + (s - n_rest); };
 
     // ---- global -> LDS staging --------------------------------------------------------------
     // A tile is 64 rows of 256 B.  One load instruction of a wavefront fills 1 KB = 4 rows
@@ -156,76 +188,56 @@ void prefill_mfma_kernel(PrefillParams p) {
     const int lr = lane >> 4, ls = lane & 15;
     int k_src_off[4];  // byte offset of this lane's piece from the chunk's first row, chunk & 3 = x
 #pragma unroll
-    for (int x = 0; x < 4; ++x) k_src_off[x] = lr * (int)kv_row_bytes + ((ls ^ lr ^ (x << 2)) << 4);
-    const int v_src_off = lr * (int)kv_row_bytes + ((ls ^ (lr << 1)) << 4);
+    for (int x = 0; x < 4; ++x) k_src_off[x] = lr * kv_row_bytes + ((ls ^ lr ^ (x << 2)) << 4);
+    const int v_src_off = lr * kv_row_bytes + ((ls ^ (lr << 1)) << 4);
 
     // tile number s of this group -> K ring (is_v = false) or V ring, slot s & 1
     auto issue = [&](int s, bool is_v) {
         if (s >= n_my) return;
-        const int tile = my_first + s * NKG;
+        const int tile = tile_of(s);
         char* dst = (is_v ? v_ring : k_ring) + (s & 1) * kTileBytes + rb * (8 * 1024);
         const int j0 = tile * BN + rb * 32;  // first row this wave loads
         if (tile * BN + BN <= L) {
-            const char* src = reinterpret_cast<const char*>(is_v ? p.vc : p.kc) + ((int64_t)j0 * p.Hkv + g) * kRowBytes;
+            const char* src = (is_v ? vc : kc) + ((int64_t)j0 * Hkv + g) * kRowBytes;
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                load_to_lds16(src + u * 4 * kv_row_bytes + (is_v ? v_src_off : k_src_off[u & 3]), dst + u * 1024);
+                load_to_lds16(src + (int64_t)u * 4 * kv_row_bytes + (is_v ? v_src_off : k_src_off[u & 3]), dst + u * 1024);
         } else {
             // the tile holds frame rows or runs past the end: rows past the last key re-read the
             // last row (finite values; every such key is masked)
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int j = min(j0 + 4 * u + lr, L + T - 1);
-                const char* row = (j < L)
-                    ? reinterpret_cast<const char*>(is_v ? p.vc : p.kc) + ((int64_t)j * p.Hkv + g) * kRowBytes
-                    : reinterpret_cast<const char*>(is_v ? p.vf : p.kf) + ((int64_t)(j - L) * p.Hkv + g) * kRowBytes;
+                const char* row = (j < L) ? (is_v ? vc : kc) + ((int64_t)j * Hkv + g) * kRowBytes
+                                          : (is_v ? vf : kf) + ((int64_t)(j - L) * Hkv + g) * kRowBytes;
                 const int piece = is_v ? (ls ^ (lr << 1)) : (ls ^ lr ^ ((u & 3) << 2));
                 load_to_lds16(row + (piece << 4), dst + u * 1024);
             }
         }
     };
 
-    // the first tiles are requested before anything else
+    // ---- what the first two blocks need is requested before anything else is set up: K of
+    //      the first tile and the query rows.  (A compute unit takes in 64 bytes per clock: the
+    //      96 KB of these two are what the start of the pipeline waits for; K of the second
+    //      tile and V of the first are requested later, from inside the first two blocks.)
+    //      Q fragments are the B operand of S^T = K Q^T, lane (col q = l32, k = 8*hi..8*hi+7);
+    //      the wave holds two row groups r = 0, 1 of 32 rows.  They are loaded straight into
+    //      a[128:191] and stay there. ----
     issue(0, false);
-    issue(0, true);
-    issue(1, false);
-
-    // fused carrier compaction: one workgroup copies the last frame row into the cache
-    if (p.k_append_dst && blockIdx.x == 0) {
-        const int n16 = (int)(kv_row_bytes / 16);  // 16-byte chunks per row
-        const uint4* ksrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.kf) + (int64_t)(T - 1) * kv_row_bytes);
-        const uint4* vsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.vf) + (int64_t)(T - 1) * kv_row_bytes);
-        for (int ch = tid; ch < n16; ch += kGroupThreads * NKG) {
-            reinterpret_cast<uint4*>(p.k_append_dst)[ch] = ksrc[ch];
-            reinterpret_cast<uint4*>(p.v_append_dst)[ch] = vsrc[ch];
-        }
-    }
-
-    // ---- Q fragments: B operand of S^T = K Q^T, lane (col q = l32, k = 8*hi..8*hi+7); the wave
-    //      holds two row groups r = 0, 1 of 32 rows.  They are parked in a[128:191]. ----
     int r_mine[2], jmax[2];  // jmax: last key index visible to this lane's query row (causal test)
     {
-        bf16x8 qf[2][8];
+        const char* qrow[2];
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             r_mine[r] = wrow0 + 32 * r + l32;
-            const int rr = min(r_mine[r], p.M - 1);
-            const int t = rr / G, hl = rr - t * G;
+            const int rr = min(r_mine[r], M - 1);
+            const int t = div_small(rr, G, inv_G), hl = rr - t * G;
             jmax[r] = L + t;
-            const __bf16* qrow = p.q + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                qf[r][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * hi);
+            qrow[r] = qbase + ((int64_t)(t * p.Hq + g * G + hl) * D + 8 * hi) * 2;
         }
-        asm volatile(VS_ASM_INIT_O : : : VS_CLOB_ACC);  // while the loads above are under way
-        asm volatile(VS_ASM_LOAD_Q
-                     :
-                     : "{v[128:131]}"(qf[0][0]), "{v[132:135]}"(qf[0][1]), "{v[136:139]}"(qf[0][2]), "{v[140:143]}"(qf[0][3]),
-                       "{v[144:147]}"(qf[0][4]), "{v[148:151]}"(qf[0][5]), "{v[152:155]}"(qf[0][6]), "{v[156:159]}"(qf[0][7]),
-                       "{v[160:163]}"(qf[1][0]), "{v[164:167]}"(qf[1][1]), "{v[168:171]}"(qf[1][2]), "{v[172:175]}"(qf[1][3]),
-                       "{v[176:179]}"(qf[1][4]), "{v[180:183]}"(qf[1][5]), "{v[184:187]}"(qf[1][6]), "{v[188:191]}"(qf[1][7])
-                     : VS_CLOB_ACC);
+        asm volatile(VS_ASM_LOAD_Q : : [qa0] "v"(qrow[0]), [qa1] "v"(qrow[1]) : VS_CLOB_ACC);
     }
+    asm volatile(VS_ASM_INIT_O : : : VS_CLOB_ACC, VS_CLOB_TMP);  // while the loads above are under way
 
     float m_ref[2] = {-INFINITY, -INFINITY};  // softmax reference (log2 units)
     float l_run[2] = {0.f, 0.f};              // this lane's share of the row sum
@@ -256,7 +268,7 @@ void prefill_mfma_kernel(PrefillParams p) {
     // tile number s of this group: LDS byte addresses of its K and V tiles, first key index
     auto k_tile = [&](int s) { return k_ring_lds + (s & 1) * kTileBytes; };
     auto v_tile = [&](int s) { return v_ring_lds + (s & 1) * kTileBytes; };
-    auto key0 = [&](int n) { return (my_first + (n >> 1) * NKG) * BN + 32 * (n & 1); };  // of sub-block n
+    auto key0 = [&](int n) { return tile_of(n >> 1) * BN + 32 * (n & 1); };  // of sub-block n
 
     // Sub-block n has gone through the speculative softmax (reference possibly stale); its PV
     // product has not been issued.  Commit its row sums, or, if a probability came out above
@@ -284,6 +296,7 @@ void prefill_mfma_kernel(PrefillParams p) {
             if (par == 0 && r == 1) asm volatile("" : "={v[144:159]}"(x));
             if (par == 1 && r == 0) asm volatile("" : "={v[160:175]}"(x));
             if (par == 1 && r == 1) asm volatile("" : "={v[176:191]}"(x));
+            const f32x16 x_raw = x;
             if (j0 + 32 > L) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
@@ -324,6 +337,12 @@ void prefill_mfma_kernel(PrefillParams p) {
                 }
             }
             l_run[r] = l_run[r] * alpha[r] + sum;
+            // the raw scores stay where they are to the end: this keeps the compiler from working
+            // in place inside the fixed registers
+            if (par == 0 && r == 0) asm volatile("" : : "{v[128:143]}"(x_raw));
+            if (par == 0 && r == 1) asm volatile("" : : "{v[144:159]}"(x_raw));
+            if (par == 1 && r == 0) asm volatile("" : : "{v[160:175]}"(x_raw));
+            if (par == 1 && r == 1) asm volatile("" : : "{v[176:191]}"(x_raw));
         }
         if (__any(alpha[0] != 1.f || alpha[1] != 1.f))
             asm volatile(VS_ASM_RESCALE : : [alpha0] "v"(alpha[0]), [alpha1] "v"(alpha[1]) : VS_CLOB_ACC, VS_CLOB_TMP);
@@ -357,33 +376,58 @@ void prefill_mfma_kernel(PrefillParams p) {
     } while (0)
 
     const unsigned long long t_loop = p.dbg ? wall_clock64() : 0;
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    __syncthreads();                     // K(0), V(0), K(1) of every group are staged
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): K(0) and Q have landed
+    __syncthreads();                     // K(0) of every group is staged
     if (n_my > 0) {
-        // sub-block 0: raw scores, then step 0 = QK(1) | SM(0) against the reference 0 (fine
-        // whenever the scaled scores are moderate; otherwise commit() redoes it exactly)
-        asm volatile(VS_ASM_QK0 : : VS_ADDR(k_tile(0), 0u) : VS_CLOBBERS);
+        // K of the group's second tile and V of its first are requested on the way: from inside
+        // the first two blocks, between their matrix instructions, when they are plain cache tiles.
+        // sub-block 0: raw scores
+        if (n_my > 1 && tile_of(1) * BN + BN <= L) {
+            unsigned long long ksrc = (unsigned long long)(kc + ((int64_t)(tile_of(1) * BN + rb * 32) * Hkv + g) * kRowBytes);
+            unsigned ldsk = k_tile(1) + rb * (8 * 1024);
+            asm volatile(VS_ASM_QK0_LOADS
+                         : "+{s[88:89]}"(ksrc), [ldsk] "+s"(ldsk)
+                         : VS_ADDR(k_tile(0), 0u), [kso0] "v"(k_src_off[0]), [kso1] "v"(k_src_off[1]),
+                           [kso2] "v"(k_src_off[2]), [kso3] "v"(k_src_off[3]), [stride] "s"(4 * kv_row_bytes)
+                         : VS_CLOBBERS, "scc");
+        } else {
+            issue(1, false);
+            asm volatile(VS_ASM_QK0 : : VS_ADDR(k_tile(0), 0u) : VS_CLOBBERS);
+        }
+        // step 0 = QK(1) | SM(0) against the reference 0 (fine whenever the scaled scores are
+        // moderate; otherwise commit() redoes it exactly)
         m_ref[0] = m_ref[1] = 0.f;
-        if (key0(0) + 32 > L) VS_STEP_MASKED(VS_ASM_FIRST_MASKED, 0, k_tile(0), 0u);
-        else VS_STEP(VS_ASM_FIRST, 0, k_tile(0), 0u);
+        if (tile_of(0) * BN + BN <= L) {
+            unsigned long long vsrc = (unsigned long long)(vc + ((int64_t)(tile_of(0) * BN + rb * 32) * Hkv + g) * kRowBytes);
+            unsigned ldsv = v_tile(0) + rb * (8 * 1024);
+            float sum0_, sum1_;
+            const float zero_ = 0.f;
+            asm volatile(VS_ASM_FIRST_LOADS
+                         : [sum0] "=&v"(sum0_), [sum1] "=&v"(sum1_), "+{s[90:91]}"(vsrc), [ldsv] "+s"(ldsv)
+                         : VS_ADDR(k_tile(0), 0u), [ms0] "v"(zero_), [ms1] "v"(zero_), [scale] "s"(p.scale_log2e),
+                           [vso] "v"(v_src_off), [stride] "s"(4 * kv_row_bytes)
+                         : VS_CLOBBERS, "scc");
+            commit(0, sum0_, sum1_);
+        } else {
+            issue(0, true);
+            if (key0(0) + 32 > L) VS_STEP_MASKED(VS_ASM_FIRST_MASKED, 0, k_tile(0), 0u);
+            else VS_STEP(VS_ASM_FIRST, 0, k_tile(0), 0u);
+        }
     }
 
-    unsigned long long* stamps = (p.dbg && blockIdx.x == 100 && tid == 0) ? p.dbg + 8192 : nullptr;
     for (int s = 0; s < n_steps; ++s) {
         // steps 2s+1 and 2s+2 of this group: they read K of tile s+1 and V of tile s
-        if (stamps) stamps[1 + 4 * s] = wall_clock64();
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of K(s+1), V(s) has landed
-        if (stamps) stamps[2 + 4 * s] = wall_clock64();
         __syncthreads();                     // ... and everybody's; K slot s&1 and V slot (s+1)&1 are free
-        if (stamps) stamps[3 + 4 * s] = wall_clock64();
         // tiles to stage now: K of tile s+2, V of tile s+1.  When both lie inside the cache rows
         // the first block issues the loads itself, between its matrix instructions.
-        const bool loads_inside = s + 2 < n_my && (my_first + (s + 2) * NKG) * BN + BN <= L;
+        // (the block that can do that is the unmasked one: tile s must be a plain tile too)
+        const bool loads_inside = s + 2 < n_my && tile_of(s + 2) * BN + BN <= L && tile_of(s + 1) * BN + BN <= L &&
+                                  tile_of(s) * BN + BN <= L;
         if (!loads_inside) {
             issue(s + 2, false);
             issue(s + 1, true);
         }
-        if (stamps) stamps[4 + 4 * s] = wall_clock64();
         if (NKG > 1 && s >= n_my) continue;  // this group idles in the last step
         const unsigned kb = k_tile(s + 1), vb = v_tile(s);
         const int n = 2 * s + 1;
@@ -393,10 +437,10 @@ void prefill_mfma_kernel(PrefillParams p) {
                 VS_STEP_MASKED(VS_ASM_ODD_MASKED, n, kb, vb);
             } else if (loads_inside) {
                 // this wave's share: rows 32*rb .. 32*rb+31 of the two tiles, head g
-                unsigned long long ksrc = (unsigned long long)(reinterpret_cast<const char*>(p.kc) +
-                    ((int64_t)((my_first + (s + 2) * NKG) * BN + rb * 32) * p.Hkv + g) * kRowBytes);
-                unsigned long long vsrc = (unsigned long long)(reinterpret_cast<const char*>(p.vc) +
-                    ((int64_t)((my_first + (s + 1) * NKG) * BN + rb * 32) * p.Hkv + g) * kRowBytes);
+                unsigned long long ksrc = (unsigned long long)(kc +
+                    ((int64_t)(tile_of(s + 2) * BN + rb * 32) * Hkv + g) * kRowBytes);
+                unsigned long long vsrc = (unsigned long long)(vc +
+                    ((int64_t)(tile_of(s + 1) * BN + rb * 32) * Hkv + g) * kRowBytes);
                 unsigned ldsk = k_tile(s) + rb * (8 * 1024);
                 unsigned ldsv = v_tile(s + 1) + rb * (8 * 1024);
                 float sum0_, sum1_;
@@ -407,7 +451,7 @@ void prefill_mfma_kernel(PrefillParams p) {
                                "+{s[88:89]}"(ksrc), "+{s[90:91]}"(vsrc), [ldsk] "+s"(ldsk), [ldsv] "+s"(ldsv)
                              : VS_ADDR(kb, vb), [ms0] "v"(ms0_), [ms1] "v"(ms1_), [scale] "s"(p.scale_log2e),
                                [kso0] "v"(k_src_off[0]), [kso1] "v"(k_src_off[1]), [kso2] "v"(k_src_off[2]), [kso3] "v"(k_src_off[3]),
-                               [vso] "v"(v_src_off), [stride] "s"(4 * (int)kv_row_bytes)
+                               [vso] "v"(v_src_off), [stride] "s"(4 * kv_row_bytes)
                              : VS_CLOBBERS, "scc");
                 commit(n, sum0_, sum1_);
             } else {
@@ -429,6 +473,18 @@ void prefill_mfma_kernel(PrefillParams p) {
 #undef VS_STEP_MASKED
 
     asm volatile("; pipeline registers free");  // marker for the listing check of the build
+
+    // fused carrier compaction: one workgroup copies the last frame row into the cache (no
+    // workgroup of this launch reads that row)
+    if (p.k_append_dst && wg_id == 0) {
+        const int n16 = kv_row_bytes / 16;  // 16-byte chunks per row
+        const uint4* ksrc = reinterpret_cast<const uint4*>(kf + (int64_t)(T - 1) * kv_row_bytes);
+        const uint4* vsrc = reinterpret_cast<const uint4*>(vf + (int64_t)(T - 1) * kv_row_bytes);
+        for (int ch = tid; ch < n16; ch += kGroupThreads * NKG) {
+            reinterpret_cast<uint4*>(p.k_append_dst)[ch] = ksrc[ch];
+            reinterpret_cast<uint4*>(p.v_append_dst)[ch] = vsrc[ch];
+        }
+    }
     const unsigned long long t_epi = p.dbg ? wall_clock64() : 0;
     f32x16 o[2][4];
     asm volatile(VS_ASM_READ_O
@@ -528,7 +584,7 @@ void prefill_mfma_kernel(PrefillParams p) {
         if (kg == 0) take_over(0); else take_over(1);
     }
     if (p.dbg && tid == 0) {
-        unsigned long long* d = p.dbg + (size_t)blockIdx.x * 4;
+        unsigned long long* d = p.dbg + (size_t)wg_id * 4;
         d[0] = t_start; d[1] = t_loop; d[2] = t_epi; d[3] = wall_clock64();
     }
 }
@@ -628,7 +684,8 @@ hipError_t launch_kvg(const PrefillParams& p, const Plan& pl, int n_kv_heads, hi
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int grid = pl.n_row_tiles * pl.nsplit * n_kv_heads;
+    // x runs fastest in dispatch order: all workgroups that read one K/V slice are neighbours
+    const dim3 grid(n_kv_heads, pl.nsplit, pl.n_row_tiles);
     prefill_mfma_kernel<KVG><<<grid, kGroupThreads * KVG, kLds, st>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.nsplit == 1 || g_tune_skip_merge) return e;
@@ -670,6 +727,8 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
     p.nsplit = pl.nsplit;
     p.n_row_tiles = pl.n_row_tiles;
     p.scale_log2e = s.softmax_scale * kLog2e;
+    p.inv_G = 1.0f / (float)p.G;
+    p.inv_nsplit = 1.0f / (float)pl.nsplit;
     const int64_t slots = (int64_t)pl.nsplit * s.n_kv_heads * pl.m_pad;
     p.part_ml = (float*)workspace;
     p.part_o = (__bf16*)(p.part_ml + slots * 2);
