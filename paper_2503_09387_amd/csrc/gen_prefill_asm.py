@@ -35,7 +35,8 @@ Scheduling rules the blocks obey (gfx950, one wavefront per SIMD):
   * ordinary instructions never read a matrix result inside the block that computes it, except
     after an explicit run of s_nop (an 8-pass instruction needs 11 idle issue slots);
   * a memory instruction reads a scalar register no earlier than five issue slots after a scalar
-    instruction wrote it (the staging loads step their base address in s[88:91]);
+    instruction wrote it (the staging loads take their base address from s[88:91], which the
+    caller sets before the block and the block leaves alone);
   * a transcendental result is not read by the next instruction; a mask written by a compare
     is not read by the next two; a dot-product result is read by other kinds of instruction no
     earlier than three instructions later; M0 is not used by the instruction after the one that
@@ -89,21 +90,20 @@ class Block:
         return " \\\n".join('    "' + l + '\\n\\t"' for l in self.lines)
 
 
-def emit_stage_load(b, u, settle=False):
+def emit_stage_load(b, u, first, last):
     """Staging load of this wave: chunk u of a K tile (u < 8) or chunk u-8 of a V tile, 16 bytes per
-    lane straight into LDS; s[88:89] / s[90:91] walk the global rows (4 rows per chunk), M0 holds
-    the LDS destination.  A memory instruction must not read a scalar register earlier than five
-    issue slots after a scalar instruction wrote it: inside the pipeline blocks the matrix and
-    softmax instructions between two loads provide that, elsewhere `settle` adds the idle slots."""
+    lane straight into LDS.  s[88:89] / s[90:91] hold the address of the wave's first row of the
+    tile, the operands ko0..7 / vo0..7 the lane's byte offset inside chunk u (its row and 16-byte
+    piece, plus u chunks of 4 rows), M0 the LDS destination: it is set for the first chunk of a
+    tile and stepped by 1 KB right after each load, so that the write and the next use are never
+    neighbours."""
     which, base = ("k", 88) if u < 8 else ("v", 90)
-    b.emit(f"s_mov_b32 m0, %[lds{which}]")
-    b.emit(f"s_add_u32 %[lds{which}], %[lds{which}], 0x400")
-    if settle:
-        b.emit("s_nop 3")
-    off = f"%[kso{u & 3}]" if which == "k" else "%[vso]"
-    b.emit(f"global_load_lds_dwordx4 {off}, s[{base}:{base + 1}]")
-    b.emit(f"s_add_u32 s{base}, s{base}, %[stride]")
-    b.emit(f"s_addc_u32 s{base + 1}, s{base + 1}, 0")
+    if first or u == 8:
+        b.emit(f"s_mov_b32 m0, %[lds{which}]")
+        b.emit("s_nop 0")
+    b.emit(f"global_load_lds_dwordx4 %[{which}o{u & 7}], s[{base}:{base + 1}]")
+    if not last and u != 7:
+        b.emit("s_add_u32 m0, m0, 0x400")
 
 
 def step(p, qk, pv, sm, masked=False, loads=()):
@@ -179,8 +179,8 @@ def step(p, qk, pv, sm, masked=False, loads=()):
             t, j = divmod(e, 8)
             b.emit(f"v_dot2c_f32_bf16_e32 %[sum{r}], v{P(p, r, t) + j // 2}, v{ONES}")
 
-    def stage_load(u):
-        emit_stage_load(b, u, settle=not sm)  # without softmax work the loads follow each other closely
+    def stage_load(j):
+        emit_stage_load(b, loads[j], j == 0, j == len(loads) - 1)
 
     # ---- schedule
     n_pairs = len(plan)
@@ -220,12 +220,22 @@ def step(p, qk, pv, sm, masked=False, loads=()):
                 cnt[issued] = frag_read(issued)
                 issued += 1
             if r == 1 and j < len(loads):
-                stage_load(loads[j])
+                stage_load(j)
             q = 2 * j + r
             b.lines += stream[pos:pos + take[q]]
             pos += take[q]
     if sm:
-        b.emit("s_nop 3")  # the sums are dot-product results
+        # flag = lanes whose sub-block needs a closer look: a sum above 2^8 (or not a number), or a
+        # row that had accumulated nothing before (sums are dot-product results: not read by
+        # another kind of instruction for three slots)
+        b.emit("v_cmp_eq_f32_e64 %[flag], 0, %[l0]")
+        b.emit("v_cmp_eq_f32_e64 vcc, 0, %[l1]")
+        b.emit("s_or_b64 %[flag], %[flag], vcc")
+        b.emit("s_nop 0")
+        b.emit("v_cmp_nge_f32_e64 vcc, %[k256], %[sum0]")
+        b.emit("s_or_b64 %[flag], %[flag], vcc")
+        b.emit("v_cmp_nge_f32_e64 vcc, %[k256], %[sum1]")
+        b.emit("s_or_b64 %[flag], %[flag], vcc")
     if qk and not pv:
         # no matrix instructions follow inside the block: let the scores settle, the caller or
         # the next block reads them with ordinary instructions

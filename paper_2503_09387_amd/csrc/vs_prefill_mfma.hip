@@ -190,6 +190,12 @@ void prefill_mfma_kernel(PrefillParams p) {
 #pragma unroll
     for (int x = 0; x < 4; ++x) k_src_off[x] = lr * kv_row_bytes + ((ls ^ lr ^ (x << 2)) << 4);
     const int v_src_off = lr * kv_row_bytes + ((ls ^ (lr << 1)) << 4);
+    int k_off[8], v_off[8];  // the same with the chunk's rows added: what the in-block staging loads use
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        k_off[u] = k_src_off[u & 3] + u * 4 * kv_row_bytes;
+        v_off[u] = v_src_off + u * 4 * kv_row_bytes;
+    }
 
     // tile number s of this group -> K ring (is_v = false) or V ring, slot s & 1
     auto issue = [&](int s, bool is_v) {
@@ -240,6 +246,7 @@ void prefill_mfma_kernel(PrefillParams p) {
     asm volatile(VS_ASM_INIT_O : : : VS_CLOB_ACC, VS_CLOB_TMP);  // while the loads above are under way
 
     float m_ref[2] = {-INFINITY, -INFINITY};  // softmax reference (log2 units)
+    float ms[2] = {0.f, 0.f};                 // what the blocks subtract: the reference, 0 while there is none
     float l_run[2] = {0.f, 0.f};              // this lane's share of the row sum
 
     // LDS read addresses (bytes inside a tile)
@@ -259,11 +266,28 @@ void prefill_mfma_kernel(PrefillParams p) {
     // P[parity][row group][step] in v[216:247] (sub-block n of this group uses parity n & 1).
     // Every block names them as clobbered, and the code between the blocks is small enough
     // that the compiler stays in the low registers there (the build checks the listing).
-#define VS_ADDR(kb, vb)                                                                          \
-    [ka0] "v"(k_rd[0] + (kb)), [ka1] "v"(k_rd[1] + (kb)), [ka2] "v"(k_rd[2] + (kb)), [ka3] "v"(k_rd[3] + (kb)), \
-    [ka4] "v"(k_rd[4] + (kb)), [ka5] "v"(k_rd[5] + (kb)), [ka6] "v"(k_rd[6] + (kb)), [ka7] "v"(k_rd[7] + (kb)), \
-    [va0] "v"(v_rd[0] + (vb)), [va1] "v"(v_rd[1] + (vb))
-#define VS_CLOBBERS VS_CLOB_ACC, VS_CLOB_S, VS_CLOB_FRAG, VS_CLOB_TMP, VS_CLOB_P
+    // the read addresses of the tiles in use: K starts in slot 0, V in slot 0; they change slot
+    // once per tile
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) k_rd[kk] += k_ring_lds;
+    v_rd[0] += v_ring_lds;
+    v_rd[1] += v_ring_lds;
+    int k_hop = kTileBytes, v_hop = kTileBytes;  // to the other slot
+#define VS_ADDR                                                                                  \
+    [ka0] "v"(k_rd[0]), [ka1] "v"(k_rd[1]), [ka2] "v"(k_rd[2]), [ka3] "v"(k_rd[3]),              \
+    [ka4] "v"(k_rd[4]), [ka5] "v"(k_rd[5]), [ka6] "v"(k_rd[6]), [ka7] "v"(k_rd[7]),              \
+    [va0] "v"(v_rd[0]), [va1] "v"(v_rd[1])
+#define VS_KOFF                                                                                  \
+    [ko0] "v"(k_off[0]), [ko1] "v"(k_off[1]), [ko2] "v"(k_off[2]), [ko3] "v"(k_off[3]),          \
+    [ko4] "v"(k_off[4]), [ko5] "v"(k_off[5]), [ko6] "v"(k_off[6]), [ko7] "v"(k_off[7])
+#define VS_VOFF                                                                                  \
+    [vo0] "v"(v_off[0]), [vo1] "v"(v_off[1]), [vo2] "v"(v_off[2]), [vo3] "v"(v_off[3]),          \
+    [vo4] "v"(v_off[4]), [vo5] "v"(v_off[5]), [vo6] "v"(v_off[6]), [vo7] "v"(v_off[7])
+    // what every block with a softmax part takes and returns: the sums, and the lanes that need the
+    // closer look of commit()
+#define VS_SM_OUT [sum0] "=&v"(sum0_), [sum1] "=&v"(sum1_), [flag] "=&s"(flag_)
+#define VS_SM_IN [ms0] "v"(ms[0]), [ms1] "v"(ms[1]), [scale] "s"(p.scale_log2e), [l0] "v"(l_run[0]), [l1] "v"(l_run[1]), [k256] "s"(256.f)
+#define VS_CLOBBERS VS_CLOB_ACC, VS_CLOB_S, VS_CLOB_FRAG, VS_CLOB_TMP, VS_CLOB_P, "vcc"
 
     // tile number s of this group: LDS byte addresses of its K and V tiles, first key index
     auto k_tile = [&](int s) { return k_ring_lds + (s & 1) * kTileBytes; };
@@ -277,7 +301,12 @@ void prefill_mfma_kernel(PrefillParams p) {
     // A row that has accumulated nothing yet runs against the made-up reference 0: there an
     // underflow (a lane that can see a key of the sub-block but whose sum vanished) also sends
     // the sub-block to the exact pass, which treats such a row as having no reference at all.
-    auto commit = [&](int n, float sum0, float sum1) {
+    auto commit = [&](int n, float sum0, float sum1, unsigned long long flag) {
+        if (flag == 0) {  // the common case, decided inside the block
+            l_run[0] += sum0;
+            l_run[1] += sum1;
+            return;
+        }
         const int jl = key0(n) + 4 * hi;  // this lane's smallest key in the sub-block
         const bool redo = !(sum0 <= 256.f) || !(sum1 <= 256.f) ||
                           (l_run[0] == 0.f && jl <= jmax[0] && sum0 < 0x1p-40f) ||
@@ -311,6 +340,7 @@ void prefill_mfma_kernel(PrefillParams p) {
             alpha[r] = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_old - m_new);
             m_ref[r] = m_new;
             const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;
+            ms[r] = m_sub;
             float sum = 0.f;
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
@@ -349,30 +379,24 @@ void prefill_mfma_kernel(PrefillParams p) {
     };
 
     // One pipeline step with a softmax part: runs the block `ASM` and commits sub-block n.
-#define VS_STEP(ASM, n, kb, vb)                                                                      \
+#define VS_STEP(ASM, n)                                                                              \
     do {                                                                                             \
         float sum0_, sum1_;                                                                          \
-        const float ms0_ = (m_ref[0] == -INFINITY) ? 0.f : m_ref[0];                                 \
-        const float ms1_ = (m_ref[1] == -INFINITY) ? 0.f : m_ref[1];                                 \
-        asm volatile(ASM                                                                             \
-                     : [sum0] "=&v"(sum0_), [sum1] "=&v"(sum1_)                            \
-                     : VS_ADDR(kb, vb), [ms0] "v"(ms0_), [ms1] "v"(ms1_), [scale] "s"(p.scale_log2e) \
-                     : VS_CLOBBERS);                                                                 \
-        commit(n, sum0_, sum1_);                                                                     \
+        unsigned long long flag_;                                                                    \
+        asm volatile(ASM : VS_SM_OUT : VS_ADDR, VS_SM_IN : VS_CLOBBERS);                             \
+        commit(n, sum0_, sum1_, flag_);                                                              \
     } while (0)
-#define VS_STEP_MASKED(ASM, n, kb, vb)                                                               \
+#define VS_STEP_MASKED(ASM, n)                                                                       \
     do {                                                                                             \
         float sum0_, sum1_;                                                                          \
-        const float ms0_ = (m_ref[0] == -INFINITY) ? 0.f : m_ref[0];                                 \
-        const float ms1_ = (m_ref[1] == -INFINITY) ? 0.f : m_ref[1];                                 \
+        unsigned long long flag_;                                                                    \
         const int d0_ = jmax[0] - (key0(n) + 4 * hi), d1_ = jmax[1] - (key0(n) + 4 * hi);            \
         unsigned long long mk0_, mk1_;                                                               \
         asm volatile(ASM                                                                             \
-                     : [sum0] "=&v"(sum0_), [sum1] "=&v"(sum1_), [mk0] "=&s"(mk0_), [mk1] "=&s"(mk1_) \
-                     : VS_ADDR(kb, vb), [ms0] "v"(ms0_), [ms1] "v"(ms1_), [scale] "s"(p.scale_log2e), \
-                       [d0] "v"(d0_), [d1] "v"(d1_)                                                  \
+                     : VS_SM_OUT, [mk0] "=&s"(mk0_), [mk1] "=&s"(mk1_)                               \
+                     : VS_ADDR, VS_SM_IN, [d0] "v"(d0_), [d1] "v"(d1_)                               \
                      : VS_CLOBBERS);                                                                 \
-        commit(n, sum0_, sum1_);                                                                     \
+        commit(n, sum0_, sum1_, flag_);                                                              \
     } while (0)
 
     const unsigned long long t_loop = p.dbg ? wall_clock64() : 0;
@@ -383,37 +407,36 @@ void prefill_mfma_kernel(PrefillParams p) {
         // the first two blocks, between their matrix instructions, when they are plain cache tiles.
         // sub-block 0: raw scores
         if (n_my > 1 && tile_of(1) * BN + BN <= L) {
-            unsigned long long ksrc = (unsigned long long)(kc + ((int64_t)(tile_of(1) * BN + rb * 32) * Hkv + g) * kRowBytes);
-            unsigned ldsk = k_tile(1) + rb * (8 * 1024);
+            const unsigned long long ksrc = (unsigned long long)(kc + ((int64_t)(tile_of(1) * BN + rb * 32) * Hkv + g) * kRowBytes);
             asm volatile(VS_ASM_QK0_LOADS
-                         : "+{s[88:89]}"(ksrc), [ldsk] "+s"(ldsk)
-                         : VS_ADDR(k_tile(0), 0u), [kso0] "v"(k_src_off[0]), [kso1] "v"(k_src_off[1]),
-                           [kso2] "v"(k_src_off[2]), [kso3] "v"(k_src_off[3]), [stride] "s"(4 * kv_row_bytes)
+                         :
+                         : VS_ADDR, VS_KOFF, "{s[88:89]}"(ksrc), [ldsk] "s"(k_tile(1) + rb * (8 * 1024))
                          : VS_CLOBBERS, "scc");
         } else {
             issue(1, false);
-            asm volatile(VS_ASM_QK0 : : VS_ADDR(k_tile(0), 0u) : VS_CLOBBERS);
+            asm volatile(VS_ASM_QK0 : : VS_ADDR : VS_CLOBBERS);
         }
         // step 0 = QK(1) | SM(0) against the reference 0 (fine whenever the scaled scores are
         // moderate; otherwise commit() redoes it exactly)
         m_ref[0] = m_ref[1] = 0.f;
         if (tile_of(0) * BN + BN <= L) {
-            unsigned long long vsrc = (unsigned long long)(vc + ((int64_t)(tile_of(0) * BN + rb * 32) * Hkv + g) * kRowBytes);
-            unsigned ldsv = v_tile(0) + rb * (8 * 1024);
+            const unsigned long long vsrc = (unsigned long long)(vc + ((int64_t)(tile_of(0) * BN + rb * 32) * Hkv + g) * kRowBytes);
             float sum0_, sum1_;
-            const float zero_ = 0.f;
+            unsigned long long flag_;
             asm volatile(VS_ASM_FIRST_LOADS
-                         : [sum0] "=&v"(sum0_), [sum1] "=&v"(sum1_), "+{s[90:91]}"(vsrc), [ldsv] "+s"(ldsv)
-                         : VS_ADDR(k_tile(0), 0u), [ms0] "v"(zero_), [ms1] "v"(zero_), [scale] "s"(p.scale_log2e),
-                           [vso] "v"(v_src_off), [stride] "s"(4 * kv_row_bytes)
+                         : VS_SM_OUT
+                         : VS_ADDR, VS_SM_IN, VS_VOFF, "{s[90:91]}"(vsrc), [ldsv] "s"(v_tile(0) + rb * (8 * 1024))
                          : VS_CLOBBERS, "scc");
-            commit(0, sum0_, sum1_);
+            commit(0, sum0_, sum1_, flag_);
         } else {
             issue(0, true);
-            if (key0(0) + 32 > L) VS_STEP_MASKED(VS_ASM_FIRST_MASKED, 0, k_tile(0), 0u);
-            else VS_STEP(VS_ASM_FIRST, 0, k_tile(0), 0u);
+            if (key0(0) + 32 > L) VS_STEP_MASKED(VS_ASM_FIRST_MASKED, 0);
+            else VS_STEP(VS_ASM_FIRST, 0);
         }
     }
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) k_rd[kk] += k_hop;  // the loop starts on K of tile 1, V of tile 0
+    k_hop = -k_hop;
 
     for (int s = 0; s < n_steps; ++s) {
         // steps 2s+1 and 2s+2 of this group: they read K of tile s+1 and V of tile s
@@ -429,45 +452,50 @@ void prefill_mfma_kernel(PrefillParams p) {
             issue(s + 1, true);
         }
         if (NKG > 1 && s >= n_my) continue;  // this group idles in the last step
-        const unsigned kb = k_tile(s + 1), vb = v_tile(s);
         const int n = 2 * s + 1;
         if (s + 1 < n_my) {
             // step 2s+1: QK(2s+2) | PV(2s) | SM(2s+1)
             if (key0(n) + 32 > L) {
-                VS_STEP_MASKED(VS_ASM_ODD_MASKED, n, kb, vb);
+                VS_STEP_MASKED(VS_ASM_ODD_MASKED, n);
             } else if (loads_inside) {
                 // this wave's share: rows 32*rb .. 32*rb+31 of the two tiles, head g
-                unsigned long long ksrc = (unsigned long long)(kc +
+                const unsigned long long ksrc = (unsigned long long)(kc +
                     ((int64_t)(tile_of(s + 2) * BN + rb * 32) * Hkv + g) * kRowBytes);
-                unsigned long long vsrc = (unsigned long long)(vc +
+                const unsigned long long vsrc = (unsigned long long)(vc +
                     ((int64_t)(tile_of(s + 1) * BN + rb * 32) * Hkv + g) * kRowBytes);
-                unsigned ldsk = k_tile(s) + rb * (8 * 1024);
-                unsigned ldsv = v_tile(s + 1) + rb * (8 * 1024);
                 float sum0_, sum1_;
-                const float ms0_ = (m_ref[0] == -INFINITY) ? 0.f : m_ref[0];
-                const float ms1_ = (m_ref[1] == -INFINITY) ? 0.f : m_ref[1];
+                unsigned long long flag_;
                 asm volatile(VS_ASM_ODD_LOADS
-                             : [sum0] "=&v"(sum0_), [sum1] "=&v"(sum1_),
-                               "+{s[88:89]}"(ksrc), "+{s[90:91]}"(vsrc), [ldsk] "+s"(ldsk), [ldsv] "+s"(ldsv)
-                             : VS_ADDR(kb, vb), [ms0] "v"(ms0_), [ms1] "v"(ms1_), [scale] "s"(p.scale_log2e),
-                               [kso0] "v"(k_src_off[0]), [kso1] "v"(k_src_off[1]), [kso2] "v"(k_src_off[2]), [kso3] "v"(k_src_off[3]),
-                               [vso] "v"(v_src_off), [stride] "s"(4 * kv_row_bytes)
+                             : VS_SM_OUT
+                             : VS_ADDR, VS_SM_IN, VS_KOFF, VS_VOFF, "{s[88:89]}"(ksrc), "{s[90:91]}"(vsrc),
+                               [ldsk] "s"(k_tile(s) + rb * (8 * 1024)), [ldsv] "s"(v_tile(s + 1) + rb * (8 * 1024))
                              : VS_CLOBBERS, "scc");
-                commit(n, sum0_, sum1_);
+                commit(n, sum0_, sum1_, flag_);
             } else {
-                VS_STEP(VS_ASM_ODD, n, kb, vb);
+                VS_STEP(VS_ASM_ODD, n);
             }
             // step 2s+2: QK(2s+3) | PV(2s+1) | SM(2s+2)
-            if (key0(n + 1) + 32 > L) VS_STEP_MASKED(VS_ASM_EVEN_MASKED, n + 1, kb, vb);
-            else VS_STEP(VS_ASM_EVEN, n + 1, kb, vb);
+            if (key0(n + 1) + 32 > L) VS_STEP_MASKED(VS_ASM_EVEN_MASKED, n + 1);
+            else VS_STEP(VS_ASM_EVEN, n + 1);
         } else {
             // the group's last tile: step 2s+1 = PV(2s) | SM(2s+1), then PV(2s+1)
-            if (key0(n) + 32 > L) VS_STEP_MASKED(VS_ASM_ODD_LAST_MASKED, n, kb, vb);
-            else VS_STEP(VS_ASM_ODD_LAST, n, kb, vb);
-            asm volatile(VS_ASM_TAIL : : VS_ADDR(kb, vb) : VS_CLOBBERS);
+            if (key0(n) + 32 > L) VS_STEP_MASKED(VS_ASM_ODD_LAST_MASKED, n);
+            else VS_STEP(VS_ASM_ODD_LAST, n);
+            asm volatile(VS_ASM_TAIL : : VS_ADDR : VS_CLOBBERS);
         }
+        // the next step reads the other slots
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) k_rd[kk] += k_hop;
+        v_rd[0] += v_hop;
+        v_rd[1] += v_hop;
+        k_hop = -k_hop;
+        v_hop = -v_hop;
     }
 #undef VS_ADDR
+#undef VS_KOFF
+#undef VS_VOFF
+#undef VS_SM_OUT
+#undef VS_SM_IN
 #undef VS_CLOBBERS
 #undef VS_STEP
 #undef VS_STEP_MASKED
