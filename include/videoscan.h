@@ -91,7 +91,9 @@ size_t vs_workspace_bytes(const vs_shape *shape, int32_t max_q_tokens, int32_t m
 /*
  * Prepares a freshly allocated (or overwritten) workspace: clears the small control
  * block at its start, which holds arrival counters that the kernels leave at zero
- * after every launch.  Must have completed on the device (same stream, or
+ * after every launch.  The first call on a device also runs a one-off probe of how the
+ * device distributes workgroups and waits for it (hip_stream is synchronised once).
+ * Must have completed on the device (same stream, or
  * synchronised) before the first call that uses the workspace; needed once, not per
  * call.  A workspace is tied to the shape it was initialised with.
  */
@@ -180,12 +182,17 @@ vs_status vs_carrier_mean_pool(const void *e, int32_t n, int32_t d, int32_t dtyp
  *   VS_TUNE_SKIP_MERGE        1 = do not launch the kernels that merge split results, so that
  *                             the attention kernels can be timed alone; outputs of calls whose
  *                             keys were split are then NOT written.  Measurement only.
+ *                             (Prefill calls that merge inside the attention kernel are not
+ *                             affected: there is no second kernel to leave out.)
+ *   VS_TUNE_PREFILL_MERGE     2 = prefill always merges split results with the second kernel,
+ *                             never inside the attention kernel
  */
 typedef enum {
     VS_TUNE_PREFILL_SPLITS = 0,
     VS_TUNE_PREFILL_KV_GROUPS = 1,
     VS_TUNE_DECODE_CHUNK_ROWS = 2,
-    VS_TUNE_SKIP_MERGE = 3
+    VS_TUNE_SKIP_MERGE = 3,
+    VS_TUNE_PREFILL_MERGE = 4
 } vs_tune_knob;
 vs_status vs_set_tuning(int32_t knob, int32_t value);
 

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     TUNE_PREFILL_KV_GROUPS,
     TUNE_DECODE_CHUNK_ROWS,
     TUNE_SKIP_MERGE,
+    TUNE_PREFILL_MERGE,
     lib_path,
     status_string,
     workspace_bytes,

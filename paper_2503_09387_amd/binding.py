@@ -202,7 +202,7 @@ def carrier_mean_pool(e, c_out, dtype, stream=None):
            "vs_carrier_mean_pool")
 
 
-TUNE_PREFILL_SPLITS, TUNE_PREFILL_KV_GROUPS, TUNE_DECODE_CHUNK_ROWS, TUNE_SKIP_MERGE = 0, 1, 2, 3
+TUNE_PREFILL_SPLITS, TUNE_PREFILL_KV_GROUPS, TUNE_DECODE_CHUNK_ROWS, TUNE_SKIP_MERGE, TUNE_PREFILL_MERGE = 0, 1, 2, 3, 4
 
 
 def set_tuning(knob, value):

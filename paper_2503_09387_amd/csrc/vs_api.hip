@@ -15,6 +15,7 @@ int g_tune_prefill_kv_groups = 0;
 int g_tune_decode_chunk_rows = 0;
 int g_tune_debug_mode = 0;
 int g_tune_skip_merge = 0;
+int g_tune_prefill_merge = 0;
 }  // namespace vs
 
 namespace {
@@ -139,6 +140,9 @@ vs_status vs_workspace_init(const vs_shape* shape, void* workspace, size_t works
     if (!workspace) return VS_ERR_NULL;
     if (!aligned16(workspace)) return VS_ERR_ALIGN;
     if (workspace_bytes < control_block_bytes(*shape)) return VS_ERR_WORKSPACE;
+    // the first call on a device also finds out how that device deals workgroups to its XCDs
+    // (one tiny launch into the control block and a wait for it)
+    if (probe_xcd_mapping(workspace, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return VS_ERR_HIP;
     return launch_zero_fill(workspace, control_block_bytes(*shape), static_cast<hipStream_t>(hip_stream)) ==
                    hipSuccess ? VS_OK : VS_ERR_HIP;
 }
@@ -306,6 +310,10 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
         case VS_TUNE_SKIP_MERGE:
             if (value > 1) return VS_ERR_SHAPE;
             g_tune_skip_merge = value;
+            return VS_OK;
+        case VS_TUNE_PREFILL_MERGE:
+            if (value != 0 && value != 2) return VS_ERR_SHAPE;
+            g_tune_prefill_merge = value;
             return VS_OK;
         default: break;
     }

@@ -17,6 +17,7 @@ extern int g_tune_prefill_kv_groups;
 extern int g_tune_decode_chunk_rows;
 extern int g_tune_debug_mode;
 extern int g_tune_skip_merge;
+extern int g_tune_prefill_merge;  // 0 automatic, 2 always by the second kernel
 
 struct LenTable {
     int32_t v[kMaxStreamsPerLaunch];
@@ -61,6 +62,9 @@ inline size_t prefill_counter_offset(const vs_shape& s) {
     return (size_t)kMaxStreamsPerLaunch * s.n_kv_heads * sizeof(unsigned int);
 }
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t st);
+// Finds out once per device how workgroup ids are dealt to the XCDs (scratch: 256 bytes of device
+// memory; synchronises the stream the first time).
+hipError_t probe_xcd_mapping(void* scratch, hipStream_t st);
 
 // row copies
 hipError_t launch_append_rows(int32_t n_caches, void* k_slab, void* v_slab, int64_t cache_stride_bytes,

@@ -77,6 +77,13 @@ struct PrefillParams {
     int M, m_pad, nsplit, n_row_tiles;
     float scale_log2e;
     float inv_G, inv_nsplit;  // reciprocals for the index arithmetic of the prologue
+    // Merging inside this kernel (see the end of the kernel): the workgroups of one (row tile,
+    // KV head) unit are placed on one XCD and count their arrivals in `arrivals`; null = the
+    // partial results are merged by prefill_combine_kernel.
+    unsigned* arrivals;       // [Hkv][row tiles], zero between launches
+    int xcd_shift;            // log2 of the number of XCDs workgroup ids are dealt to in turn
+    int units_per_xcd;
+    float inv_row_tiles;
     unsigned long long* dbg;  // tuning aid: per-workgroup timestamps, normally null
 };
 
@@ -136,8 +143,25 @@ void prefill_mfma_kernel(PrefillParams p) {
     const int rb = w & 1;   // which 64 rows of the tile
     const int kg = w >> 1;  // key group of this wave
     const int l32 = lane & 31, hi = lane >> 5;
-    // grid (Hkv, nsplit, row tiles): x runs fastest in dispatch order
-    const int g = blockIdx.x, split = blockIdx.y, rt = blockIdx.z;
+    int g, split, rt;
+    if (p.arrivals) {
+        // 1-D grid.  Workgroup ids are dealt to the XCDs in turn (id mod number of XCDs), and a
+        // unit = (KV head, row tile) is merged through the L2 its XCD's compute units share, so
+        // all splits of a unit take ids of one residue: XCD x holds units x*units_per_xcd ..
+        // (consecutive units: the same KV head, whose K/V that L2 then holds once), each with
+        // nsplit consecutive slots.
+        const int x = blockIdx.x & ((1 << p.xcd_shift) - 1), slot = blockIdx.x >> p.xcd_shift;
+        const int j = div_small(slot, nsplit, inv_nsplit);
+        const int unit = x * p.units_per_xcd + j;
+        if (j >= p.units_per_xcd || unit >= p.n_row_tiles * Hkv) return;  // spare ids
+        split = slot - j * nsplit;
+        g = div_small(unit, p.n_row_tiles, p.inv_row_tiles);
+        rt = unit - g * p.n_row_tiles;
+    } else {
+        // grid (Hkv, nsplit, row tiles): x runs fastest in dispatch order, so with nsplit*Hkv a
+        // multiple of the number of XCDs all workgroups that read one K/V slice share an L2
+        g = blockIdx.x, split = blockIdx.y, rt = blockIdx.z;
+    }
     const int c = split * Hkv + g;  // which partial result
     const int wg_id = rt * (nsplit * Hkv) + c;
     const int kv_row_bytes = Hkv * kRowBytes;
@@ -556,7 +580,8 @@ void prefill_mfma_kernel(PrefillParams p) {
                     bf16x8 wv;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) wv[j] = (__bf16)(oo[db][8 * h2 + j] * inv);
-                    __builtin_nontemporal_store(wv, &po[(db * 2 + h2) * 64]);
+                    if (p.arrivals) po[(db * 2 + h2) * 64] = wv;  // read back from L2 by this launch
+                    else __builtin_nontemporal_store(wv, &po[(db * 2 + h2) * 64]);
                 }
             if (hi == 0) {
                 const int64_t prow = (int64_t)c * p.m_pad + r_mine[r];
@@ -610,6 +635,96 @@ void prefill_mfma_kernel(PrefillParams p) {
         if (kg == 0) hand_over(1); else hand_over(0);
         __syncthreads();
         if (kg == 0) take_over(0); else take_over(1);
+
+        if (p.arrivals) {
+            // ---- merge of the splits inside this launch.  Every workgroup has stored its
+            // partial result above (ordinary stores: they stay in the XCD's L2, and all splits
+            // of the unit run on this XCD).  Once the stores of all four wavefronts have been
+            // acknowledged the workgroup counts itself in; the one that finds all others
+            // counted reads their partials back from L2 and writes the unit's output rows.
+            // Nobody waits for anybody.  The sums run over the splits in index order and take
+            // this workgroup's own part rounded as stored, so the result does not depend on
+            // which workgroup comes last, and equals what prefill_combine_kernel computes. ----
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+            __syncthreads();                     // also: the exchange area is free again
+            unsigned* const box = reinterpret_cast<unsigned*>(dyn_smem);
+            unsigned* const counter = p.arrivals + g * p.n_row_tiles + rt;
+            if (tid == 0)
+                *box = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __syncthreads();
+            const unsigned before = *box;
+            if (before + 1 == (unsigned)nsplit) {
+                if (tid == 0) *counter = 0;  // zero again for the next launch
+                const int r = kg, rg = rb * 2 + r;
+                const bool row_ok = r_mine[r] < M;
+                const int t = row_ok ? div_small(r_mine[r], G, inv_G) : 0, hl = r_mine[r] - t * G;
+                __bf16* const orow = p.out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
+                const float* const ml0 = p.part_ml + ((int64_t)g * p.m_pad + r_mine[r]) * 2;
+                const int64_t ml_step = (int64_t)Hkv * p.m_pad * 2;      // floats between splits
+                const bf16x8* const po0 = reinterpret_cast<const bf16x8*>(p.part_o) +
+                                          (((int64_t)g * p.n_row_tiles + rt) * 4 + rg) * (8 * 64) + lane;
+                const int64_t po_step = (int64_t)Hkv * p.n_row_tiles * 4 * (8 * 64);  // bf16x8 between splits
+                // NS splits, the 8 pieces of a lane in PASSES rounds: everything of a round is
+                // requested before anything is used (a round trip to L2 is what this tail costs)
+                auto tail = [&](auto ns_tag, auto passes_tag) {
+                    constexpr int NS = decltype(ns_tag)::value, PASSES = decltype(passes_tag)::value, PIECES = 8 / PASSES;
+                    float2 ml[NS];
+                    bf16x8 v[NS][PIECES];
+#pragma unroll
+                    for (int u = 0; u < NS; ++u) ml[u] = *reinterpret_cast<const float2*>(ml0 + u * ml_step);
+#pragma unroll
+                    for (int pass = 0; pass < PASSES; ++pass) {
+#pragma unroll
+                        for (int u = 0; u < NS; ++u)
+#pragma unroll
+                            for (int k = 0; k < PIECES; ++k) v[u][k] = po0[u * po_step + (pass * PIECES + k) * 64];
+                        float m_star = -INFINITY;
+#pragma unroll
+                        for (int u = 0; u < NS; ++u) m_star = fmaxf(m_star, ml[u].x);
+                        float wgt[NS], denom = 0.f;
+#pragma unroll
+                        for (int u = 0; u < NS; ++u) {
+                            wgt[u] = (ml[u].x != -INFINITY) ? __builtin_amdgcn_exp2f(ml[u].x - m_star) * ml[u].y : 0.f;
+                            denom += wgt[u];
+                        }
+                        const float inv = 1.0f / denom;
+#pragma unroll
+                        for (int k = 0; k < PIECES; ++k) {
+                            float acc[8];
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+#pragma unroll
+                            for (int u = 0; u < NS; ++u)
+#pragma unroll
+                                for (int j = 0; j < 8; ++j) acc[j] += wgt[u] * (float)v[u][k][j];
+                            if (row_ok) {
+                                // piece (db, h2) = ((pass*PIECES + k) >> 1, & 1): dims 32 db + 16 h2 + 4 hi + 0..3, + 8
+                                const int piece = pass * PIECES + k;
+                                bf16x4 w0, w1;
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    w0[j] = (__bf16)(acc[j] * inv);
+                                    w1[j] = (__bf16)(acc[4 + j] * inv);
+                                }
+                                __bf16* dst = orow + 16 * piece + 4 * hi;
+                                *reinterpret_cast<bf16x4*>(dst) = w0;
+                                *reinterpret_cast<bf16x4*>(dst + 8) = w1;
+                            }
+                        }
+                    }
+                };
+                using std::integral_constant;
+                switch (nsplit) {
+                    case 2: tail(integral_constant<int, 2>{}, integral_constant<int, 1>{}); break;
+                    case 3: tail(integral_constant<int, 3>{}, integral_constant<int, 1>{}); break;
+                    case 4: tail(integral_constant<int, 4>{}, integral_constant<int, 1>{}); break;
+                    case 5: tail(integral_constant<int, 5>{}, integral_constant<int, 1>{}); break;
+                    case 6: tail(integral_constant<int, 6>{}, integral_constant<int, 1>{}); break;
+                    case 7: tail(integral_constant<int, 7>{}, integral_constant<int, 2>{}); break;
+                    default: tail(integral_constant<int, 8>{}, integral_constant<int, 2>{}); break;
+                }
+            }
+        }
     }
     if (p.dbg && tid == 0) {
         unsigned long long* d = p.dbg + (size_t)wg_id * 4;
@@ -620,7 +735,7 @@ void prefill_mfma_kernel(PrefillParams p) {
 // Merge of the per-split partials: out = sum_s w_s l_s Ohat_s / sum_s w_s l_s with
 // w_s = 2^(m_s - m*).  One 64-thread block per (row tile, row group, dim block, half): the same
 // lane -> element mapping as the attention kernel, so the partials are read 1 KB at a time; all
-// loads of up to 8 splits are issued before any is used.
+// loads of up to 8 splits, references and sums included, are issued before any is used.
 __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
     const int lane = threadIdx.x, l32 = lane & 31, hi = lane >> 5;
     int b = blockIdx.x;
@@ -635,26 +750,41 @@ __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-    float mstar = -INFINITY;
-    for (int s = 0; s < p.nsplit; ++s)
-        mstar = fmaxf(mstar, p.part_ml[((int64_t)(s * p.Hkv + g) * p.m_pad + rr) * 2]);
-    float denom = 0.f;
+    // Up to 8 splits at a time: everything of a chunk is requested before anything is used (one
+    // memory round trip for the usual case), and chunks are merged like sub-blocks of the online
+    // softmax, against the running reference m_run.
+    float m_run = -INFINITY, denom = 0.f;
     for (int s0 = 0; s0 < p.nsplit; s0 += 8) {
         float ms[8], ls[8];
         bf16x8 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int s = min(s0 + u, p.nsplit - 1);
-            const int c = s * p.Hkv + g;
-            const int64_t prow = (int64_t)c * p.m_pad + rr;
-            ms[u] = p.part_ml[prow * 2];
-            ls[u] = p.part_ml[prow * 2 + 1];
-            const int64_t unit = (int64_t)c * p.n_row_tiles + rt;
-            v[u] = (reinterpret_cast<const bf16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane)[(db * 2 + h2) * 64];
+            ms[u] = -INFINITY;
+            ls[u] = 0.f;
+            if (s0 + u < p.nsplit) {
+                const int c = (s0 + u) * p.Hkv + g;
+                const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + ((int64_t)c * p.m_pad + rr) * 2);
+                ms[u] = ml.x;
+                ls[u] = ml.y;
+                const int64_t unit = (int64_t)c * p.n_row_tiles + rt;
+                v[u] = (reinterpret_cast<const bf16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane)[(db * 2 + h2) * 64];
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[u][j] = (__bf16)0.f;
+            }
         }
+        float m_new = m_run;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) m_new = fmaxf(m_new, ms[u]);
+        if (m_new == -INFINITY) continue;  // nothing in these splits (and nothing before)
+        const float keep = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 for the first chunk with content
+        denom *= keep;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] *= keep;
+        m_run = m_new;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const float w = (s0 + u < p.nsplit && ms[u] != -INFINITY) ? __builtin_amdgcn_exp2f(ms[u] - mstar) * ls[u] : 0.f;
+            const float w = (ms[u] != -INFINITY) ? __builtin_amdgcn_exp2f(ms[u] - m_new) * ls[u] : 0.f;
             denom += w;
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] += w * (float)v[u][j];
@@ -676,7 +806,19 @@ __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
 
 struct Plan {
     int kvg, n_row_tiles, m_pad, nsplit;
+    bool merge_inside;  // the attention kernel merges the splits itself
 };
+
+// How this device deals workgroup ids to its XCDs, found once per device by xcd_probe_kernel:
+// log2 of the number of XCDs if ids go to them in turn (id mod count), -1 if not (or not yet
+// probed): then the splits are merged by the second kernel.
+int g_xcd_shift[16] = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1};
+
+__global__ void xcd_probe_kernel(unsigned* out) {
+    unsigned x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+    if (threadIdx.x == 0) out[blockIdx.x] = x & 15u;
+}
 
 Plan make_plan(const vs_shape& s, int n_tokens, int len) {
     const int G = s.n_q_heads / s.n_kv_heads;
@@ -699,6 +841,9 @@ Plan make_plan(const vs_shape& s, int n_tokens, int len) {
     if (ns >= step) ns -= ns % step;
     if (g_tune_prefill_splits) ns = g_tune_prefill_splits < max_tiles ? g_tune_prefill_splits : (max_tiles > 0 ? max_tiles : 1);
     pl.nsplit = ns;
+    int dev = 0;
+    pl.merge_inside = g_tune_prefill_merge != 2 && pl.kvg == 2 && ns > 1 && ns <= 8 && pl.n_row_tiles <= kMaxRowTiles &&
+                      hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && g_xcd_shift[dev] >= 0;
     return pl;
 }
 
@@ -713,15 +858,40 @@ hipError_t launch_kvg(const PrefillParams& p, const Plan& pl, int n_kv_heads, hi
         attr_set = true;
     }
     // x runs fastest in dispatch order: all workgroups that read one K/V slice are neighbours
-    const dim3 grid(n_kv_heads, pl.nsplit, pl.n_row_tiles);
+    const dim3 grid = p.arrivals ? dim3((unsigned)((p.units_per_xcd * pl.nsplit) << p.xcd_shift))
+                                 : dim3(n_kv_heads, pl.nsplit, pl.n_row_tiles);
     prefill_mfma_kernel<KVG><<<grid, kGroupThreads * KVG, kLds, st>>>(p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.nsplit == 1 || g_tune_skip_merge) return e;
+    if (e != hipSuccess || pl.nsplit == 1 || g_tune_skip_merge || p.arrivals) return e;
     prefill_combine_kernel<<<dim3(pl.n_row_tiles * 4 * 4 * 2, n_kv_heads), 64, 0, st>>>(p);
     return hipGetLastError();
 }
 
 }  // namespace
+
+hipError_t probe_xcd_mapping(void* scratch, hipStream_t st) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= 16 || g_xcd_shift[dev] >= 0) return e;
+    constexpr int kProbe = 64;
+    unsigned ids[kProbe];
+    xcd_probe_kernel<<<kProbe, 64, 0, st>>>((unsigned*)scratch);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = hipMemcpyAsync(ids, scratch, sizeof(ids), hipMemcpyDeviceToHost, st)) != hipSuccess) return e;
+    if ((e = hipStreamSynchronize(st)) != hipSuccess) return e;
+    for (int shift = 0; shift <= 4; ++shift) {
+        const int n = 1 << shift;
+        bool ok = true;
+        for (int i = 0; i < kProbe && ok; ++i) ok = ids[i] == ids[i % n];          // period n
+        for (int i = 0; i < n && ok; ++i)
+            for (int j = 0; j < i && ok; ++j) ok = ids[i] != ids[j];                // n different XCDs
+        if (ok) {
+            g_xcd_shift[dev] = shift;
+            break;
+        }
+    }
+    return hipSuccess;
+}
 
 size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens) {
     const int G = s.n_q_heads / s.n_kv_heads;
@@ -733,7 +903,7 @@ size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens) {
 
 hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc, int32_t len,
                                const void* q, const void* kf, const void* vf, int32_t n_tokens,
-                               void* out, void* k_append_dst, void* v_append_dst, void* /*counters*/,
+                               void* out, void* k_append_dst, void* v_append_dst, void* counters,
                                void* workspace, hipStream_t st) {
     const Plan pl = make_plan(s, n_tokens, len);
     PrefillParams p;
@@ -757,6 +927,17 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
     p.scale_log2e = s.softmax_scale * kLog2e;
     p.inv_G = 1.0f / (float)p.G;
     p.inv_nsplit = 1.0f / (float)pl.nsplit;
+    p.arrivals = nullptr;
+    p.xcd_shift = p.units_per_xcd = 0;
+    p.inv_row_tiles = 1.0f / (float)pl.n_row_tiles;
+    if (pl.merge_inside && counters) {
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        p.arrivals = (unsigned*)counters;
+        p.xcd_shift = g_xcd_shift[dev];
+        const int units = pl.n_row_tiles * s.n_kv_heads, n_xcd = 1 << p.xcd_shift;
+        p.units_per_xcd = (units + n_xcd - 1) / n_xcd;
+    }
     const int64_t slots = (int64_t)pl.nsplit * s.n_kv_heads * pl.m_pad;
     p.part_ml = (float*)workspace;
     p.part_o = (__bf16*)(p.part_ml + slots * 2);

@@ -22,7 +22,7 @@ QW = CONFIGS["cfg2"]["shape"]
 @pytest.fixture(autouse=True)
 def _reset_tuning():
     yield
-    for knob in (0, 1, 2, 3):
+    for knob in (0, 1, 2, 3, 4):
         vs.set_tuning(knob, 0)
 
 
@@ -239,6 +239,26 @@ def test_prefill_result_does_not_depend_on_the_split(kv_groups):
         outs.append(out.float())
     for o in outs[1:]:
         assert (o - outs[0]).abs().max().item() <= 2 ** -7 * outs[0].abs().max().item()
+
+
+@pytest.mark.parametrize("L,T,splits", [(4424, 170, 0), (1500, 170, 0), (1500, 170, 3), (3000, 300, 8), (700, 40, 2)])
+def test_prefill_merge_inside_the_kernel_equals_the_second_kernel(L, T, splits):
+    """Split results are merged either by the last workgroup of a row tile to arrive, inside the
+    attention kernel, or by a second kernel: the same sums in the same order, so the same bits;
+    also on repeated calls through one workspace (the arrival counters return to zero)."""
+    s = QW
+    hk, hv = cache_rows(31, s, L, 0.5)
+    q, kf, vf = frame_inputs(31, s, T, 0.5, q_gain=4)
+    ref = oracle_prefill_rows(s, q, hk, hv, L, kf, vf)
+    ws = workspace(s, T, L, 0)
+    vs.set_tuning(vs.TUNE_PREFILL_SPLITS, splits)
+    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 2)
+    two_kernels, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
+    check_close(two_kernels, ref, "bf16", f"second-kernel merge L={L} T={T} splits={splits}")
+    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
+    for rep in range(3):
+        inside, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
+        assert same_bits(inside, two_kernels.cpu()), f"merge inside the kernel differs (call {rep})"
 
 
 @pytest.mark.parametrize("L", [130, 1500])
