@@ -31,9 +31,11 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # kernels (profiles/*.md), scaled by what the same counters read for a plain 1 GiB copy
 # (FETCH_SIZE x2.0, WRITE_SIZE x1.0).  Static because counters cannot be read inside a timed run.
 TRAFFIC = {
-    "prefill_mfma_kernel": {"fetch_bytes": 13.63e6, "write_bytes": 8.11e6,
-                            "note": "cfg3 launch shape; algorithmic 11.84e6 bytes; the writes are the bf16 "
-                                    "partial results of the 6 key splits (7.9e6), merged by the second kernel"},
+    "prefill_mfma_kernel": {"fetch_bytes": 28.14e6, "write_bytes": 9.34e6,
+                            "note": "cfg3 launch shape; algorithmic 11.85e6 bytes; on top of that the bf16 partial "
+                                    "results of the 6 key splits are written (7.9e6) and read back by the merging "
+                                    "workgroups (7.9e6), and each head's K/V is fetched by the two XCDs that "
+                                    "hold its row tiles (+9e6)"},
     "decode_mfma_kernel": {"fetch_bytes": 159.5e6, "write_bytes": 3.72e6,
                            "note": "cfg4 launch shape; algorithmic 159.4e6 bytes; the writes are the bf16 "
                                    "partial results of the wavefronts and the appended rows"},
@@ -186,9 +188,10 @@ def main():
         gpu_ms = ev0.elapsed_time(ev1)
         assert all(cch.len == P0 + K for cch in caches)
         # Second pass, for the roofline of the dominant kernel: the same K x 28 launches with the
-        # split-merge kernel and the mean pool switched off, so that the stream holds nothing but
-        # attention kernels back to back; HIP events on the launch stream around the whole run,
-        # divided by the number of launches.  (Events around single launches read 3-6 us more
+        # mean pool switched off, so that the stream holds nothing but attention kernels back to
+        # back (the kernel merges its key splits itself; where the library falls back to a second
+        # merge kernel, TUNE_SKIP_MERGE leaves that one out); HIP events on the launch stream
+        # around the whole run, divided by the number of launches.  (Events around single launches read 3-6 us more
         # than the kernel's own start-to-end time; a run of launches back to back reads what
         # rocprofv3 --kernel-trace reports as the average duration, plus the dispatch gap.)
         vs.set_tuning(vs.TUNE_SKIP_MERGE, 1)
@@ -201,9 +204,20 @@ def main():
         run_frames(K, pool=False)
         kb.record()
         torch.cuda.synchronize()
-        vs.set_tuning(vs.TUNE_SKIP_MERGE, 0)
         n_launch = K * NL
         launch_s = ka.elapsed_time(kb) * 1e-3 / n_launch
+        # context: the same with the merge left to the second kernel, and that kernel left out
+        vs.set_tuning(vs.TUNE_PREFILL_MERGE, 2)
+        reset()
+        kc_, kd_ = event_pair()
+        torch.cuda.synchronize()
+        kc_.record()
+        run_frames(K, pool=False)
+        kd_.record()
+        torch.cuda.synchronize()
+        bare_s = kc_.elapsed_time(kd_) * 1e-3 / n_launch
+        vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
+        vs.set_tuning(vs.TUNE_SKIP_MERGE, 0)
         fl = np.array([prefill_flops(s, P0 + f, T) for f in range(K)], dtype=np.float64)
         by = np.array([prefill_bytes(s, P0 + f, T) for f in range(K)], dtype=np.float64)
         achieved = float(fl.mean() / launch_s / 1e12)
@@ -212,16 +226,22 @@ def main():
             roofline=dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                           frac=achieved / PEAK_BF16_TFLOPS,
                           traffic=TRAFFIC.get("prefill_mfma_kernel"),
-                          kernel="prefill_mfma_kernel<2> (attention + fused carrier compaction)",
+                          kernel="prefill_mfma_kernel<2> (attention + merge of the key splits by the last workgroup "
+                                 "of a row tile + fused carrier compaction)",
                           avg_launch_us=float(launch_s * 1e6), launches_timed=n_launch,
                           timing="HIP events on the launch stream around K x 28 attention launches back to back "
-                                 "(merge kernel and mean pool off), divided by the number of launches",
+                                 "(mean pool off), divided by the number of launches",
+                          without_merge=dict(avg_launch_us=float(bare_s * 1e6),
+                                             tflops=float(fl.mean() / bare_s / 1e12),
+                                             frac=float(fl.mean() / bare_s / 1e12 / PEAK_BF16_TFLOPS),
+                                             note="same kernel with the merge left to a second kernel that is "
+                                                  "not launched: the attention part alone, context only"),
                           layer_period_us=float(gpu_ms * 1e3 / n_launch),
                           algorithmic_gflop_per_launch=float(fl.mean() / 1e9),
                           algorithmic_mbytes_per_launch=float(by.mean() / 1e6)))
         log(f"[bench] cfg3: {K / wall:.1f} frames/s, {wall * 1e3 / K:.3f} ms/frame ({gpu_ms * 1e3 / n_launch:.1f} us per "
             f"layer); attention kernel {launch_s * 1e6:.1f} us = {achieved:.1f} TFLOP/s "
-            f"({100 * achieved / PEAK_BF16_TFLOPS:.1f}% of bf16 peak)")
+            f"({100 * achieved / PEAK_BF16_TFLOPS:.1f}% of bf16 peak); without its merge part {bare_s * 1e6:.1f} us")
         del qp, kp, vp
 
     # ------------------------------------------------------------------ CPU baseline (oracle)
