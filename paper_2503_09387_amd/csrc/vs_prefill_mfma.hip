@@ -13,12 +13,15 @@
 //     slot permuted by the row number so that both the row-wise K reads and the transposing
 //     V reads are free of bank conflicts without padding.  One barrier per tile.
 //   * Too few rows exist to fill 256 compute units, so the key tiles a row tile can see are
-//     split twice: across `nsplit` workgroups (shares weighted by cost: a tile with frame
-//     rows counts double), and inside a workgroup across NKG "key groups" of two wavefronts
-//     that take alternate tiles and are merged through LDS at the end (each group closes one
-//     half of the rows).  One wavefront per SIMD: it owns all 512 registers.  The
-//     per-workgroup partials (reference, sum, normalised accumulator in bf16) are merged by
-//     a second small kernel.
+//     split twice: across `nsplit` workgroups, and inside a workgroup across NKG "key groups"
+//     of two wavefronts that are merged through LDS at the end (each group closes one half
+//     of the rows).  Tiles are dealt to the (split, key group) lanes in whole tiles, equally
+//     many per lane; the tiles that hold frame rows are spread over the lanes and come first
+//     in their lane.  One wavefront per SIMD: it owns all 512 registers.
+//   * The per-workgroup partials (reference, sum, normalised accumulator in bf16) are merged
+//     inside the launch by the last workgroup of a row tile to arrive (all splits of a row
+//     tile run on one XCD and count themselves in through its L2; nobody waits), or, where
+//     that is not possible, by a second small kernel.  Same sums, same order, same bits.
 //   * Scores are computed transposed, S^T = K Q^T (v_mfma_f32_32x32x16_bf16), so that a
 //     lane owns one query column: softmax statistics stay in the lane, and the
 //     probabilities are already laid out as the B operand of O^T += V^T P^T.  V^T comes
@@ -33,9 +36,8 @@
 //     a row sum comes out above 2^8, or a row without history underflows, is the sub-block
 //     redone exactly from its raw scores (true maximum, accumulators rescaled).  After the
 //     first sub-block that is rare.
-//   * Workgroup id = row_tile * (nsplit*Hkv) + (split*Hkv + kv_head): with nsplit*Hkv a
-//     multiple of 8, all workgroups that read one K/V slice run on one XCD (ids are
-//     dealt round-robin to the 8 XCDs) and share its L2.
+//   * Workgroup ids are dealt to the 8 XCDs in turn, and each XCD has its own L2: ids are
+//     chosen so that the workgroups of one KV head sit on as few XCDs as possible.
 #include <type_traits>
 
 #include "vs_internal.h"
