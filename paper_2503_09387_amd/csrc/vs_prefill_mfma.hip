@@ -637,27 +637,32 @@ void prefill_mfma_kernel(PrefillParams p) {
         if (kg == 0) hand_over(1); else hand_over(0);
         __syncthreads();
         if (kg == 0) take_over(0); else take_over(1);
+    }
 
-        if (p.arrivals) {
-            // ---- merge of the splits inside this launch.  Every workgroup has stored its
-            // partial result above (ordinary stores: they stay in the XCD's L2, and all splits
-            // of the unit run on this XCD).  Once the stores of all four wavefronts have been
-            // acknowledged the workgroup counts itself in; the one that finds all others
-            // counted reads their partials back from L2 and writes the unit's output rows.
-            // Nobody waits for anybody.  The sums run over the splits in index order and take
-            // this workgroup's own part rounded as stored, so the result does not depend on
-            // which workgroup comes last, and equals what prefill_combine_kernel computes. ----
-            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-            __syncthreads();                     // also: the exchange area is free again
-            unsigned* const box = reinterpret_cast<unsigned*>(dyn_smem);
-            unsigned* const counter = p.arrivals + g * p.n_row_tiles + rt;
-            if (tid == 0)
-                *box = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            __syncthreads();
-            const unsigned before = *box;
-            if (before + 1 == (unsigned)nsplit) {
-                if (tid == 0) *counter = 0;  // zero again for the next launch
-                const int r = kg, rg = rb * 2 + r;
+    if (p.arrivals) {
+        // ---- merge of the splits inside this launch.  Every workgroup has stored its
+        // partial result above (ordinary stores: they stay in the XCD's L2, and all splits
+        // of the unit run on this XCD).  Once the stores of all its wavefronts have been
+        // acknowledged the workgroup counts itself in; the one that finds all others
+        // counted reads their partials back from L2 and writes the unit's output rows.
+        // Nobody waits for anybody.  The sums run over the splits in index order and take
+        // this workgroup's own part rounded as stored, so the result does not depend on
+        // which workgroup comes last, and equals what prefill_combine_kernel computes. ----
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        __syncthreads();                     // also: the exchange area is free again
+        unsigned* const box = reinterpret_cast<unsigned*>(dyn_smem);
+        unsigned* const counter = p.arrivals + g * p.n_row_tiles + rt;
+        if (tid == 0)
+            *box = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __syncthreads();
+        const unsigned before = *box;
+        if (before + 1 == (unsigned)nsplit) {
+            if (tid == 0) *counter = 0;  // zero again for the next launch
+            // the rows this wavefront has closed: row group kg of its 64 rows, or both
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                if (NKG == 2 && r != kg) continue;
+                const int rg = rb * 2 + r;
                 const bool row_ok = r_mine[r] < M;
                 const int t = row_ok ? div_small(r_mine[r], G, inv_G) : 0, hl = r_mine[r] - t * G;
                 __bf16* const orow = p.out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
@@ -672,14 +677,19 @@ void prefill_mfma_kernel(PrefillParams p) {
                     constexpr int NS = decltype(ns_tag)::value, PASSES = decltype(passes_tag)::value, PIECES = 8 / PASSES;
                     float2 ml[NS];
                     bf16x8 v[NS][PIECES];
+                    // (addresses are worked out here, per case: an opaque copy of the bases keeps the
+                    // compiler from preparing those of all cases ahead of the switch)
+                    const float* mlb = ml0;
+                    const bf16x8* pob = po0;
+                    asm volatile("" : "+v"(mlb), "+v"(pob));
 #pragma unroll
-                    for (int u = 0; u < NS; ++u) ml[u] = *reinterpret_cast<const float2*>(ml0 + u * ml_step);
+                    for (int u = 0; u < NS; ++u) ml[u] = *reinterpret_cast<const float2*>(mlb + u * ml_step);
 #pragma unroll
                     for (int pass = 0; pass < PASSES; ++pass) {
 #pragma unroll
                         for (int u = 0; u < NS; ++u)
 #pragma unroll
-                            for (int k = 0; k < PIECES; ++k) v[u][k] = po0[u * po_step + (pass * PIECES + k) * 64];
+                            for (int k = 0; k < PIECES; ++k) v[u][k] = pob[u * po_step + (pass * PIECES + k) * 64];
                         float m_star = -INFINITY;
 #pragma unroll
                         for (int u = 0; u < NS; ++u) m_star = fmaxf(m_star, ml[u].x);
@@ -716,15 +726,17 @@ void prefill_mfma_kernel(PrefillParams p) {
                     }
                 };
                 using std::integral_constant;
+                constexpr int kPasses = NKG == 1 ? 2 : 1;  // (one key group: two row groups to do, fewer registers each)
                 switch (nsplit) {
-                    case 2: tail(integral_constant<int, 2>{}, integral_constant<int, 1>{}); break;
-                    case 3: tail(integral_constant<int, 3>{}, integral_constant<int, 1>{}); break;
-                    case 4: tail(integral_constant<int, 4>{}, integral_constant<int, 1>{}); break;
-                    case 5: tail(integral_constant<int, 5>{}, integral_constant<int, 1>{}); break;
-                    case 6: tail(integral_constant<int, 6>{}, integral_constant<int, 1>{}); break;
+                    case 2: tail(integral_constant<int, 2>{}, integral_constant<int, kPasses>{}); break;
+                    case 3: tail(integral_constant<int, 3>{}, integral_constant<int, kPasses>{}); break;
+                    case 4: tail(integral_constant<int, 4>{}, integral_constant<int, kPasses>{}); break;
+                    case 5: tail(integral_constant<int, 5>{}, integral_constant<int, kPasses>{}); break;
+                    case 6: tail(integral_constant<int, 6>{}, integral_constant<int, kPasses>{}); break;
                     case 7: tail(integral_constant<int, 7>{}, integral_constant<int, 2>{}); break;
                     default: tail(integral_constant<int, 8>{}, integral_constant<int, 2>{}); break;
                 }
+                __builtin_amdgcn_sched_barrier(0);  // one row group at a time: its loads fill the registers
             }
         }
     }
@@ -844,7 +856,7 @@ Plan make_plan(const vs_shape& s, int n_tokens, int len) {
     if (g_tune_prefill_splits) ns = g_tune_prefill_splits < max_tiles ? g_tune_prefill_splits : (max_tiles > 0 ? max_tiles : 1);
     pl.nsplit = ns;
     int dev = 0;
-    pl.merge_inside = g_tune_prefill_merge != 2 && pl.kvg == 2 && ns > 1 && ns <= 8 && pl.n_row_tiles <= kMaxRowTiles &&
+    pl.merge_inside = g_tune_prefill_merge != 2 && ns > 1 && ns <= 8 && pl.n_row_tiles <= kMaxRowTiles &&
                       hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && g_xcd_shift[dev] >= 0;
     return pl;
 }

@@ -241,7 +241,8 @@ def test_prefill_result_does_not_depend_on_the_split(kv_groups):
         assert (o - outs[0]).abs().max().item() <= 2 ** -7 * outs[0].abs().max().item()
 
 
-@pytest.mark.parametrize("L,T,splits", [(4424, 170, 0), (1500, 170, 0), (1500, 170, 3), (3000, 300, 8), (700, 40, 2)])
+@pytest.mark.parametrize("L,T,splits", [(4424, 170, 0), (1500, 170, 0), (1500, 170, 3), (3000, 300, 8), (700, 40, 2),
+                                          (200, 170, 0), (264, 170, 3), (100, 20, 2)])
 def test_prefill_merge_inside_the_kernel_equals_the_second_kernel(L, T, splits):
     """Split results are merged either by the last workgroup of a row tile to arrive, inside the
     attention kernel, or by a second kernel: the same sums in the same order, so the same bits;
