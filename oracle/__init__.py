@@ -5,6 +5,8 @@ package.  It shares no code with the GPU library and never imports it.
 """
 from .vs_oracle import (  # noqa: F401
     attention,
+    bank_apply,
+    bank_victim,
     compact_append,
     decode,
     frame_prefill,

@@ -15,6 +15,8 @@
  *     the frame's tokens are run through the decoder once.
  *   - Section 3.3, decoding phase: visual tokens are discarded afterwards;
  *     decoding reads the retained carrier K/V only.
+ *   - Section 3.3, memory mechanism: a bank of at most M carriers; at
+ *     capacity the older carrier of the most similar adjacent pair is dropped.
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   - every token of the frame run sees all retained cache rows; inside the
@@ -211,5 +213,71 @@ int vs_oracle_mean_pool(const double *E, int64_t N, int64_t d, double *c) {
         for (int64_t i = 0; i < N; ++i) s += E[(size_t)i * d + j];
         c[j] = s / (double)N;
     }
+    return VSO_OK;
+}
+
+/*
+ * Memory bank with capacity M (Section 3.3, memory mechanism): the bank keeps
+ * the embeddings of at most M semantic carriers, oldest first, together with
+ * their K/V rows.  When a carrier arrives at a full bank, embeddings of
+ * adjacent carriers are compared and the older one of the most similar pair
+ * is dropped.  Reading taken here (the passage is ambiguous, see the design
+ * notes): the sequence s_0 .. s_{M-1} (bank, oldest first), s_M (incoming) has
+ * M adjacent pairs (i, i+1); the victim is the i with the largest cosine
+ * cos(s_i, s_{i+1}); of equal cosines the smallest i.  policy 1 is the other
+ * reading: the i < M with the largest cos(s_i, s_M).  A vector of norm 0 has
+ * cosine 0 with everything.
+ *
+ * E [M][d] bank embeddings, e_new [d].  Writes the M cosines to cosines (may
+ * be NULL) and the victim's index to *victim.
+ */
+int vs_oracle_bank_victim(const double *E, int64_t M, int64_t d, const double *e_new, int32_t policy,
+                          double *cosines, int64_t *victim) {
+    if (!E || !e_new || !victim || M < 1 || d < 1 || (policy != 0 && policy != 1)) return VSO_ERR_ARG;
+    int64_t best = 0;
+    double best_cos = 0.0;
+    for (int64_t i = 0; i < M; ++i) {
+        const double *a = E + (size_t)i * d;
+        const double *b = (policy == 1 || i + 1 == M) ? e_new : E + (size_t)(i + 1) * d;
+        double ab = 0.0, aa = 0.0, bb = 0.0;
+        for (int64_t j = 0; j < d; ++j) {
+            ab += a[j] * b[j];
+            aa += a[j] * a[j];
+            bb += b[j] * b[j];
+        }
+        const double c = (aa > 0.0 && bb > 0.0) ? ab / (sqrt(aa) * sqrt(bb)) : 0.0;
+        if (cosines) cosines[i] = c;
+        if (i == 0 || c > best_cos) {
+            best = i;
+            best_cos = c;
+        }
+    }
+    *victim = best;
+    return VSO_OK;
+}
+
+/*
+ * One carrier arrives at the bank.  rows [capacity][width] is any of the
+ * per-carrier tables kept in step with the bank (the embeddings, or one
+ * layer's K or V rows behind `first` rows that are not carriers, e.g. a text
+ * prefix); n = carriers held before the call (n <= M, first + M <= capacity).
+ * With room left the new row is appended at first + n; with the bank full
+ * (n == M) row first + victim is removed, the rows behind it move up by one
+ * and the new row becomes the last.  Returns the count after the call in *n_out.
+ */
+int vs_oracle_bank_apply(double *rows, int64_t capacity, int64_t width, int64_t first, int64_t M, int64_t n,
+                         int64_t victim, const double *row_new, int64_t *n_out) {
+    if (!rows || !row_new || !n_out || width < 1 || first < 0 || M < 1 || n < 0 || n > M) return VSO_ERR_ARG;
+    if (first + M > capacity) return VSO_ERR_CAPACITY;
+    if (n < M) {
+        memcpy(rows + (size_t)(first + n) * width, row_new, (size_t)width * sizeof(double));
+        *n_out = n + 1;
+        return VSO_OK;
+    }
+    if (victim < 0 || victim >= M) return VSO_ERR_ARG;
+    for (int64_t r = victim; r + 1 < M; ++r)
+        memcpy(rows + (size_t)(first + r) * width, rows + (size_t)(first + r + 1) * width, (size_t)width * sizeof(double));
+    memcpy(rows + (size_t)(first + M - 1) * width, row_new, (size_t)width * sizeof(double));
+    *n_out = M;
     return VSO_OK;
 }

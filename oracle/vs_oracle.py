@@ -39,6 +39,8 @@ def _lib():
         lib.vs_oracle_compact_append.argtypes = [dp, dp, i64, ip, dp, dp, i64, i64, i32, i32, ip]
         lib.vs_oracle_decode.argtypes = [dp, dp, dp, i64, ip, dp, dp, i32, i32, i32, f64, dp]
         lib.vs_oracle_mean_pool.argtypes = [dp, i64, i64, dp]
+        lib.vs_oracle_bank_victim.argtypes = [dp, i64, i64, dp, i32, dp, ip]
+        lib.vs_oracle_bank_apply.argtypes = [dp, i64, i64, i64, i64, i64, i64, dp, ip]
         _LIB = lib
     return _LIB
 
@@ -144,3 +146,31 @@ def mean_pool(E):
     if rc:
         raise OracleError(rc, "mean_pool")
     return c
+
+
+def bank_victim(E, e_new, policy=0):
+    """Section 3.3, memory mechanism: which carrier a full bank drops.  E [M][d] bank embeddings
+    (oldest first), e_new [d].  Returns (victim index, cosines [M])."""
+    E, e_new = _c(E), _c(e_new)
+    M, d = E.shape
+    cos = np.empty(M, dtype=np.float64)
+    victim = ctypes.c_int64(-1)
+    rc = _lib().vs_oracle_bank_victim(_p(E), M, d, _p(e_new), policy, _p(cos), ctypes.byref(victim))
+    if rc:
+        raise OracleError(rc, "bank_victim")
+    return int(victim.value), cos
+
+
+def bank_apply(rows, first, M, n, victim, row_new):
+    """A carrier arrives: rows [capacity][...] (modified in place) holds n <= M carrier rows behind
+    `first` other rows.  Appends, or drops row first+victim, closes the gap and puts the new row
+    last.  Returns the carrier count after the call."""
+    assert rows.dtype == np.float64 and rows.flags.c_contiguous
+    width = int(np.prod(rows.shape[1:]))
+    row_new = _c(row_new).reshape(-1)
+    assert row_new.size == width
+    n_out = ctypes.c_int64(-1)
+    rc = _lib().vs_oracle_bank_apply(_p(rows), rows.shape[0], width, first, M, n, victim, _p(row_new), ctypes.byref(n_out))
+    if rc:
+        raise OracleError(rc, "bank_apply")
+    return int(n_out.value)

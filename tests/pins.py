@@ -378,6 +378,76 @@ def pin_mean_pool(impl):
     assert np.array_equal(impl.mean_pool(E2), np.array([4.0, 5.0, 6.0, 7.0]))
 
 
+def pin_memory_bank(impl):
+    """Section 3.3, memory mechanism: at capacity the OLDER carrier of the most similar ADJACENT
+    pair goes (the incoming carrier is the last element of the sequence); order is kept, the
+    incoming carrier becomes the last."""
+    # closed form: unit vectors at known angles.  s_i = (cos t_i, sin t_i): cos(s_i, s_j) = cos(t_i - t_j)
+    t = np.array([0.0, 1.0, 1.9, 2.0, 3.5, 5.0])           # bank of 5 + incoming at 5.0
+    S = np.stack([np.cos(t), np.sin(t)], axis=1)
+    v, c = impl.bank_victim(S[:5], S[5])
+    _close(c, np.cos(np.diff(t)), 1e-14, "cosines of adjacent pairs, the last pair with the incoming one")
+    assert v == 2, "pair (1.9, 2.0) is the most similar one; its OLDER member is index 2"
+    # the other reading: similarity to the incoming carrier only
+    v1, c1 = impl.bank_victim(S[:5], S[5], 1)
+    _close(c1, np.cos(t[:5] - t[5]), 1e-14, "cosines with the incoming carrier")
+    assert v1 == int(np.argmax(np.cos(t[:5] - t[5])))
+    # cosine, not dot product: scaling any vector changes nothing; a long vector does not win
+    r = _rng(31)
+    E, e = r.normal(size=(9, 12)), r.normal(size=12)
+    v0, c0 = impl.bank_victim(E, e)
+    scale = r.uniform(0.1, 50.0, size=(9, 1))
+    v2, c2 = impl.bank_victim(E * scale, e * 7.0)
+    assert v2 == v0
+    _close(c2, c0, 1e-13, "scale invariance")
+    # brute force with math.fsum
+    seq = np.concatenate([E, e[None]])
+    want = []
+    for i in range(9):
+        a, b = seq[i], seq[i + 1]
+        want.append(math.fsum(a * b) / math.sqrt(math.fsum(a * a) * math.fsum(b * b)))
+    _close(c0, np.array(want), 1e-14, "brute force cosines")
+    assert v0 == int(np.argmax(want))
+    # the incoming carrier takes part: a bank of mutually orthogonal vectors and an incoming copy of the last
+    E = np.eye(6)[:5] * 3.0
+    v, c = impl.bank_victim(E, E[4] * 0.5)
+    assert v == 4 and c[4] == 1.0 and np.all(c[:4] == 0.0)
+    # ties: the smallest index (the oldest pair)
+    E = np.array([[1.0, 0], [1, 0], [0, 1], [0, 1], [1, 1]])
+    v, c = impl.bank_victim(E, np.array([-1.0, 0.0]))
+    assert c[0] == c[2] == 1.0 and v == 0
+    # a zero vector has cosine 0 with everything (and is never not-a-number)
+    E = np.array([[0.0, 0], [1, 0], [-1, 0.1]])
+    v, c = impl.bank_victim(E, np.array([1.0, 0.0]))
+    assert c[0] == 0.0 and np.all(np.isfinite(c)) and v == 0   # the other cosines are negative
+    # applying it: append while there is room, then drop / close the gap / new row last
+    rows = np.zeros((7, 2, 2))
+    rows[0] = -1.0                                            # one row in front that is no carrier
+    n = 0
+    for k in range(4):
+        n = impl.bank_apply(rows, 1, 4, n, -1, np.full((2, 2), 10.0 + k))
+    assert n == 4 and np.array_equal(rows[1:5, 0, 0], [10, 11, 12, 13]) and np.all(rows[5:] == 0)
+    n = impl.bank_apply(rows, 1, 4, n, 1, np.full((2, 2), 14.0))
+    assert n == 4 and np.array_equal(rows[1:5, 0, 0], [10, 12, 13, 14]), "victim 1 dropped, order kept, new last"
+    assert np.all(rows[0] == -1.0) and np.all(rows[5:] == 0), "rows outside the bank untouched"
+    n = impl.bank_apply(rows, 1, 4, n, 3, np.full((2, 2), 15.0))
+    assert np.array_equal(rows[1:5, 0, 0], [10, 12, 13, 15]), "dropping the newest of the bank"
+    n = impl.bank_apply(rows, 1, 4, n, 0, np.full((2, 2), 16.0))
+    assert np.array_equal(rows[1:5, 0, 0], [12, 13, 15, 16]) and np.all(rows[1:5, 1, 1] == rows[1:5, 0, 0])
+    # a stream: the bank never exceeds M and always ends with the newest carrier
+    M, d = 5, 8
+    bank = np.zeros((M, d))
+    ids = np.zeros((M, 1))
+    n = 0
+    for f in range(20):
+        e = r.normal(size=d)
+        v = impl.bank_victim(bank, e)[0] if n == M else -1
+        n2 = impl.bank_apply(ids, 0, M, n, v, np.array([float(f)]))
+        n = impl.bank_apply(bank, 0, M, n, v, e)
+        assert n == n2 == min(f + 1, M) and ids[n - 1, 0] == f and np.array_equal(bank[n - 1], e)
+        assert np.all(np.diff(ids[:n, 0]) > 0), "arrival order is kept"
+
+
 ALL_PINS = [
     pin_golden_rational,
     pin_uniform_scores_mean_of_visible,
@@ -395,4 +465,5 @@ ALL_PINS = [
     pin_streaming_equals_one_shot,
     pin_decode,
     pin_mean_pool,
+    pin_memory_bank,
 ]

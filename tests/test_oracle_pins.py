@@ -97,11 +97,49 @@ class NumpyImpl:
             return np.resize(E.mean(axis=1), E.shape[1])
         return E.sum(axis=0) / E.shape[0]
 
+    def bank_victim(self, E, e_new, policy=0):
+        E, e_new = np.asarray(E, dtype=np.float64), np.asarray(e_new, dtype=np.float64)
+        M = len(E)
+        if self.bug == "bank_ignores_incoming":
+            nxt = np.concatenate([E[1:], E[-1:]])
+        else:
+            nxt = np.concatenate([E[1:], e_new[None]])
+        if policy == 1:
+            nxt = np.tile(e_new, (M, 1))
+        dots = (E * nxt).sum(axis=1)
+        na, nb = np.sqrt((E * E).sum(axis=1)), np.sqrt((nxt * nxt).sum(axis=1))
+        ok = (na > 0) & (nb > 0)
+        cos = np.where(ok, dots / np.where(ok, na * nb, 1.0), 0.0)
+        if self.bug == "bank_dot_not_cosine":
+            cos = dots
+        if self.bug == "bank_least_similar":
+            return int(np.argmin(cos)), cos
+        if self.bug == "bank_tie_last":
+            return int(M - 1 - np.argmax(cos[::-1])), cos
+        v = int(np.argmax(cos))
+        if self.bug == "bank_drops_newer" and policy == 0:
+            v = min(v + 1, M - 1)
+        return v, cos
+
+    def bank_apply(self, rows, first, M, n, victim, row_new):
+        row_new = np.asarray(row_new, dtype=np.float64).reshape(rows.shape[1:])
+        if n < M:
+            rows[first + n] = row_new
+            return n + 1
+        if self.bug == "bank_overwrites_victim":
+            rows[first + victim] = row_new
+            return M
+        rows[first + victim:first + M - 1] = rows[first + victim + 1:first + M].copy()
+        rows[first + M - (2 if self.bug == "bank_new_row_off_by_one" else 1)] = row_new
+        return M
+
 
 BUGS = ["gqa_interleaved", "scores_from_v", "no_scale", "scale_squared", "no_normalise",
         "negated_scores", "self_invisible", "sees_next", "no_mask", "frame_before_cache",
         "keeps_first_token", "no_capacity_check", "overwrites_last", "v_gets_k",
-        "decode_attends_before_append", "pool_sum", "pool_unbiased", "pool_over_features"]
+        "decode_attends_before_append", "pool_sum", "pool_unbiased", "pool_over_features",
+        "bank_ignores_incoming", "bank_dot_not_cosine", "bank_least_similar", "bank_tie_last",
+        "bank_drops_newer", "bank_overwrites_victim", "bank_new_row_off_by_one"]
 
 
 def _failures(impl):
