@@ -173,6 +173,59 @@ vs_status vs_carrier_mean_pool(const void *e, int32_t n, int32_t d, int32_t dtyp
                                void *hip_stream);
 
 /*
+ * Memory bank of the semantic carriers (Section 3.3, memory mechanism): at most
+ * `capacity` carriers are kept, oldest first; their embeddings live in `e`, their K/V
+ * rows in the layers' caches behind the rows that are not carriers (e.g. a text prefix).
+ */
+typedef struct {
+    void *e;          /* device, [capacity][d], storage type `dtype` */
+    int32_t capacity; /* M, 1..1024 */
+    int32_t len;      /* carriers held, host-side truth */
+    int32_t d;        /* embedding width; d * element size a multiple of 16 bytes */
+    int32_t dtype;    /* vs_dtype */
+} vs_bank;
+
+/* Bytes of device scratch vs_memory_bank_push needs for a bank of this capacity. */
+size_t vs_memory_bank_workspace_bytes(int32_t capacity);
+
+/*
+ * A carrier with embedding e_new [d] (device) arrives at the bank (Section 3.3, memory
+ * mechanism: embeddings of adjacent carriers are compared, and of the most similar pair
+ * the older carrier is dropped).  With room left the embedding is appended, bank->len
+ * grows by one and -1 is written to *victim.  With the bank full the cosines of the
+ * `capacity` adjacent pairs of the sequence e[0], .., e[capacity-1], e_new are taken
+ * (fp32 sums; a vector of norm 0 has cosine 0), the pair (i, i+1) with the largest one
+ * names the victim i (of equal cosines the smallest i; policy 1: the i with the largest
+ * cosine to e_new instead), row i is removed, the rows behind it move up, e_new becomes the
+ * last row, bank->len stays, and i is written to *victim.  `victim` is DEVICE memory (one
+ * int32, may not be NULL): the decision is taken on the device and handed to
+ * vs_carrier_evict_append through it, with no wait on the host.  workspace: device,
+ * 16-byte aligned, vs_memory_bank_workspace_bytes(capacity) bytes, used by this call only.
+ * Errors: VS_ERR_NULL, VS_ERR_SHAPE (capacity, len, d, policy out of range),
+ * VS_ERR_UNSUPPORTED (dtype), VS_ERR_ALIGN, VS_ERR_WORKSPACE, VS_ERR_HIP.
+ */
+vs_status vs_memory_bank_push(vs_bank *bank, const void *e_new, int32_t policy, int32_t *victim,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The K/V side of the same step, for n_layers caches at once (n_layers = 1: one layer, as a
+ * decoder produces them): cache l receives the carrier's K/V row k_rows + l*layer_stride_bytes,
+ * v_rows + l*layer_stride_bytes ([n_kv_heads][head_dim] each, device).  Rows 0..first_row-1
+ * of every cache are not carriers and stay.  A cache that holds fewer than bank_capacity
+ * carriers (len < first_row + bank_capacity) appends the row and its len grows by one;
+ * otherwise carrier row first_row + *victim is removed, the rows behind it move up, the new
+ * row becomes the last and len stays (Sections 3.2, 3.3: the bank stores the carriers'
+ * associated KV pairs).  `victim` is the DEVICE int32 that vs_memory_bank_push wrote; it is
+ * read by the kernel, never by the host.  `caches` is a HOST array; all of them must hold the
+ * same number of rows.  Errors as above plus VS_ERR_CAPACITY (first_row + bank_capacity
+ * exceeds a cache's capacity); lengths untouched on error.
+ */
+vs_status vs_carrier_evict_append(const vs_shape *shape, int32_t n_layers, vs_cache *caches,
+                                  int32_t first_row, int32_t bank_capacity, const void *k_rows,
+                                  const void *v_rows, int64_t layer_stride_bytes, const int32_t *victim,
+                                  void *hip_stream);
+
+/*
  * Launch-plan overrides for tuning and for tests that must show a result does not
  * depend on how the keys were split.  Process-wide, not thread-safe; value 0 restores
  * the library's own choice.  Unknown knobs or out-of-range values: VS_ERR_SHAPE.

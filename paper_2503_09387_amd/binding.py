@@ -11,7 +11,8 @@ _LIB = None
 EXPORTS = [
     "vs_status_string", "vs_workspace_bytes", "vs_workspace_init", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
     "vs_carrier_compact_append", "vs_carrier_compact_append_batched", "vs_decode_attn",
-    "vs_carrier_mean_pool", "vs_set_tuning",
+    "vs_carrier_mean_pool", "vs_set_tuning", "vs_memory_bank_push", "vs_carrier_evict_append",
+    "vs_memory_bank_workspace_bytes",
 ]
 
 
@@ -87,7 +88,11 @@ def lib():
         L.vs_decode_attn.argtypes = [sp, i32, vp, vp, i32, ip, vp, vp, vp, vp, vp, sz, vp]
         L.vs_carrier_mean_pool.argtypes = [vp, i32, i32, i32, vp, vp]
         L.vs_set_tuning.argtypes = [i32, i32]
-        for name in EXPORTS[2:]:
+        L.vs_memory_bank_push.argtypes = [vp, vp, i32, vp, vp, sz, vp]
+        L.vs_carrier_evict_append.argtypes = [sp, i32, vp, i32, i32, vp, vp, ctypes.c_int64, vp, vp]
+        L.vs_memory_bank_workspace_bytes.argtypes = [i32]
+        L.vs_memory_bank_workspace_bytes.restype = sz
+        for name in EXPORTS[2:-1]:
             getattr(L, name).restype = ctypes.c_int
         _LIB = L
     return _LIB
@@ -194,6 +199,50 @@ def decode_attn(shape, k_slab, v_slab, lens, q, k_new, v_new, out, workspace, st
     _check(lib().vs_decode_attn(ctypes.byref(shape), n_streams, _ptr(k_slab), _ptr(v_slab), capacity, lens,
                                 _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), wp, wb, _stream(stream)),
            "vs_decode_attn")
+
+
+class _CBank(ctypes.Structure):
+    _fields_ = [("e", ctypes.c_void_p), ("capacity", ctypes.c_int32), ("len", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class Bank:
+    """Memory bank of the carriers' embeddings: a device tensor [capacity][d] and a host-side count."""
+
+    def __init__(self, e, dtype, length=0):
+        assert e.dim() == 2 and e.is_contiguous()
+        self.e = e
+        code = {"f32": VS_F32, "bf16": VS_BF16}.get(dtype, dtype)
+        self.c = _CBank(e.data_ptr(), e.shape[0], int(length), e.shape[1], code)
+
+    @property
+    def len(self):
+        return self.c.len
+
+
+def memory_bank_workspace_bytes(capacity):
+    return int(lib().vs_memory_bank_workspace_bytes(capacity))
+
+
+def memory_bank_push(bank, e_new, victim, workspace, policy=0, stream=None):
+    """victim: device int32 tensor with one element (written by the call)."""
+    wp, wb = _ws(workspace)
+    _check(lib().vs_memory_bank_push(ctypes.byref(bank.c), _ptr(e_new), policy, _ptr(victim), wp, wb,
+                                     _stream(stream)), "vs_memory_bank_push")
+
+
+def carrier_evict_append(shape, caches, first_row, bank_capacity, k_rows, v_rows, victim, stream=None):
+    """caches: list of Cache (one per layer); k_rows / v_rows: device tensors [n_layers][Hkv][D]."""
+    n = len(caches)
+    arr = (_CCache * n)(*[c.c for c in caches])
+    stride = k_rows.stride(0) * k_rows.element_size() if n > 1 else 0
+    try:
+        _check(lib().vs_carrier_evict_append(ctypes.byref(shape), n, arr, first_row, bank_capacity, _ptr(k_rows),
+                                             _ptr(v_rows), stride, _ptr(victim), _stream(stream)),
+               "vs_carrier_evict_append")
+    finally:
+        for c, a in zip(caches, arr):
+            c.c.len = a.len
 
 
 def carrier_mean_pool(e, c_out, dtype, stream=None):

@@ -4,6 +4,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <vector>
 
 #include "vs_internal.h"
 
@@ -289,6 +290,75 @@ vs_status vs_decode_attn(const vs_shape* shape, int32_t n_streams, void* k_slab,
     }
     if (add)
         for (int32_t s = 0; s < n_streams; ++s) lens[s] += 1;
+    return VS_OK;
+}
+
+size_t vs_memory_bank_workspace_bytes(int32_t capacity) {
+    if (capacity < 1 || capacity > 1024) return 0;
+    return round256(sizeof(float) * (size_t)capacity);
+}
+
+vs_status vs_memory_bank_push(vs_bank* bank, const void* e_new, int32_t policy, int32_t* victim,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!bank || !e_new || !victim || !bank->e) return VS_ERR_NULL;
+    if (bank->dtype != VS_F32 && bank->dtype != VS_BF16) return VS_ERR_UNSUPPORTED;
+    const int64_t rb = (int64_t)bank->d * (bank->dtype == VS_F32 ? 4 : 2);
+    if (bank->capacity < 1 || bank->capacity > 1024 || bank->len < 0 || bank->len > bank->capacity ||
+        bank->d < 1 || rb % 16 != 0 || (policy != 0 && policy != 1))
+        return VS_ERR_SHAPE;
+    if (!aligned16(bank->e) || !aligned16(e_new) || (reinterpret_cast<uintptr_t>(victim) & 3u)) return VS_ERR_ALIGN;
+    if (!workspace || workspace_bytes < vs_memory_bank_workspace_bytes(bank->capacity)) return VS_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return VS_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    void* base = bank->e;
+    const void* row = e_new;
+    if (bank->len < bank->capacity) {
+        if (launch_bank_shift(1, &base, &row, rb, 0, bank->capacity, bank->len, nullptr, victim, st) != hipSuccess)
+            return VS_ERR_HIP;
+        bank->len += 1;
+        return VS_OK;
+    }
+    float* cosines = static_cast<float*>(workspace);
+    if (launch_bank_cosines(bank->e, e_new, bank->capacity, bank->d, bank->dtype, policy, cosines, st) != hipSuccess)
+        return VS_ERR_HIP;
+    return launch_bank_shift(1, &base, &row, rb, 0, bank->capacity, -1, cosines, victim, st) == hipSuccess
+               ? VS_OK : VS_ERR_HIP;
+}
+
+vs_status vs_carrier_evict_append(const vs_shape* shape, int32_t n_layers, vs_cache* caches, int32_t first_row,
+                                  int32_t bank_capacity, const void* k_rows, const void* v_rows,
+                                  int64_t layer_stride_bytes, const int32_t* victim, void* hip_stream) {
+    vs_status st = check_shape(shape);
+    if (st != VS_OK) return st;
+    if (!caches || !k_rows || !v_rows || !victim) return VS_ERR_NULL;
+    const int64_t rb = row_bytes(shape);
+    if (n_layers < 1 || n_layers > 1024 || first_row < 0 || bank_capacity < 1 || bank_capacity > 1024 ||
+        layer_stride_bytes < 0 || layer_stride_bytes % 16 != 0 || (n_layers > 1 && layer_stride_bytes < rb))
+        return VS_ERR_SHAPE;
+    if (!aligned16(k_rows) || !aligned16(v_rows) || (reinterpret_cast<uintptr_t>(victim) & 3u)) return VS_ERR_ALIGN;
+    const int32_t len = caches[0].len;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        st = check_cache(&caches[l], false);
+        if (st != VS_OK) return st;
+        if (!caches[l].k || !caches[l].v) return VS_ERR_NULL;
+        if (caches[l].len != len || len < first_row || len > first_row + bank_capacity) return VS_ERR_SHAPE;
+        if ((int64_t)first_row + bank_capacity > caches[l].capacity) return VS_ERR_CAPACITY;
+    }
+    const bool room = len < first_row + bank_capacity;
+    std::vector<void*> bases(2 * (size_t)n_layers);
+    std::vector<const void*> rows(2 * (size_t)n_layers);
+    for (int32_t l = 0; l < n_layers; ++l) {
+        bases[2 * l] = caches[l].k;
+        bases[2 * l + 1] = caches[l].v;
+        rows[2 * l] = static_cast<const char*>(k_rows) + (int64_t)l * layer_stride_bytes;
+        rows[2 * l + 1] = static_cast<const char*>(v_rows) + (int64_t)l * layer_stride_bytes;
+    }
+    if (launch_bank_shift(2 * n_layers, bases.data(), rows.data(), rb, first_row, bank_capacity,
+                          room ? len - first_row : -1, nullptr, room ? nullptr : const_cast<int32_t*>(victim),
+                          static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return VS_ERR_HIP;
+    if (room)
+        for (int32_t l = 0; l < n_layers; ++l) caches[l].len += 1;
     return VS_OK;
 }
 

@@ -72,6 +72,14 @@ hipError_t launch_append_rows(int32_t n_caches, void* k_slab, void* v_slab, int6
                               const void* k_src, const void* v_src, int64_t src_stride_bytes,
                               int64_t src_row_offset_bytes, int32_t row_bytes, hipStream_t st);
 
+// memory bank (Section 3.3, memory mechanism)
+constexpr int kBankMaxTables = 64;  // tables (layers x {K, V}) per launch: their pointers travel by value
+hipError_t launch_bank_cosines(const void* e, const void* e_new, int32_t M, int32_t d, int32_t dtype,
+                               int32_t policy, float* cosines, hipStream_t st);
+hipError_t launch_bank_shift(int32_t n_tables, void* const* bases, const void* const* new_rows, int64_t row_bytes,
+                             int32_t first, int32_t M, int32_t append_at, const float* cosines, int32_t* victim_io,
+                             hipStream_t st);
+
 hipError_t launch_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, void* c_out,
                             hipStream_t st);
 

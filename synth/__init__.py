@@ -10,6 +10,7 @@ from .gen import (  # noqa: F401
     draw,
     frame_inputs,
     cache_rows,
+    carrier_embeddings,
     decode_step_inputs,
     decode_lengths,
     cfg1_inputs,

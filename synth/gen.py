@@ -84,3 +84,18 @@ def cfg1_inputs(cfg):
     k_f = rn(T, s.n_kv_heads, s.head_dim)
     v_f = rn(T, s.n_kv_heads, s.head_dim)
     return dict(k_c=k_c, v_c=v_c, e=e, q=q, k_f=k_f, v_f=v_f)
+
+
+def carrier_embeddings(seed, n, d, dtype):
+    """Embeddings [n][d] of the carriers of a slowly changing scene with cuts: neighbours are
+    similar, as the pooled embeddings of consecutive video frames are (synthetic stand-in)."""
+    g = torch.Generator(device="cpu").manual_seed(int(seed))
+    e = torch.empty((n, d), dtype=torch.float32)
+    cur = torch.randn(d, generator=g)
+    for t in range(n):
+        if t % 11 == 10:
+            cur = torch.randn(d, generator=g)  # a cut
+        step = 0.2 + 0.8 * float(torch.rand((), generator=g))
+        cur = 0.8 * cur + 0.6 * step * torch.randn(d, generator=g)
+        e[t] = cur
+    return e.to(_TORCH_DTYPE[dtype]).contiguous()

@@ -11,7 +11,7 @@ import oracle
 import paper_2503_09387_amd as vs
 from gpu_util import (DEV, check_close, lens_array, oracle_prefill_rows, run_prefill, scale32,
                       torch_dtype, vs_shape, workspace)
-from synth import (CONFIGS, AttnShape, cache_rows, cfg1_inputs, decode_lengths, decode_step_inputs,
+from synth import (CONFIGS, AttnShape, cache_rows, carrier_embeddings, cfg1_inputs, decode_lengths, decode_step_inputs,
                    draw, frame_inputs, to_f64)
 
 pytestmark = pytest.mark.gpu
@@ -415,3 +415,106 @@ def test_batched_compaction(n_caches):
         want_k[i, lens0[i]] = kf[i, T - 1]
         want_v[i, lens0[i]] = vf[i, T - 1]
     assert same_bits(ks, want_k) and same_bits(vsl, want_v)
+
+
+# ---------------------------------------------------------------------------- memory bank
+@pytest.mark.parametrize("dtype,M,d,policy", [("bf16", 128, 3584, 0), ("f32", 16, 256, 0), ("bf16", 64, 3584, 1),
+                                              ("bf16", 5, 8, 0), ("f32", 130, 64, 0)])
+def test_memory_bank_stream(dtype, M, d, policy):
+    """Carriers arrive one by one: the bank fills, then drops the older carrier of the most similar
+    adjacent pair.  Victim indices against the fp64 oracle (equal whenever the two best cosines
+    differ by more than the fp32 summation error), embeddings and the K/V rows of three layers
+    bit for bit."""
+    s = AttnShape(4, 2, 64, "f32") if dtype == "f32" else QW
+    n_layers, first, extra = 3, 5, 40
+    n = M + extra
+    emb = carrier_embeddings(7, n, d, dtype)
+    kv = draw(99, (n, n_layers, 2, s.n_kv_heads, s.head_dim), 1.0, dtype)   # [carrier][layer][k|v]
+    dt = torch_dtype(dtype)
+    bank = vs.Bank(torch.zeros((M, d), dtype=dt, device=DEV), dtype)
+    caches = [vs.Cache(torch.full((first + M + 2, s.n_kv_heads, s.head_dim), 7.0, dtype=dt, device=DEV),
+                       torch.full((first + M + 2, s.n_kv_heads, s.head_dim), -7.0, dtype=dt, device=DEV), first)
+              for _ in range(n_layers)]
+    victim = torch.full((1,), -5, dtype=torch.int32, device=DEV)
+    ws = torch.empty(vs.memory_bank_workspace_bytes(M), dtype=torch.uint8, device=DEV)
+    # the oracle's state
+    o_emb = np.zeros((M, d))
+    o_k = [np.full((first + M + 2, s.n_kv_heads, s.head_dim), 7.0) for _ in range(n_layers)]
+    o_v = [np.full((first + M + 2, s.n_kv_heads, s.head_dim), -7.0) for _ in range(n_layers)]
+    o_n = 0
+    near_ties = 0
+    for t in range(n):
+        e_dev = emb[t].to(DEV)
+        rows = kv[t].to(DEV)
+        vs.memory_bank_push(bank, e_dev, victim, ws, policy=policy)
+        vs.carrier_evict_append(vs_shape(s), caches, first, M, rows[:, 0], rows[:, 1], victim)
+        got = int(victim.cpu()[0])
+        e64 = to_f64(emb[t])
+        if o_n < M:
+            assert got == -1
+            want = -1
+        else:
+            want, cos = oracle.bank_victim(o_emb, e64, policy)
+            top = np.sort(cos)[::-1]
+            assert 0 <= got < M and cos[got] >= top[0] - 1e-5, f"carrier {t}: victim {got}, cosine {cos[got]} vs best {top[0]}"
+            if top[0] - top[1] > 1e-5:
+                assert got == want, f"carrier {t}: victim {got}, oracle {want}"
+            else:
+                near_ties += 1
+        n2 = oracle.bank_apply(o_emb, 0, M, o_n, got, e64)
+        for l in range(n_layers):
+            oracle.bank_apply(o_k[l], first, M, o_n, got, to_f64(kv[t, l, 0]))
+            oracle.bank_apply(o_v[l], first, M, o_n, got, to_f64(kv[t, l, 1]))
+        o_n = n2
+        assert bank.len == o_n and all(c.len == first + o_n for c in caches)
+        if t % 13 == 0 or t >= n - 3:
+            assert np.array_equal(bank.e.double().cpu().numpy(), o_emb), f"embeddings after carrier {t}"
+            for l in range(n_layers):
+                assert np.array_equal(caches[l].k.double().cpu().numpy(), o_k[l]), f"K rows of layer {l} after carrier {t}"
+                assert np.array_equal(caches[l].v.double().cpu().numpy(), o_v[l]), f"V rows of layer {l} after carrier {t}"
+    assert near_ties <= extra // 4
+
+
+def test_memory_bank_ties_and_zero_vectors():
+    """Equal cosines: the smallest index goes; a zero vector has cosine 0 and never wins over a
+    positive one."""
+    M, d = 6, 16
+    e = torch.zeros((M, d), dtype=torch.float32)
+    e[0, 0] = 1.0
+    e[1, 1] = 2.0
+    e[2, 1] = 0.5          # pair (1, 2): cosine 1
+    e[3, 2] = 1.0
+    e[4, 3] = 3.0
+    e[5, 3] = 1.0          # pair (4, 5): cosine 1 as well
+    new = torch.zeros(d)
+    bank = vs.Bank(e.to(DEV), "f32", M)
+    victim = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(vs.memory_bank_workspace_bytes(M), dtype=torch.uint8, device=DEV)
+    vs.memory_bank_push(bank, new.to(DEV), victim, ws)
+    assert int(victim.cpu()[0]) == 1 == oracle.bank_victim(e.double().numpy(), new.double().numpy())[0]
+    want = e.double().numpy().copy()
+    oracle.bank_apply(want, 0, M, M, 1, new.double().numpy())
+    assert np.array_equal(bank.e.double().cpu().numpy(), want)
+
+
+def test_memory_bank_rejects_bad_arguments():
+    s = QW
+    e = torch.zeros((4, 8), dtype=torch.bfloat16, device=DEV)
+    victim = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(256, dtype=torch.uint8, device=DEV)
+    bank = vs.Bank(e, "bf16")
+    with pytest.raises(vs.VSError) as err:
+        vs.memory_bank_push(bank, e[0], victim, ws, policy=3)
+    assert err.value.code == 2
+    with pytest.raises(vs.VSError) as err:
+        vs.memory_bank_push(bank, e[0], victim, ws[:8])
+    assert err.value.code == 5 and bank.len == 0
+    k = torch.zeros((6, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+    cache = vs.Cache(k, k.clone(), 2)
+    rows = torch.zeros((1, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(vs.VSError) as err:       # prefix + bank does not fit the cache
+        vs.carrier_evict_append(vs_shape(s), [cache], 2, 5, rows, rows, victim)
+    assert err.value.code == 4 and cache.len == 2
+    with pytest.raises(vs.VSError) as err:       # fewer rows than the prefix
+        vs.carrier_evict_append(vs_shape(s), [cache], 3, 2, rows, rows, victim)
+    assert err.value.code == 2
