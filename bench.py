@@ -89,13 +89,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--decode-steps", type=int, default=64)
     ap.add_argument("--parts", default="all",
-                    help="comma list of: stream,decode,cfg2,cfg5,compaction,cpu (default all); "
+                    help="comma list of: stream,decode,cfg2,cfg5,compaction,bank,cpu (default all); "
                          "calib = only a 1 GiB device copy, the known-size kernel that the HBM "
                          "counters of a rocprofv3 --pmc run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
-    parts = set("stream,decode,cfg2,cfg5,compaction,cpu".split(",")) if args.parts == "all" \
+    parts = set("stream,decode,cfg2,cfg5,compaction,bank,cpu".split(",")) if args.parts == "all" \
         else set(args.parts.split(","))
 
     import numpy as np
@@ -481,6 +481,42 @@ def main():
                  "32 KB host-to-device copy of the lengths); in the stream the compaction is fused into the "
                  "prefill launch and costs no launch of its own")
         log(f"[bench] compaction: batched {tb * 1e6:.1f} us = {moved / tb / 1e9:.0f} GB/s; single call {t1 * 1e6:.2f} us")
+
+    if "bank" in parts:
+        # memory bank at capacity (Section 3.3, memory mechanism; the paper evaluates M = 64 and 128):
+        # one carrier arrives per frame, a victim is chosen from the embeddings and its row leaves the
+        # embedding table and the K/V rows of all 28 layers
+        from synth import carrier_embeddings
+        Mb, d_emb, first = 128, 3584, 200
+        emb = carrier_embeddings(3, Mb + 64, d_emb, "bf16").to(dev)
+        bank = vs.Bank(emb[:Mb].clone(), "bf16", Mb)
+        rows_kv = draw(8, (64, NL, 2, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(dev)
+        bcaches = [vs.Cache(torch.zeros((first + Mb, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=dev),
+                            torch.zeros((first + Mb, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=dev),
+                            first + Mb) for _ in range(NL)]
+        victim = torch.zeros(1, dtype=torch.int32, device=dev)
+        wsb = torch.empty(vs.memory_bank_workspace_bytes(Mb), dtype=torch.uint8, device=dev)
+
+        def pushes(n):
+            for i in range(n):
+                vs.memory_bank_push(bank, emb[Mb + i % 64], victim, wsb)
+                vs.carrier_evict_append(sh, bcaches, first, Mb, rows_kv[i % 64, :, 0], rows_kv[i % 64, :, 1], victim)
+        pushes(8)
+        a, b = event_pair()
+        torch.cuda.synchronize()
+        a.record()
+        pushes(200)
+        b.record()
+        torch.cuda.synchronize()
+        tp = a.elapsed_time(b) * 1e-3 / 200
+        # bytes if the victim were the oldest carrier (every row moves): embeddings + K and V of 28 layers, read + write
+        worst = 2 * Mb * (d_emb * 2 + NL * 2 * s.n_kv_heads * s.head_dim * 2)
+        extras["memory_bank"] = dict(capacity=Mb, layers=NL, us_per_carrier=tp * 1e6, launches_per_carrier=3,
+                                     worst_case_mbytes_moved=worst / 1e6,
+                                     note="bank at capacity: cosines of 128 adjacent pairs (d = 3584), victim chosen on the "
+                                          "device, rows closed up in the embedding table and in K/V of 28 layers (one launch "
+                                          "for all layers); three dependent small launches, launch-latency-bound")
+        log(f"[bench] memory bank: {tp * 1e6:.1f} us per carrier at capacity {Mb}, {NL} layers")
 
     line = {
         "metric": "streamed frames/sec (28-layer prefill attn + carrier compaction)",
