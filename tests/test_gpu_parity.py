@@ -518,3 +518,62 @@ def test_memory_bank_rejects_bad_arguments():
     with pytest.raises(vs.VSError) as err:       # fewer rows than the prefix
         vs.carrier_evict_append(vs_shape(s), [cache], 3, 2, rows, rows, victim)
     assert err.value.code == 2
+
+
+def test_stream_with_memory_bank_prefill_reads_the_bank():
+    """Frames arrive at a bank of 4 carriers behind a 3-row prefix, two layers: every frame's
+    prefill attends to [prefix | carriers held], then its carrier is pushed (evicting one once the
+    bank is full).  Outputs against the oracle run over the oracle's own bank; victims, lengths and
+    retained rows as the oracle has them."""
+    s = QW
+    M, first, n_layers, frames, T, d = 4, 3, 2, 10, 21, 64
+    emb = carrier_embeddings(17, frames, d, "bf16")
+    dt = torch.bfloat16
+    caches, o_k, o_v = [], [], []
+    for l in range(n_layers):
+        hk, hv = cache_rows(40 + l, s, first, 0.5)
+        k = torch.zeros((first + M, s.n_kv_heads, s.head_dim), dtype=dt, device=DEV)
+        v = torch.zeros_like(k)
+        k[:first].copy_(hk)
+        v[:first].copy_(hv)
+        caches.append(vs.Cache(k, v, first))
+        ok, ov = np.zeros((first + M, s.n_kv_heads, s.head_dim)), np.zeros((first + M, s.n_kv_heads, s.head_dim))
+        ok[:first], ov[:first] = to_f64(hk), to_f64(hv)
+        o_k.append(ok)
+        o_v.append(ov)
+    bank = vs.Bank(torch.zeros((M, d), dtype=dt, device=DEV), "bf16")
+    o_emb, o_n = np.zeros((M, d)), 0
+    victim = torch.zeros(1, dtype=torch.int32, device=DEV)
+    bws = torch.empty(vs.memory_bank_workspace_bytes(M), dtype=torch.uint8, device=DEV)
+    ws = workspace(s, T, first + M, 0)
+    for f in range(frames):
+        rows_k = torch.empty((n_layers, s.n_kv_heads, s.head_dim), dtype=dt, device=DEV)
+        rows_v = torch.empty_like(rows_k)
+        o_rows = []
+        for l in range(n_layers):
+            q, kf, vf = frame_inputs(500 + 10 * f + l, s, T, 0.5, q_gain=2)
+            out = torch.full(q.shape, float("nan"), dtype=dt, device=DEV)
+            vs.frame_prefill_attn(vs_shape(s), caches[l], q.to(DEV), kf.to(DEV), vf.to(DEV), out, ws)
+            L = first + o_n
+            ref = oracle.frame_prefill(to_f64(q), o_k[l][:L], o_v[l][:L], to_f64(kf), to_f64(vf), scale32(s))
+            check_close(out, ref, "bf16", f"frame {f} layer {l} over {o_n} carriers")
+            rows_k[l].copy_(kf[T - 1])
+            rows_v[l].copy_(vf[T - 1])
+            o_rows.append((to_f64(kf[T - 1]), to_f64(vf[T - 1])))
+        vs.memory_bank_push(bank, emb[f].to(DEV), victim, bws)
+        vs.carrier_evict_append(vs_shape(s), caches, first, M, rows_k, rows_v, victim)
+        got = int(victim.cpu()[0])
+        e64 = to_f64(emb[f])
+        if o_n == M:
+            want, cos = oracle.bank_victim(o_emb, e64)
+            top = np.sort(cos)[::-1]
+            assert got == want or top[0] - top[1] <= 1e-5
+        else:
+            assert got == -1
+        for l in range(n_layers):
+            oracle.bank_apply(o_k[l], first, M, o_n, got, o_rows[l][0])
+            oracle.bank_apply(o_v[l], first, M, o_n, got, o_rows[l][1])
+        o_n = oracle.bank_apply(o_emb, 0, M, o_n, got, e64)
+        assert bank.len == o_n and all(c.len == first + o_n for c in caches)
+    for l in range(n_layers):
+        assert np.array_equal(caches[l].k.double().cpu().numpy(), o_k[l]) and np.array_equal(caches[l].v.double().cpu().numpy(), o_v[l])
