@@ -17,6 +17,8 @@
  *     decoding reads the retained carrier K/V only.
  *   - Section 3.3, memory mechanism: a bank of at most M carriers; at
  *     capacity the older carrier of the most similar adjacent pair is dropped.
+ *   - Section 3.4, semantic-aware mask: in a run of several frames a token
+ *     reaches earlier frames only through their carriers.
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   - every token of the frame run sees all retained cache rows; inside the
@@ -280,4 +282,79 @@ int vs_oracle_bank_apply(double *rows, int64_t capacity, int64_t width, int64_t 
     memcpy(rows + (size_t)(first + M - 1) * width, row_new, (size_t)width * sizeof(double));
     *n_out = M;
     return VSO_OK;
+}
+
+/*
+ * Several frames in one run with the semantic-aware mask (Section 3.4: later
+ * tokens reach earlier frames only through those frames' semantic carriers;
+ * Section 3.2: the carrier is the last token of its frame).  The run holds F
+ * frames of T tokens each.  Token i of frame a sees
+ *   - the L retained cache rows,
+ *   - the carriers (token T-1) of frames a' < a of this run,
+ *   - tokens 0..i of its own frame,
+ * and nothing else.  Q, O [F][T][Hq][D]; Kf, Vf [F][T][Hkv][D].  Written out as
+ * the definition: for every (head, query) the visible keys are listed, scored,
+ * soft-maxed in two passes and summed.
+ */
+int vs_oracle_frames_prefill(const double *Q, const double *Kc, const double *Vc, int64_t L,
+                             const double *Kf, const double *Vf, int64_t F, int64_t T,
+                             int32_t Hq, int32_t Hkv, int32_t D, double scale, double *O) {
+    if (L < 0 || F < 1 || T < 1 || !Q || !Kf || !Vf || !O || (L > 0 && (!Kc || !Vc))) return VSO_ERR_ARG;
+    if (Hq < 1 || Hkv < 1 || D < 1 || Hq % Hkv != 0) return VSO_ERR_ARG;
+    const int32_t G = Hq / Hkv;
+    const size_t row = (size_t)Hkv * D;
+    const int64_t max_keys = L + F + T;
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel for collapse(2) schedule(dynamic)
+#endif
+    for (int64_t a = 0; a < F; ++a) {
+        for (int32_t h = 0; h < Hq; ++h) {
+            const int32_t g = h / G;
+            const double **kp = (const double **)malloc((size_t)max_keys * sizeof(double *));
+            const double **vp = (const double **)malloc((size_t)max_keys * sizeof(double *));
+            double *z = (double *)malloc((size_t)max_keys * sizeof(double));
+            if (!kp || !vp || !z) {
+                failed = 1;
+                free(kp); free(vp); free(z);
+                continue;
+            }
+            for (int64_t i = 0; i < T; ++i) {
+                int64_t n = 0;
+                for (int64_t j = 0; j < L; ++j) {            /* retained rows */
+                    kp[n] = Kc + (size_t)j * row + (size_t)g * D;
+                    vp[n++] = Vc + (size_t)j * row + (size_t)g * D;
+                }
+                for (int64_t b = 0; b < a; ++b) {            /* carriers of earlier frames of the run */
+                    kp[n] = Kf + ((size_t)b * T + (size_t)(T - 1)) * row + (size_t)g * D;
+                    vp[n++] = Vf + ((size_t)b * T + (size_t)(T - 1)) * row + (size_t)g * D;
+                }
+                for (int64_t j = 0; j <= i; ++j) {           /* own frame, causal */
+                    kp[n] = Kf + ((size_t)a * T + (size_t)j) * row + (size_t)g * D;
+                    vp[n++] = Vf + ((size_t)a * T + (size_t)j) * row + (size_t)g * D;
+                }
+                const double *q = Q + (((size_t)a * T + (size_t)i) * Hq + (size_t)h) * D;
+                double m = -INFINITY;
+                for (int64_t k = 0; k < n; ++k) {
+                    double s = 0.0;
+                    for (int32_t d = 0; d < D; ++d) s += q[d] * kp[k][d];
+                    z[k] = s * scale;
+                    if (z[k] > m) m = z[k];
+                }
+                double Z = 0.0;
+                for (int64_t k = 0; k < n; ++k) {
+                    z[k] = exp(z[k] - m);
+                    Z += z[k];
+                }
+                double *o = O + (((size_t)a * T + (size_t)i) * Hq + (size_t)h) * D;
+                for (int32_t d = 0; d < D; ++d) o[d] = 0.0;
+                for (int64_t k = 0; k < n; ++k) {
+                    const double p = z[k] / Z;
+                    for (int32_t d = 0; d < D; ++d) o[d] += p * vp[k][d];
+                }
+            }
+            free(kp); free(vp); free(z);
+        }
+    }
+    return failed ? VSO_ERR_NOMEM : VSO_OK;
 }

@@ -39,6 +39,7 @@ def _lib():
         lib.vs_oracle_compact_append.argtypes = [dp, dp, i64, ip, dp, dp, i64, i64, i32, i32, ip]
         lib.vs_oracle_decode.argtypes = [dp, dp, dp, i64, ip, dp, dp, i32, i32, i32, f64, dp]
         lib.vs_oracle_mean_pool.argtypes = [dp, i64, i64, dp]
+        lib.vs_oracle_frames_prefill.argtypes = [dp, dp, dp, i64, dp, dp, i64, i64, i32, i32, i32, f64, dp]
         lib.vs_oracle_bank_victim.argtypes = [dp, i64, i64, dp, i32, dp, ip]
         lib.vs_oracle_bank_apply.argtypes = [dp, i64, i64, i64, i64, i64, i64, dp, ip]
         _LIB = lib
@@ -174,3 +175,23 @@ def bank_apply(rows, first, M, n, victim, row_new):
     if rc:
         raise OracleError(rc, "bank_apply")
     return int(n_out.value)
+
+
+def frames_prefill(Q, Kc, Vc, Kf, Vf, scale):
+    """Several frames in one run with the semantic-aware mask (Section 3.4): a token sees the
+    retained rows, the carriers (last tokens) of earlier frames of the run, and its own frame up
+    to itself.  Q [F][T][Hq][D], Kf/Vf [F][T][Hkv][D], Kc/Vc [L][Hkv][D] or None."""
+    Q, Kf, Vf = _c(Q), _c(Kf), _c(Vf)
+    F, T, Hq, D = Q.shape
+    Hkv = Kf.shape[2]
+    assert Kf.shape == (F, T, Hkv, D) and Vf.shape == Kf.shape
+    if Kc is None or len(Kc) == 0:
+        L, Kc, Vc = 0, None, None
+    else:
+        Kc, Vc = _c(Kc), _c(Vc)
+        L = Kc.shape[0]
+    O = np.empty((F, T, Hq, D), dtype=np.float64)
+    rc = _lib().vs_oracle_frames_prefill(_p(Q), _p(Kc), _p(Vc), L, _p(Kf), _p(Vf), F, T, Hq, Hkv, D, float(scale), _p(O))
+    if rc:
+        raise OracleError(rc, "frames_prefill")
+    return O

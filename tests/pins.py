@@ -448,6 +448,53 @@ def pin_memory_bank(impl):
         assert np.all(np.diff(ids[:n, 0]) > 0), "arrival order is kept"
 
 
+def pin_frames_with_semantic_mask(impl):
+    """Section 3.4: several frames in one run; a token reaches earlier frames only through their
+    carriers (last tokens)."""
+    r = _rng(41)
+    F, T, Hq, Hkv, D, L = 4, 5, 4, 2, 6, 3
+    Q = r.normal(size=(F, T, Hq, D))
+    Kf, Vf = r.normal(size=(F, T, Hkv, D)), r.normal(size=(F, T, Hkv, D))
+    Kc, Vc = r.normal(size=(L, Hkv, D)), r.normal(size=(L, Hkv, D))
+    O = impl.frames_prefill(Q, Kc, Vc, Kf, Vf, 0.5)
+    # one frame: the ordinary frame prefill
+    _close(impl.frames_prefill(Q[:1], Kc, Vc, Kf[:1], Vf[:1], 0.5)[0], impl.frame_prefill(Q[0], Kc, Vc, Kf[0], Vf[0], 0.5),
+           1e-14, "a run of one frame")
+    # the run equals streaming: frame by frame, each followed by the carrier compaction
+    cap = L + F
+    K2, V2 = np.zeros((cap, Hkv, D)), np.zeros((cap, Hkv, D))
+    K2[:L], V2[:L] = Kc, Vc
+    n = L
+    for a in range(F):
+        _close(O[a], impl.frame_prefill(Q[a], K2[:n], V2[:n], Kf[a], Vf[a], 0.5), 1e-13, f"frame {a} of the run vs streaming")
+        _, n = impl.compact_append(K2, V2, n, Kf[a], Vf[a])
+    # brute force of the mask on the flattened run: key (b, j) visible to query (a, i) iff
+    # (b == a and j <= i) or (b < a and j == T-1)
+    Kall = np.concatenate([Kc, Kf.reshape(F * T, Hkv, D)])
+    Vall = np.concatenate([Vc, Vf.reshape(F * T, Hkv, D)])
+    for a, i, h in ((0, 0, 0), (1, 2, 3), (3, 4, 1), (2, 0, 2)):
+        vis = list(range(L)) + [L + b * T + j for b in range(F) for j in range(T)
+                                if (b == a and j <= i) or (b < a and j == T - 1)]
+        g = h // (Hq // Hkv)
+        z = [0.5 * math.fsum(Q[a, i, h] * Kall[k, g]) for k in vis]
+        m = max(z)
+        w = [math.exp(x - m) for x in z]
+        want = [math.fsum(w[n_] * Vall[k, g, d] for n_, k in enumerate(vis)) / math.fsum(w) for d in range(D)]
+        _close(O[a, i, h], np.array(want), 1e-13, f"brute force ({a},{i},{h})")
+    # no leak: changing the visual tokens (not the carrier) of frame 1 changes no later frame at all,
+    # changing its carrier changes every later frame, and nothing ever changes an earlier frame
+    Kp, Vp = Kf.copy(), Vf.copy()
+    Kp[1, :T - 1] += 1.0
+    Vp[1, :T - 1] -= 2.0
+    O2 = impl.frames_prefill(Q, Kc, Vc, Kp, Vp, 0.5)
+    assert np.array_equal(O2[0], O[0]) and np.array_equal(O2[2:], O[2:]) and not np.array_equal(O2[1], O[1])
+    Kp, Vp = Kf.copy(), Vf.copy()
+    Vp[1, T - 1] += 1.0
+    O3 = impl.frames_prefill(Q, Kc, Vc, Kp, Vp, 0.5)
+    assert np.array_equal(O3[0], O[0]) and np.array_equal(O3[1, :T - 1], O[1, :T - 1])
+    assert all(np.abs(O3[a] - O[a]).min() > 0 for a in (2, 3)) and np.abs(O3[1, T - 1] - O[1, T - 1]).min() > 0
+
+
 ALL_PINS = [
     pin_golden_rational,
     pin_uniform_scores_mean_of_visible,
@@ -466,4 +513,5 @@ ALL_PINS = [
     pin_decode,
     pin_mean_pool,
     pin_memory_bank,
+    pin_frames_with_semantic_mask,
 ]

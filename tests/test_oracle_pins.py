@@ -97,6 +97,37 @@ class NumpyImpl:
             return np.resize(E.mean(axis=1), E.shape[1])
         return E.sum(axis=0) / E.shape[0]
 
+    def frames_prefill(self, Q, Kc, Vc, Kf, Vf, scale):
+        Q, Kf, Vf = (np.asarray(a, dtype=np.float64) for a in (Q, Kf, Vf))
+        F, T, Hq, D = Q.shape
+        Hkv = Kf.shape[2]
+        L = 0 if Kc is None else len(Kc)
+        parts_k = ([np.asarray(Kc, dtype=np.float64)] if L else []) + [Kf.reshape(F * T, Hkv, D)]
+        parts_v = ([np.asarray(Vc, dtype=np.float64)] if L else []) + [Vf.reshape(F * T, Hkv, D)]
+        Kall, Vall = np.concatenate(parts_k), np.concatenate(parts_v)
+        car = 0 if self.bug == "run_carrier_is_first_token" else T - 1
+        O = np.zeros((F, T, Hq, D))
+        for a in range(F):
+            for i in range(T):
+                mask = np.zeros(L + F * T, dtype=bool)
+                mask[:L] = True
+                for b in range(F):
+                    for j in range(T):
+                        own = b == a and (j <= i or self.bug == "run_sees_own_future")
+                        earlier = b < a and (j == car or self.bug == "run_no_semantic_mask")
+                        if self.bug == "run_no_earlier_carriers":
+                            earlier = False
+                        if self.bug == "run_sees_later_carriers":
+                            earlier = b != a and j == car
+                        mask[L + b * T + j] = own or earlier
+                idx = np.nonzero(mask)[0]
+                for h in range(Hq):
+                    g = h // (Hq // Hkv)
+                    z = (Kall[idx, g] @ Q[a, i, h]) * scale
+                    w = np.exp(z - z.max())
+                    O[a, i, h] = (w / w.sum()) @ Vall[idx, g]
+        return O
+
     def bank_victim(self, E, e_new, policy=0):
         E, e_new = np.asarray(E, dtype=np.float64), np.asarray(e_new, dtype=np.float64)
         M = len(E)
@@ -139,7 +170,9 @@ BUGS = ["gqa_interleaved", "scores_from_v", "no_scale", "scale_squared", "no_nor
         "keeps_first_token", "no_capacity_check", "overwrites_last", "v_gets_k",
         "decode_attends_before_append", "pool_sum", "pool_unbiased", "pool_over_features",
         "bank_ignores_incoming", "bank_dot_not_cosine", "bank_least_similar", "bank_tie_last",
-        "bank_drops_newer", "bank_overwrites_victim", "bank_new_row_off_by_one"]
+        "bank_drops_newer", "bank_overwrites_victim", "bank_new_row_off_by_one",
+        "run_carrier_is_first_token", "run_sees_own_future", "run_no_semantic_mask", "run_no_earlier_carriers",
+        "run_sees_later_carriers"]
 
 
 def _failures(impl):
