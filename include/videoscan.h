@@ -173,6 +173,25 @@ vs_status vs_carrier_mean_pool(const void *e, int32_t n, int32_t d, int32_t dtyp
                                void *hip_stream);
 
 /*
+ * A run of several frames in one call, under the semantic-aware mask (Section 3.4: later
+ * tokens reach earlier frames only through those frames' semantic carriers; Section 3.2: the
+ * carrier is the last token of its frame).  q, out [n_frames][n_tokens][n_q_heads][head_dim],
+ * k_f, v_f [n_frames][n_tokens][n_kv_heads][head_dim].  Token i of frame a sees the cache's
+ * `len` rows, the carriers (token n_tokens-1) of frames 0..a-1 of the run, and tokens 0..i of
+ * its own frame; Eq. 1 over that set.  All carriers are appended to the cache, in frame
+ * order, as rows len..len+n_frames-1, and cache->len grows by n_frames: the call computes what
+ * n_frames calls of vs_frame_prefill_compact would, one frame after the other.  bf16 only.
+ * 1 <= n_frames <= 64, n_frames * n_tokens <= 4096.  workspace: vs_frames_workspace_bytes.
+ * Errors as vs_frame_prefill_compact (VS_ERR_CAPACITY if the cache has no room for n_frames
+ * rows; VS_ERR_UNSUPPORTED for fp32 storage).
+ */
+size_t vs_frames_workspace_bytes(const vs_shape *shape, int32_t n_frames, int32_t n_tokens,
+                                 int32_t max_cache_rows);
+vs_status vs_frames_prefill_attn(const vs_shape *shape, vs_cache *cache, const void *q, const void *k_f,
+                                 const void *v_f, int32_t n_frames, int32_t n_tokens, void *out,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Memory bank of the semantic carriers (Section 3.3, memory mechanism): at most
  * `capacity` carriers are kept, oldest first; their embeddings live in `e`, their K/V
  * rows in the layers' caches behind the rows that are not carriers (e.g. a text prefix).

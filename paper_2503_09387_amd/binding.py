@@ -12,7 +12,7 @@ EXPORTS = [
     "vs_status_string", "vs_workspace_bytes", "vs_workspace_init", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
     "vs_carrier_compact_append", "vs_carrier_compact_append_batched", "vs_decode_attn",
     "vs_carrier_mean_pool", "vs_set_tuning", "vs_memory_bank_push", "vs_carrier_evict_append",
-    "vs_memory_bank_workspace_bytes",
+    "vs_frames_prefill_attn", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
 ]
 
 
@@ -92,7 +92,10 @@ def lib():
         L.vs_carrier_evict_append.argtypes = [sp, i32, vp, i32, i32, vp, vp, ctypes.c_int64, vp, vp]
         L.vs_memory_bank_workspace_bytes.argtypes = [i32]
         L.vs_memory_bank_workspace_bytes.restype = sz
-        for name in EXPORTS[2:-1]:
+        L.vs_frames_prefill_attn.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+        L.vs_frames_workspace_bytes.argtypes = [sp, i32, i32, i32]
+        L.vs_frames_workspace_bytes.restype = sz
+        for name in EXPORTS[2:-2]:
             getattr(L, name).restype = ctypes.c_int
         _LIB = L
     return _LIB
@@ -199,6 +202,18 @@ def decode_attn(shape, k_slab, v_slab, lens, q, k_new, v_new, out, workspace, st
     _check(lib().vs_decode_attn(ctypes.byref(shape), n_streams, _ptr(k_slab), _ptr(v_slab), capacity, lens,
                                 _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), wp, wb, _stream(stream)),
            "vs_decode_attn")
+
+
+def frames_workspace_bytes(shape, n_frames, n_tokens, max_cache_rows):
+    return int(lib().vs_frames_workspace_bytes(ctypes.byref(shape), n_frames, n_tokens, max_cache_rows))
+
+
+def frames_prefill_attn(shape, cache, q, k_f, v_f, out, workspace, stream=None):
+    """A run of frames under the semantic-aware mask: q, out [F][T][Hq][D], k_f, v_f [F][T][Hkv][D]."""
+    wp, wb = _ws(workspace)
+    _check(lib().vs_frames_prefill_attn(ctypes.byref(shape), ctypes.byref(cache.c), _ptr(q), _ptr(k_f), _ptr(v_f),
+                                        q.shape[0], q.shape[1], _ptr(out), wp, wb, _stream(stream)),
+           "vs_frames_prefill_attn")
 
 
 class _CBank(ctypes.Structure):

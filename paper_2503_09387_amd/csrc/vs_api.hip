@@ -293,6 +293,53 @@ vs_status vs_decode_attn(const vs_shape* shape, int32_t n_streams, void* k_slab,
     return VS_OK;
 }
 
+size_t vs_frames_workspace_bytes(const vs_shape* shape, int32_t n_frames, int32_t n_tokens,
+                                 int32_t max_cache_rows) {
+    if (check_shape(shape) != VS_OK || shape->dtype != VS_BF16) return 0;
+    if (n_frames < 1 || n_frames > 64 || n_tokens < 1 || (int64_t)n_frames * n_tokens > kMaxTokens ||
+        max_cache_rows < 0)
+        return 0;
+    // the plan's number of splits grows with the rows: size for the longest cache
+    int ns = prefill_frames_splits(*shape, n_frames, n_tokens, max_cache_rows);
+    // (short caches run one key group per workgroup and may take a split or two more)
+    for (int tiles = 1; tiles <= 7; ++tiles) {
+        const int len = tiles * 64 - n_tokens - (n_frames - 1);
+        if (len >= 0 && len <= max_cache_rows) ns = std::max(ns, prefill_frames_splits(*shape, n_frames, n_tokens, len));
+    }
+    size_t need = prefill_frames_workspace_bytes(*shape, n_frames, n_tokens, ns);
+    if (n_frames == 1) need = std::max(need, prefill_mfma_workspace_bytes(*shape, n_tokens));
+    return control_block_bytes(*shape) + round256(need);
+}
+
+vs_status vs_frames_prefill_attn(const vs_shape* shape, vs_cache* cache, const void* q, const void* k_f,
+                                 const void* v_f, int32_t n_frames, int32_t n_tokens, void* out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+    vs_status st = check_shape(shape);
+    if (st != VS_OK) return st;
+    if (shape->dtype != VS_BF16) return VS_ERR_UNSUPPORTED;
+    st = check_cache(cache, true);
+    if (st != VS_OK) return st;
+    if (!q || !k_f || !v_f || !out) return VS_ERR_NULL;
+    if (n_frames < 1 || n_frames > 64 || n_tokens < 1 || (int64_t)n_frames * n_tokens > kMaxTokens) return VS_ERR_SHAPE;
+    if ((int64_t)cache->len + n_frames > cache->capacity) return VS_ERR_CAPACITY;
+    if (!aligned16(q) || !aligned16(k_f) || !aligned16(v_f) || !aligned16(out)) return VS_ERR_ALIGN;
+    const size_t ctrl = control_block_bytes(*shape);
+    const int ns = prefill_frames_splits(*shape, n_frames, n_tokens, cache->len);
+    const size_t need = ctrl + prefill_frames_workspace_bytes(*shape, n_frames, n_tokens, ns);
+    if (!workspace || workspace_bytes < need) return VS_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return VS_ERR_ALIGN;
+    const int64_t rb = row_bytes(shape);
+    char* wsb = static_cast<char*>(workspace);
+    char* kdst = static_cast<char*>(cache->k) + (int64_t)cache->len * rb;
+    char* vdst = static_cast<char*>(cache->v) + (int64_t)cache->len * rb;
+    if (launch_prefill_mfma(*shape, cache->k, cache->v, cache->len, q, k_f, v_f, n_tokens, out, kdst, vdst,
+                            wsb + prefill_counter_offset(*shape), wsb + ctrl, static_cast<hipStream_t>(hip_stream),
+                            n_frames) != hipSuccess)
+        return VS_ERR_HIP;
+    cache->len += n_frames;
+    return VS_OK;
+}
+
 size_t vs_memory_bank_workspace_bytes(int32_t capacity) {
     if (capacity < 1 || capacity > 1024) return 0;
     return round256(sizeof(float) * (size_t)capacity);

@@ -41,10 +41,14 @@ hipError_t launch_decode_simple(const vs_shape& s, int32_t n_streams, const void
 
 // bf16 MFMA prefill with split along cache rows; optional fused carrier append.
 size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens);
+// n_frames > 1: q, kf, vf, out hold a run of frames [n_frames][n_tokens][..] under the semantic-aware
+// mask; k_append_dst / v_append_dst (row `len` of the cache) then receive all their carriers.
 hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc, int32_t len,
                                const void* q, const void* kf, const void* vf, int32_t n_tokens,
                                void* out, void* k_append_dst, void* v_append_dst, void* counters,
-                               void* workspace, hipStream_t st);
+                               void* workspace, hipStream_t st, int32_t n_frames = 1);
+size_t prefill_frames_workspace_bytes(const vs_shape& s, int32_t n_frames, int32_t n_tokens, int32_t nsplit);
+int prefill_frames_splits(const vs_shape& s, int32_t n_frames, int32_t n_tokens, int32_t len);
 
 // bf16 split-row decode over ragged streams; appends (k_new, v_new) on the side when given.
 // `counters` points at the decode counters of an initialised workspace control block.

@@ -86,6 +86,11 @@ struct PrefillParams {
     int xcd_shift;            // log2 of the number of XCDs workgroup ids are dealt to in turn
     int units_per_xcd;
     float inv_row_tiles;
+    // A run of F frames (semantic-aware mask, Section 3.4): frame a has its own T rows of q, kf,
+    // vf and out, and sees L + a retained rows (the carriers of the frames before it have been
+    // appended to the cache ahead of this launch).  F = 1: the single frame.
+    int F;
+    float inv_frame_tiles;    // 1 / (F * row tiles)
     unsigned long long* dbg;  // tuning aid: per-workgroup timestamps, normally null
 };
 
@@ -131,10 +136,11 @@ void prefill_mfma_kernel(PrefillParams p) {
     // fetches each one where it is first used, and waits there).
     const char* const kc = reinterpret_cast<const char*>(p.kc);
     const char* const vc = reinterpret_cast<const char*>(p.vc);
-    const char* const kf = reinterpret_cast<const char*>(p.kf);
-    const char* const vf = reinterpret_cast<const char*>(p.vf);
-    const char* const qbase = reinterpret_cast<const char*>(p.q);
-    const int L = p.L, T = p.T, G = p.G, M = p.M, Hkv = p.Hkv, nsplit = p.nsplit;
+    const char* kf = reinterpret_cast<const char*>(p.kf);
+    const char* vf = reinterpret_cast<const char*>(p.vf);
+    const char* qbase = reinterpret_cast<const char*>(p.q);
+    int L = p.L;
+    const int T = p.T, G = p.G, M = p.M, Hkv = p.Hkv, nsplit = p.nsplit;
     const float inv_G = p.inv_G, inv_nsplit = p.inv_nsplit;
     asm volatile("" : : "s"(kc), "s"(vc), "s"(kf), "s"(vf), "s"(qbase), "s"(L), "s"(T), "s"(G), "s"(M), "s"(Hkv),
                  "s"(nsplit), "s"(inv_G), "s"(inv_nsplit), "s"(p.Hq), "s"(p.scale_log2e), "s"(p.dbg));
@@ -145,27 +151,39 @@ void prefill_mfma_kernel(PrefillParams p) {
     const int rb = w & 1;   // which 64 rows of the tile
     const int kg = w >> 1;  // key group of this wave
     const int l32 = lane & 31, hi = lane >> 5;
-    int g, split, rt;
+    int g, split, rt, frame;
     if (p.arrivals) {
         // 1-D grid.  Workgroup ids are dealt to the XCDs in turn (id mod number of XCDs), and a
-        // unit = (KV head, row tile) is merged through the L2 its XCD's compute units share, so
+        // unit = (KV head, frame, row tile) is merged through the L2 its XCD's compute units share, so
         // all splits of a unit take ids of one residue: XCD x holds units x*units_per_xcd ..
         // (consecutive units: the same KV head, whose K/V that L2 then holds once), each with
         // nsplit consecutive slots.
         const int x = blockIdx.x & ((1 << p.xcd_shift) - 1), slot = blockIdx.x >> p.xcd_shift;
         const int j = div_small(slot, nsplit, inv_nsplit);
         const int unit = x * p.units_per_xcd + j;
-        if (j >= p.units_per_xcd || unit >= p.n_row_tiles * Hkv) return;  // spare ids
+        if (j >= p.units_per_xcd || unit >= p.n_row_tiles * p.F * Hkv) return;  // spare ids
         split = slot - j * nsplit;
-        g = div_small(unit, p.n_row_tiles, p.inv_row_tiles);
-        rt = unit - g * p.n_row_tiles;
+        g = div_small(unit, p.n_row_tiles * p.F, p.inv_frame_tiles);
+        const int ft = unit - g * p.n_row_tiles * p.F;
+        frame = div_small(ft, p.n_row_tiles, p.inv_row_tiles);
+        rt = ft - frame * p.n_row_tiles;
     } else {
-        // grid (Hkv, nsplit, row tiles): x runs fastest in dispatch order, so with nsplit*Hkv a
-        // multiple of the number of XCDs all workgroups that read one K/V slice share an L2
-        g = blockIdx.x, split = blockIdx.y, rt = blockIdx.z;
+        // grid (Hkv, nsplit, frames x row tiles): x runs fastest in dispatch order, so with
+        // nsplit*Hkv a multiple of the number of XCDs all workgroups that read one K/V slice
+        // share an L2
+        g = blockIdx.x, split = blockIdx.y;
+        frame = div_small(blockIdx.z, p.n_row_tiles, p.inv_row_tiles);
+        rt = blockIdx.z - frame * p.n_row_tiles;
     }
-    const int c = split * Hkv + g;  // which partial result
-    const int wg_id = rt * (nsplit * Hkv) + c;
+    // the frame's own tensors and retained rows
+    L += frame;
+    qbase += (int64_t)frame * T * p.Hq * (D * 2);
+    kf += (int64_t)frame * T * Hkv * kRowBytes;
+    vf += (int64_t)frame * T * Hkv * kRowBytes;
+    __bf16* const out = p.out + (int64_t)frame * T * p.Hq * D;
+    const int gf = g * p.F + frame, HF = Hkv * p.F;  // (head, frame) pairs index partial results and counters
+    const int c = split * HF + gf;  // which partial result
+    const int wg_id = rt * (nsplit * HF) + c;
     const int kv_row_bytes = Hkv * kRowBytes;
     char* const k_ring = dyn_smem + kg * kGroupLds;
     char* const v_ring = k_ring + 2 * kTileBytes;
@@ -560,7 +578,7 @@ void prefill_mfma_kernel(PrefillParams p) {
         if (p.nsplit == 1) {
             if (r_mine[r] < p.M) {
                 const int t = r_mine[r] / G, hl = r_mine[r] - t * G;
-                __bf16* orow = p.out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
+                __bf16* orow = out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -651,7 +669,7 @@ void prefill_mfma_kernel(PrefillParams p) {
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         __syncthreads();                     // also: the exchange area is free again
         unsigned* const box = reinterpret_cast<unsigned*>(dyn_smem);
-        unsigned* const counter = p.arrivals + g * p.n_row_tiles + rt;
+        unsigned* const counter = p.arrivals + gf * p.n_row_tiles + rt;
         if (tid == 0)
             *box = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         __syncthreads();
@@ -665,12 +683,12 @@ void prefill_mfma_kernel(PrefillParams p) {
                 const int rg = rb * 2 + r;
                 const bool row_ok = r_mine[r] < M;
                 const int t = row_ok ? div_small(r_mine[r], G, inv_G) : 0, hl = r_mine[r] - t * G;
-                __bf16* const orow = p.out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
-                const float* const ml0 = p.part_ml + ((int64_t)g * p.m_pad + r_mine[r]) * 2;
-                const int64_t ml_step = (int64_t)Hkv * p.m_pad * 2;      // floats between splits
+                __bf16* const orow = out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
+                const float* const ml0 = p.part_ml + ((int64_t)gf * p.m_pad + r_mine[r]) * 2;
+                const int64_t ml_step = (int64_t)HF * p.m_pad * 2;       // floats between splits
                 const bf16x8* const po0 = reinterpret_cast<const bf16x8*>(p.part_o) +
-                                          (((int64_t)g * p.n_row_tiles + rt) * 4 + rg) * (8 * 64) + lane;
-                const int64_t po_step = (int64_t)Hkv * p.n_row_tiles * 4 * (8 * 64);  // bf16x8 between splits
+                                          (((int64_t)gf * p.n_row_tiles + rt) * 4 + rg) * (8 * 64) + lane;
+                const int64_t po_step = (int64_t)HF * p.n_row_tiles * 4 * (8 * 64);  // bf16x8 between splits
                 // NS splits, the 8 pieces of a lane in PASSES rounds: everything of a round is
                 // requested before anything is used (a round trip to L2 is what this tail costs)
                 auto tail = [&](auto ns_tag, auto passes_tag) {
@@ -757,7 +775,8 @@ __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
     const int db = b & 3; b >>= 2;
     const int rg = b & 3; b >>= 2;
     const int rt = b;
-    const int g = blockIdx.y;
+    const int g = blockIdx.y, frame = blockIdx.z;
+    const int gf = g * p.F + frame, HF = p.Hkv * p.F;
     if (rt * BM + rg * 32 >= p.M) return;  // whole block beyond the rows
     const int r = rt * BM + rg * 32 + l32;
     const int rr = min(r, p.M - 1);
@@ -776,7 +795,7 @@ __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
             ms[u] = -INFINITY;
             ls[u] = 0.f;
             if (s0 + u < p.nsplit) {
-                const int c = (s0 + u) * p.Hkv + g;
+                const int c = (s0 + u) * HF + gf;
                 const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + ((int64_t)c * p.m_pad + rr) * 2);
                 ms[u] = ml.x;
                 ls[u] = ml.y;
@@ -807,7 +826,8 @@ __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
     if (r >= p.M) return;
     const float inv = 1.0f / denom;
     const int t = r / p.G, hl = r - t * p.G;
-    __bf16* orow = p.out + ((int64_t)t * p.Hq + (int64_t)g * p.G + hl) * D + 32 * db + 16 * h2 + 4 * hi;
+    __bf16* orow = p.out + (int64_t)frame * p.T * p.Hq * D + ((int64_t)t * p.Hq + (int64_t)g * p.G + hl) * D +
+                   32 * db + 16 * h2 + 4 * hi;
     bf16x4 w0, w1;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -834,14 +854,14 @@ __global__ void xcd_probe_kernel(unsigned* out) {
     if (threadIdx.x == 0) out[blockIdx.x] = x & 15u;
 }
 
-Plan make_plan(const vs_shape& s, int n_tokens, int len) {
+Plan make_plan(const vs_shape& s, int n_tokens, int len, int n_frames) {
     const int G = s.n_q_heads / s.n_kv_heads;
     const int M = n_tokens * G;
     Plan pl;
     pl.n_row_tiles = (M + BM - 1) / BM;
     pl.m_pad = pl.n_row_tiles * BM;
-    const int units = pl.n_row_tiles * s.n_kv_heads;
-    const int max_tiles = (len + n_tokens + BN - 1) / BN;
+    const int units = pl.n_row_tiles * s.n_kv_heads * n_frames;
+    const int max_tiles = (len + n_frames - 1 + n_tokens + BN - 1) / BN;
     // 4-wave workgroups (two key groups) when there are enough key tiles to share out
     pl.kvg = g_tune_prefill_kv_groups ? g_tune_prefill_kv_groups : (max_tiles >= 8 ? 2 : 1);
     int ns = (pl.kvg == 1 ? 512 : 256) / units;  // fill the chip in a single round
@@ -856,7 +876,7 @@ Plan make_plan(const vs_shape& s, int n_tokens, int len) {
     if (g_tune_prefill_splits) ns = g_tune_prefill_splits < max_tiles ? g_tune_prefill_splits : (max_tiles > 0 ? max_tiles : 1);
     pl.nsplit = ns;
     int dev = 0;
-    pl.merge_inside = g_tune_prefill_merge != 2 && ns > 1 && ns <= 8 && pl.n_row_tiles <= kMaxRowTiles &&
+    pl.merge_inside = g_tune_prefill_merge != 2 && ns > 1 && ns <= 8 && pl.n_row_tiles * n_frames <= kMaxRowTiles &&
                       hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && g_xcd_shift[dev] >= 0;
     return pl;
 }
@@ -873,11 +893,11 @@ hipError_t launch_kvg(const PrefillParams& p, const Plan& pl, int n_kv_heads, hi
     }
     // x runs fastest in dispatch order: all workgroups that read one K/V slice are neighbours
     const dim3 grid = p.arrivals ? dim3((unsigned)((p.units_per_xcd * pl.nsplit) << p.xcd_shift))
-                                 : dim3(n_kv_heads, pl.nsplit, pl.n_row_tiles);
+                                 : dim3(n_kv_heads, pl.nsplit, pl.n_row_tiles * p.F);
     prefill_mfma_kernel<KVG><<<grid, kGroupThreads * KVG, kLds, st>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.nsplit == 1 || g_tune_skip_merge || p.arrivals) return e;
-    prefill_combine_kernel<<<dim3(pl.n_row_tiles * 4 * 4 * 2, n_kv_heads), 64, 0, st>>>(p);
+    prefill_combine_kernel<<<dim3(pl.n_row_tiles * 4 * 4 * 2, n_kv_heads, p.F), 64, 0, st>>>(p);
     return hipGetLastError();
 }
 
@@ -915,11 +935,36 @@ size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens) {
     return (size_t)(slots * (D * sizeof(__bf16) + 2 * sizeof(float))) + (1u << 20);  // + tuning-aid block
 }
 
+// Bytes the partial results of a run of n_frames frames can take (the plan's own choice of
+// splits; a tuning override that asks for more is refused by the caller's size check).
+size_t prefill_frames_workspace_bytes(const vs_shape& s, int32_t n_frames, int32_t n_tokens, int32_t nsplit) {
+    const int G = s.n_q_heads / s.n_kv_heads;
+    const int64_t M = (int64_t)n_tokens * G;
+    const int64_t m_pad = ((M + BM - 1) / BM) * BM;
+    const int64_t slots = (int64_t)nsplit * s.n_kv_heads * n_frames * m_pad;
+    return (size_t)(slots * (D * sizeof(__bf16) + 2 * sizeof(float)));
+}
+
+int prefill_frames_splits(const vs_shape& s, int32_t n_frames, int32_t n_tokens, int32_t len) {
+    return make_plan(s, n_tokens, len, n_frames).nsplit;
+}
+
+__global__ __launch_bounds__(64) void gather_carriers_kernel(const uint4* __restrict__ kf, const uint4* __restrict__ vf,
+                                                             uint4* __restrict__ kdst, uint4* __restrict__ vdst,
+                                                             int T, int row16) {
+    // frame blockIdx.x: its last row (the carrier) becomes retained row blockIdx.x behind the old ones
+    const int64_t src = ((int64_t)blockIdx.x * T + (T - 1)) * row16, dst = (int64_t)blockIdx.x * row16;
+    for (int i = threadIdx.x; i < row16; i += 64) {
+        kdst[dst + i] = kf[src + i];
+        vdst[dst + i] = vf[src + i];
+    }
+}
+
 hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc, int32_t len,
                                const void* q, const void* kf, const void* vf, int32_t n_tokens,
                                void* out, void* k_append_dst, void* v_append_dst, void* counters,
-                               void* workspace, hipStream_t st) {
-    const Plan pl = make_plan(s, n_tokens, len);
+                               void* workspace, hipStream_t st, int32_t n_frames) {
+    const Plan pl = make_plan(s, n_tokens, len, n_frames);
     PrefillParams p;
     p.kc = (const __bf16*)kc;
     p.vc = (const __bf16*)vc;
@@ -944,18 +989,30 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
     p.arrivals = nullptr;
     p.xcd_shift = p.units_per_xcd = 0;
     p.inv_row_tiles = 1.0f / (float)pl.n_row_tiles;
+    p.F = n_frames;
+    p.inv_frame_tiles = 1.0f / (float)(pl.n_row_tiles * n_frames);
+    if (n_frames > 1) {
+        // the carriers of the run's frames go behind the retained rows first: frame a then reads
+        // len + a rows, exactly what it would find if the frames came one call at a time
+        p.k_append_dst = p.v_append_dst = nullptr;
+        const int row16 = s.n_kv_heads * kRowBytes / 16;
+        gather_carriers_kernel<<<n_frames, 64, 0, st>>>((const uint4*)kf, (const uint4*)vf, (uint4*)k_append_dst,
+                                                        (uint4*)v_append_dst, n_tokens, row16);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     if (pl.merge_inside && counters) {
         int dev = 0;
         (void)hipGetDevice(&dev);
         p.arrivals = (unsigned*)counters;
         p.xcd_shift = g_xcd_shift[dev];
-        const int units = pl.n_row_tiles * s.n_kv_heads, n_xcd = 1 << p.xcd_shift;
+        const int units = pl.n_row_tiles * s.n_kv_heads * n_frames, n_xcd = 1 << p.xcd_shift;
         p.units_per_xcd = (units + n_xcd - 1) / n_xcd;
     }
-    const int64_t slots = (int64_t)pl.nsplit * s.n_kv_heads * pl.m_pad;
+    const int64_t slots = (int64_t)pl.nsplit * s.n_kv_heads * n_frames * pl.m_pad;
     p.part_ml = (float*)workspace;
     p.part_o = (__bf16*)(p.part_ml + slots * 2);
-    p.dbg = g_tune_debug_mode == 7
+    p.dbg = g_tune_debug_mode == 7 && n_frames == 1
                 ? (unsigned long long*)((char*)workspace + prefill_mfma_workspace_bytes(s, n_tokens) - (1 << 20))
                 : nullptr;
     return pl.kvg == 1 ? launch_kvg<1>(p, pl, s.n_kv_heads, st) : launch_kvg<2>(p, pl, s.n_kv_heads, st);

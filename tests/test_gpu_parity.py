@@ -577,3 +577,50 @@ def test_stream_with_memory_bank_prefill_reads_the_bank():
         assert bank.len == o_n and all(c.len == first + o_n for c in caches)
     for l in range(n_layers):
         assert np.array_equal(caches[l].k.double().cpu().numpy(), o_k[l]) and np.array_equal(caches[l].v.double().cpu().numpy(), o_v[l])
+
+
+# ---------------------------------------------------------------------------- run of several frames
+@pytest.mark.parametrize("F,T,L,splits", [(1, 170, 300, 0), (4, 170, 1500, 0), (8, 170, 4296, 0), (3, 21, 0, 0),
+                                          (6, 40, 70, 0), (2, 170, 4296, 5), (64, 20, 500, 0)])
+def test_run_of_frames_with_semantic_mask(F, T, L, splits):
+    """Several frames in one call: outputs against the oracle's definition of the mask, the carriers
+    appended in frame order bit for bit, and the same as feeding the frames one call at a time."""
+    s = QW
+    hk, hv = cache_rows(61, s, L, 0.5)
+    q = draw(62, (F, T, s.n_q_heads, s.head_dim), 0.5 * 3, "bf16")
+    kf = draw(63, (F, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
+    vf = draw(64, (F, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
+    ref = oracle.frames_prefill(to_f64(q), to_f64(hk) if L else None, to_f64(hv) if L else None, to_f64(kf), to_f64(vf),
+                                scale32(s))
+    dt = torch.bfloat16
+
+    def fresh_cache():
+        k = torch.zeros((L + F, s.n_kv_heads, s.head_dim), dtype=dt, device=DEV)
+        v = torch.zeros_like(k)
+        if L:
+            k[:L].copy_(hk)
+            v[:L].copy_(hv)
+        return vs.Cache(k, v, L)
+
+    vs.set_tuning(vs.TUNE_PREFILL_SPLITS, splits)
+    cache = fresh_cache()
+    ws = torch.empty(vs.frames_workspace_bytes(vs_shape(s), F, T, L + F), dtype=torch.uint8, device=DEV)
+    vs.workspace_init(vs_shape(s), ws)
+    out = torch.full(q.shape, float("nan"), dtype=dt, device=DEV)
+    vs.frames_prefill_attn(vs_shape(s), cache, q.to(DEV), kf.to(DEV), vf.to(DEV), out, ws)
+    torch.cuda.synchronize()
+    assert cache.len == L + F
+    check_close(out, ref, "bf16", f"run of {F} frames of {T} over {L} rows")
+    assert same_bits(cache.k[L:], kf[:, T - 1]) and same_bits(cache.v[L:], vf[:, T - 1])
+    if L:
+        assert same_bits(cache.k[:L], hk) and same_bits(cache.v[:L], hv)
+    # one call per frame gives the same values up to the rounding of differently split sums
+    c2 = fresh_cache()
+    ws1 = workspace(s, T, L + F, 0)
+    for a in range(F):
+        o1 = torch.full(q.shape[1:], float("nan"), dtype=dt, device=DEV)
+        vs.frame_prefill_compact(vs_shape(s), c2, q[a].to(DEV), kf[a].to(DEV), vf[a].to(DEV), o1, ws1)
+        torch.cuda.synchronize()
+        d = (o1.float() - out[a].float()).abs().max().item()
+        assert d <= 2 ** -7 * out[a].float().abs().max().item() + 1e-6, f"frame {a}: {d}"
+    assert torch.equal(c2.k, cache.k) and torch.equal(c2.v, cache.v) and c2.len == cache.len
