@@ -89,13 +89,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--decode-steps", type=int, default=64)
     ap.add_argument("--parts", default="all",
-                    help="comma list of: stream,decode,cfg2,cfg5,compaction,bank,cpu (default all); "
+                    help="comma list of: stream,decode,cfg2,cfg5,compaction,bank,frames,cpu (default all); "
                          "calib = only a 1 GiB device copy, the known-size kernel that the HBM "
                          "counters of a rocprofv3 --pmc run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
-    parts = set("stream,decode,cfg2,cfg5,compaction,bank,cpu".split(",")) if args.parts == "all" \
+    parts = set("stream,decode,cfg2,cfg5,compaction,bank,frames,cpu".split(",")) if args.parts == "all" \
         else set(args.parts.split(","))
 
     import numpy as np
@@ -495,6 +495,50 @@ def main():
                  "32 KB host-to-device copy of the lengths); in the stream the compaction is fused into the "
                  "prefill launch and costs no launch of its own")
         log(f"[bench] compaction: batched {tb * 1e6:.1f} us = {moved / tb / 1e9:.0f} GB/s; single call {t1 * 1e6:.2f} us")
+
+    if "frames" in parts:
+        # catching up on a backlog: runs of F frames per call under the semantic-aware mask (Section 3.4),
+        # cfg3's shapes otherwise (28 layers, 4296 retained rows at the start); not the streamed metric
+        fr = {}
+        for Fb in (2, 3, 6, 8, 12):
+            qf = draw(21, (Fb, T, s.n_q_heads, s.head_dim), 0.5, "bf16").to(dev)
+            kff = draw(22, (Fb, T, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(dev)
+            vff = draw(23, (Fb, T, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(dev)
+            hk, hv = cache_rows(24, s, P0, 0.5)
+            n_calls = 6
+            capf = P0 + Fb * (n_calls + 2) + 1
+            fcaches = []
+            for l in range(NL):
+                kc = torch.zeros((capf, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+                vc = torch.zeros_like(kc)
+                kc[:P0].copy_(hk)
+                vc[:P0].copy_(hv)
+                fcaches.append(vs.Cache(kc, vc, P0))
+            wsf = torch.empty(vs.frames_workspace_bytes(sh, Fb, T, capf), dtype=torch.uint8, device=dev)
+            vs.workspace_init(sh, wsf)
+            of = torch.empty_like(qf)
+
+            def calls(n):
+                for _ in range(n):
+                    for l in range(NL):
+                        vs.frames_prefill_attn(sh, fcaches[l], qf, kff, vff, of, wsf)
+            calls(2)
+            a, b = event_pair()
+            torch.cuda.synchronize()
+            a.record()
+            calls(n_calls)
+            b.record()
+            torch.cuda.synchronize()
+            tf = a.elapsed_time(b) * 1e-3 / n_calls
+            flf = sum(prefill_flops(s, P0 + 2 * Fb + c_ * Fb + a_, T) for c_ in range(n_calls) for a_ in range(Fb)) / n_calls * NL
+            fr[f"F={Fb}"] = dict(frames_per_s=Fb / tf, us_per_layer_call=tf * 1e6 / NL, tflops=flf / tf / 1e12,
+                                 frac_mfma=flf / tf / 1e12 / PEAK_BF16_TFLOPS)
+            log(f"[bench] runs of {Fb} frames: {Fb / tf:.0f} frames/s, {tf * 1e6 / NL:.1f} us per layer call, "
+                f"{flf / tf / 1e12:.0f} TFLOP/s ({100 * flf / tf / 1e12 / PEAK_BF16_TFLOPS:.1f}% of bf16 peak)")
+            del fcaches, wsf
+        extras["runs_of_frames"] = dict(**fr, note="vs_frames_prefill_attn over 28 layers, same inputs every call (warm), "
+                                                  "HIP events around 6 x 28 calls; includes the carrier gather launch and "
+                                                  "the merge; catch-up mode, not the streamed metric")
 
     if "bank" in parts:
         # memory bank at capacity (Section 3.3, memory mechanism; the paper evaluates M = 64 and 128):

@@ -873,6 +873,23 @@ Plan make_plan(const vs_shape& s, int n_tokens, int len, int n_frames) {
     while (h % gcd8 != 0) gcd8 >>= 1;
     const int step = 8 / gcd8;
     if (ns >= step) ns -= ns % step;
+    // More units than half the chip has compute units (runs of frames, long runs of tokens): the
+    // workgroups go through the chip in several rounds, and more, shorter ones may end sooner
+    // than few long ones with a thin last round.  Estimated time of a launch in units of one
+    // pipeline step (one tile per key group, ~2 us): rounds x (steps of a workgroup + its fixed
+    // cost of ~2.25 steps), plus the merge when there are splits.
+    if (units > 128 && pl.kvg == 2) {
+        float best = 0.f;
+        for (int cand = 1; cand <= 8 && cand <= max_tiles / pl.kvg; ++cand) {
+            const int rounds = (units * cand + 255) / 256;
+            const int steps = ((max_tiles + cand - 1) / cand + pl.kvg - 1) / pl.kvg;
+            const float cost = rounds * (steps + 2.25f) + (cand > 1 ? 1.25f : 0.f);
+            if (cand == 1 || cost < best) {
+                best = cost;
+                ns = cand;
+            }
+        }
+    }
     if (g_tune_prefill_splits) ns = g_tune_prefill_splits < max_tiles ? g_tune_prefill_splits : (max_tiles > 0 ? max_tiles : 1);
     pl.nsplit = ns;
     int dev = 0;
