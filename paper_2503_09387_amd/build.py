@@ -33,8 +33,8 @@ def generate() -> None:
 def check_prefill_listing() -> None:
     """The prefill kernel keeps state in fixed registers that the compiler does not know about
     (accumulators and query fragments in a0..a191 for the whole kernel; scores, fragments and
-    temporaries in v128..v215 while the pipeline runs).  Compile it to a listing and make sure
-    that no compiler-generated instruction touches a0..a191, or writes v128..v215 between the
+    temporaries and packed probabilities in v128..v247 while the pipeline runs).  Compile it to a listing and make sure
+    that no compiler-generated instruction touches a0..a191, or writes v128..v247 between the
     first matrix block and the marker that ends the pipeline."""
     import re
     import tempfile
@@ -83,7 +83,10 @@ def check_prefill_listing() -> None:
             if d:
                 lo = int(d.group(1) or d.group(2))
                 hi = int(d.group(3) or lo)
-                if hi >= 128 and lo <= 215:
+                # (the exact redo of a sub-block rebuilds its packed probabilities in their fixed
+                # registers v216..v247: those conversions are the one intended compiler write)
+                rebuild = lo >= 216 and parts[0] == "v_cvt_pk_bf16_f32"
+                if hi >= 128 and lo <= 247 and not rebuild:
                     bad.append((ln, t, False))
     if bad:
         raise RuntimeError("prefill kernel: the compiler touches registers reserved for the hand-scheduled "
