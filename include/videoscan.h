@@ -258,13 +258,18 @@ vs_status vs_carrier_evict_append(const vs_shape *shape, int32_t n_layers, vs_ca
  *                             affected: there is no second kernel to leave out.)
  *   VS_TUNE_PREFILL_MERGE     2 = prefill always merges split results with the second kernel,
  *                             never inside the attention kernel
+ *   VS_TUNE_TIMESTAMPS        7 = the bf16 prefill kernel of single-frame calls records four clock
+ *                             readings per workgroup in the last MiB of the prefill part of the
+ *                             workspace (vs_workspace_bytes always includes that MiB).
+ *                             Measurement only.
  */
 typedef enum {
     VS_TUNE_PREFILL_SPLITS = 0,
     VS_TUNE_PREFILL_KV_GROUPS = 1,
     VS_TUNE_DECODE_CHUNK_ROWS = 2,
     VS_TUNE_SKIP_MERGE = 3,
-    VS_TUNE_PREFILL_MERGE = 4
+    VS_TUNE_PREFILL_MERGE = 4,
+    VS_TUNE_TIMESTAMPS = 99
 } vs_tune_knob;
 vs_status vs_set_tuning(int32_t knob, int32_t value);
 

@@ -434,7 +434,11 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
             return VS_OK;
         default: break;
     }
-    if (knob == 99) { g_tune_debug_mode = value; return VS_OK; }
+    if (knob == VS_TUNE_TIMESTAMPS) {
+        if (value != 0 && value != 7) return VS_ERR_SHAPE;
+        g_tune_debug_mode = value;
+        return VS_OK;
+    }
     return VS_ERR_SHAPE;
 }
 

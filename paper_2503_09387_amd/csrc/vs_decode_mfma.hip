@@ -59,7 +59,6 @@ struct DecodeParams {
     int n_wg;                // workgroups along x
     int total_tiles;         // tile_prefix[n_streams]
     float scale_log2e;
-    unsigned long long* dbg;  // tuning aid: per-workgroup timestamps, normally null
     LenTable lens;           // valid rows per stream, the appended row included
     int tile_prefix[kMaxStreamsPerLaunch + 1];  // tiles of the streams before this one
 };
@@ -153,12 +152,9 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
 #define VS_TILE(R0, X) VS_TILE_COMPUTE(R0, k0##X, k1##X, k2##X, k3##X, k4##X, k5##X, k6##X, k7##X)
 
 // Grid (n_wg, Hkv / nh).
-template <int MODE, int DEPTH>
-__global__ __launch_bounds__(kThreads, DEPTH == 1 ? 3 : 2) void decode_mfma_kernel(DecodeParams p) {
+__global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p) {
     __shared__ __attribute__((aligned(16))) char smem[kWaves * TR * VSTR * 2];  // per-wave V tiles
 
-    const unsigned long long t_start = p.dbg ? wall_clock64() : 0;
-    unsigned long long t_first = 0, t_loop = 0;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i16 = lane & 15, kq = lane >> 4;
@@ -172,7 +168,7 @@ __global__ __launch_bounds__(kThreads, DEPTH == 1 ? 3 : 2) void decode_mfma_kern
     __bf16* vs_w = reinterpret_cast<__bf16*>(smem) + wave * (TR * VSTR);
     const __bf16* vrd = &vs_w[(4 * kq + (i16 >> 2)) * VSTR + 4 * (i16 & 3)];
 
-  for (bool first_segment = true; flat < flat_end; first_segment = false, ++s) {
+  for (; flat < flat_end; ++s) {
     // ---- one segment: tiles [seg_a, seg_b) of stream s; this wavefront takes the sub-range
     //      [tile_a, tile_b) of it for head g ----
     const int len = p.lens.v[s];
@@ -199,7 +195,7 @@ __global__ __launch_bounds__(kThreads, DEPTH == 1 ? 3 : 2) void decode_mfma_kern
     uint4 k0b = zz, k1b = zz, k2b = zz, k3b = zz, k4b = zz, k5b = zz, k6b = zz, k7b = zz;
     uint4 v0b = zz, v1b = zz, v2b = zz, v3b = zz, v4b = zz, v5b = zz, v6b = zz, v7b = zz;
     if (0 < n_tiles) VS_FETCH(0, a);
-    if (DEPTH == 2 && 1 < n_tiles) VS_FETCH(1, b);
+    if (1 < n_tiles) VS_FETCH(1, b);
 
     // the step's new row also goes into the slab (nobody reads it from there in this launch):
     // done by the wavefront whose range ends with the stream's last tile
@@ -229,24 +225,8 @@ __global__ __launch_bounds__(kThreads, DEPTH == 1 ? 3 : 2) void decode_mfma_kern
     f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = o0, o2 = o0, o3 = o0, o4 = o0, o5 = o0, o6 = o0, o7 = o0;
     float m_ref = -INFINITY, l_run = 0.f;  // m_ref: softmax reference (log2 units), uniform per head column
 
-    if (p.dbg && first_segment) t_first = wall_clock64();
     // the LDS buffer is private to the wave, whose LDS operations execute in program order
-    for (int t = 0; t < n_tiles; t += DEPTH) {
-        if (DEPTH == 1) {
-            VS_PARK(a);
-            VS_TILE(row_begin + t * TR, a);
-            if (t + 1 < n_tiles) VS_FETCH(t + 1, a);
-            continue;
-        }
-        if (MODE == 1) {  // experiment: consume the loads without computing
-            o0[0] += __builtin_bit_cast(float, k0a.x ^ k1a.x ^ k2a.x ^ k3a.x ^ k4a.x ^ k5a.x ^ k6a.x ^ k7a.x ^ v0a.x ^ v1a.x ^ v2a.x ^ v3a.x ^ v4a.x ^ v5a.x ^ v6a.x ^ v7a.x);
-            if (t + 2 < n_tiles) VS_FETCH(t + 2, a);
-            if (t + 1 < n_tiles) {
-                o1[0] += __builtin_bit_cast(float, k0b.x ^ k1b.x ^ k2b.x ^ k3b.x ^ k4b.x ^ k5b.x ^ k6b.x ^ k7b.x ^ v0b.x ^ v1b.x ^ v2b.x ^ v3b.x ^ v4b.x ^ v5b.x ^ v6b.x ^ v7b.x);
-                if (t + 3 < n_tiles) VS_FETCH(t + 3, b);
-            }
-            continue;
-        }
+    for (int t = 0; t < n_tiles; t += 2) {
         VS_PARK(a);
         VS_TILE(row_begin + t * TR, a);
         if (t + 2 < n_tiles) VS_FETCH(t + 2, a);
@@ -256,7 +236,6 @@ __global__ __launch_bounds__(kThreads, DEPTH == 1 ? 3 : 2) void decode_mfma_kern
             if (t + 3 < n_tiles) VS_FETCH(t + 3, b);
         }
     }
-    if (p.dbg) t_loop = wall_clock64();
 
     // ---- this wavefront's result: lane (head = i16, kq) holds dims 16*db + 4*kq + e ----
     l_run += __shfl_xor(l_run, 16);
@@ -283,10 +262,6 @@ __global__ __launch_bounds__(kThreads, DEPTH == 1 ? 3 : 2) void decode_mfma_kern
         VS_OUT(o0, 0); VS_OUT(o1, 1); VS_OUT(o2, 2); VS_OUT(o3, 3);
         VS_OUT(o4, 4); VS_OUT(o5, 5); VS_OUT(o6, 6); VS_OUT(o7, 7);
 #undef VS_OUT
-    }
-    if (p.dbg && tid == 0) {
-        unsigned long long* d = p.dbg + (size_t)blockIdx.x * 4;
-        d[0] = t_start; d[1] = t_first; d[2] = t_loop; d[3] = wall_clock64();
     }
     flat = p.tile_prefix[s] + seg_b;  // next segment: the next stream
   }
@@ -440,11 +415,8 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     const int64_t rows = ((int64_t)kDecodeMaxWorkgroups + n_streams) * per_slot * p.G;
     p.part_ml = (float*)workspace;
     p.part_o = (__bf16*)(p.part_ml + rows * 2);
-    p.dbg = g_tune_debug_mode == 7 ? (unsigned long long*)((char*)workspace + (12u << 20)) : nullptr;
     const dim3 grid(p.n_wg, groups_y);
-    if (g_tune_debug_mode == 1) decode_mfma_kernel<1, 2><<<grid, kThreads, 0, st>>>(p);
-    else if (g_tune_debug_mode == 3) decode_mfma_kernel<0, 1><<<grid, kThreads, 0, st>>>(p);
-    else decode_mfma_kernel<0, 2><<<grid, kThreads, 0, st>>>(p);
+    decode_mfma_kernel<<<grid, kThreads, 0, st>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || g_tune_skip_merge) return e;
     decode_combine_kernel<<<dim3(n_streams, s.n_q_heads), 16 * kCombineGroups, 0, st>>>(p);
