@@ -248,7 +248,7 @@ def main():
     cpu = None
     if "cpu" in parts:
         import oracle
-        sample = [(f, l) for f in (0, 127, 255) for l in range(0, NL, 2)]  # 42 frame-layers
+        sample = [(f, l) for f in (0, 127, 255) for l in range(NL)]  # 84 frame-layers, ~12 s of CPU work
         t_tot = 0.0
         for f, l in sample:
             L = P0 + f
@@ -260,7 +260,7 @@ def main():
             t_tot += time.perf_counter() - t0
         per_layer = t_tot / len(sample)
         cpu = dict(value=1.0 / (per_layer * NL), unit="frames/s", cores=oracle.num_threads(), kind="oracle",
-                   sample=f"prefill of frames 0/127/255 x even layers of cfg3 ({len(sample)} frame-layers, "
+                   sample=f"prefill of frames 0/127/255 x all 28 layers of cfg3 ({len(sample)} frame-layers, "
                           f"{t_tot:.1f}s of CPU work); frames/s extrapolated as 1/(28 x mean per-layer time); "
                           f"fp64, OpenMP",
                    affinity_cores=len(os.sched_getaffinity(0)))
@@ -352,7 +352,7 @@ def main():
         if "cpu" in parts:
             import oracle
             t_tot = 0.0
-            n_l, n_t = 4, 8
+            n_l, n_t = 4, min(32, steps)
             for l in range(n_l):
                 for i in range(S):
                     n = lens0[i]
