@@ -147,6 +147,68 @@ def test_mean_pool_and_tuning_argument_errors():
     assert L.vs_set_tuning(2, 100) == 2 and L.vs_set_tuning(9, 1) == 2
     assert L.vs_set_tuning(3, 2) == 2 and L.vs_set_tuning(3, 1) == 0 and L.vs_set_tuning(3, 0) == 0
     assert L.vs_set_tuning(0, 4) == 0 and L.vs_set_tuning(0, 0) == 0
+    assert L.vs_set_tuning(4, 1) == 2 and L.vs_set_tuning(4, 2) == 0 and L.vs_set_tuning(4, 0) == 0
+    assert L.vs_set_tuning(99, 3) == 2 and L.vs_set_tuning(99, 0) == 0
+
+
+def test_memory_bank_argument_errors():
+    L = vs.lib()
+    assert L.vs_memory_bank_workspace_bytes(0) == 0 and L.vs_memory_bank_workspace_bytes(1025) == 0
+    assert L.vs_memory_bank_workspace_bytes(128) >= 4 * 128
+
+    def bank(e=FAKE, cap=4, ln=0, d=8, dt=vs.VS_BF16):
+        return binding._CBank(e, cap, ln, d, dt)
+
+    def push(b, e_new=FAKE, policy=0, victim=FAKE, ws=FAKE, wsb=1 << 20):
+        return L.vs_memory_bank_push(ctypes.byref(b), e_new, policy, victim, ws, wsb, None)
+
+    assert push(bank(e=None)) == 1 and push(bank(), e_new=None) == 1 and push(bank(), victim=None) == 1
+    assert push(bank(dt=7)) == 3
+    assert push(bank(cap=0)) == 2 and push(bank(cap=2000)) == 2 and push(bank(ln=5)) == 2
+    assert push(bank(d=4)) == 2                                    # 8 bytes per row: not a multiple of 16
+    assert push(bank(), policy=2) == 2
+    assert push(bank(e=ODD)) == 6 and push(bank(), victim=FAKE + 2) == 6
+    b = bank(ln=4)
+    assert push(b, ws=None) == 5 and push(b, wsb=8) == 5 and b.len == 4
+    # the K/V side
+    sh = _shape()
+
+    def evict(caches, n=1, first=2, cap=4, k=FAKE, v=FAKE, stride=0, victim=FAKE):
+        arr = (binding._CCache * len(caches))(*caches)
+        rc = L.vs_carrier_evict_append(ctypes.byref(sh), n, arr, first, cap, k, v, stride, victim, None)
+        return rc, [c.len for c in arr]
+
+    assert evict([_cache()], k=None)[0] == 1 and evict([_cache()], victim=None)[0] == 1
+    assert evict([_cache()], n=0)[0] == 2 and evict([_cache()], cap=0)[0] == 2 and evict([_cache()], stride=8)[0] == 2
+    assert evict([_cache(ln=1)])[0] == 2                           # fewer rows than the prefix
+    assert evict([_cache(ln=7)])[0] == 2                           # more carriers than the bank holds
+    assert evict([_cache(cap=5)]) == (4, [2])                      # prefix + bank does not fit, length untouched
+    assert evict([_cache(), _cache(ln=3)], n=2, stride=1024)[0] == 2   # layers out of step
+    assert evict([_cache()], k=ODD)[0] == 6
+
+
+def test_runs_of_frames_argument_errors():
+    L = vs.lib()
+    sh = _shape()
+    L.vs_frames_workspace_bytes.restype = ctypes.c_size_t
+    assert L.vs_frames_workspace_bytes(ctypes.byref(sh), 0, 170, 100) == 0
+    assert L.vs_frames_workspace_bytes(ctypes.byref(sh), 65, 10, 100) == 0
+    assert L.vs_frames_workspace_bytes(ctypes.byref(sh), 8, 1000, 100) == 0      # more than 4096 tokens in the run
+    assert L.vs_frames_workspace_bytes(ctypes.byref(_shape(4, 1, 64, vs.VS_F32)), 2, 10, 100) == 0
+    need = L.vs_frames_workspace_bytes(ctypes.byref(sh), 4, 170, 5000)
+    assert need > 0 and L.vs_frames_workspace_bytes(ctypes.byref(sh), 8, 170, 5000) >= need
+
+    def run(cache, q=FAKE, kf=FAKE, vf=FAKE, F=2, n=4, out=FAKE, ws=FAKE, wsb=1 << 30, shape=sh):
+        return L.vs_frames_prefill_attn(ctypes.byref(shape), ctypes.byref(cache), q, kf, vf, F, n, out, ws, wsb, None)
+
+    c = _cache(cap=8, ln=2)
+    assert run(c, q=None) == 1 and run(c, out=None) == 1
+    assert run(c, F=0) == 2 and run(c, F=65) == 2 and run(c, n=0) == 2 and run(c, F=8, n=1000) == 2
+    assert run(c, shape=_shape(4, 1, 64, vs.VS_F32)) == 3
+    assert run(_cache(cap=3, ln=2)) == 4 and run(c, F=7) == 4     # no room for the run's carriers
+    assert run(c, kf=ODD) == 6
+    assert run(c, ws=None) == 5 and run(c, wsb=64) == 5
+    assert c.len == 2
 
 
 def test_product_path_does_not_touch_the_oracle():
