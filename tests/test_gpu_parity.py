@@ -624,3 +624,59 @@ def test_run_of_frames_with_semantic_mask(F, T, L, splits):
         d = (o1.float() - out[a].float()).abs().max().item()
         assert d <= 2 ** -7 * out[a].float().abs().max().item() + 1e-6, f"frame {a}: {d}"
     assert torch.equal(c2.k, cache.k) and torch.equal(c2.v, cache.v) and c2.len == cache.len
+
+
+def test_prefill_random_shapes_sweep():
+    """Seeded sweep over cache lengths, run lengths, head groupings, forced splits and key-group
+    counts: exercises every way the key tiles can fall onto the (split, key group) lanes (fewer
+    tiles than lanes, frame tiles on several lanes, a lane made of frame tiles only, ...)."""
+    rng = np.random.default_rng(2024)
+    groupings = [(28, 4), (8, 8), (8, 1), (12, 4), (16, 2)]
+    for case in range(96):
+        hq, hkv = groupings[rng.integers(len(groupings))]
+        s = AttnShape(hq, hkv, 128, "bf16")
+        L = int(rng.choice([0, 1, 63, 64, 65, 127, 200, 449, 512, 1000, 1733]))
+        T = int(rng.choice([1, 2, 9, 19, 37, 64, 101, 170, 257]))
+        splits = int(rng.choice([0, 0, 1, 2, 3, 5, 8, 13, 32]))
+        kvg = int(rng.choice([0, 0, 1, 2]))
+        gain = float(rng.choice([1, 1, 6]))
+        vs.set_tuning(vs.TUNE_PREFILL_SPLITS, splits)
+        vs.set_tuning(vs.TUNE_PREFILL_KV_GROUPS, kvg)
+        hk, hv = cache_rows(700 + case, s, L, 0.5)
+        q, kf, vf = frame_inputs(700 + case, s, T, 0.5, q_gain=gain)
+        out, cache, row = run_prefill(s, hk, hv, L, q, kf, vf, fused=bool(case & 1))
+        ref = oracle_prefill_rows(s, q, hk, hv, L, kf, vf)
+        check_close(out, ref, "bf16", f"case {case}: Hq/Hkv {hq}/{hkv} L={L} T={T} splits={splits} kv_groups={kvg} gain={gain}")
+        if case & 1:
+            assert row == L and cache.len == L + 1 and same_bits(cache.k[L], kf[T - 1]) and same_bits(cache.v[L], vf[T - 1])
+
+
+def test_runs_of_frames_random_shapes_sweep():
+    rng = np.random.default_rng(77)
+    for case in range(24):
+        hq, hkv = [(28, 4), (8, 8), (8, 1)][rng.integers(3)]
+        s = AttnShape(hq, hkv, 128, "bf16")
+        F = int(rng.choice([1, 2, 3, 5, 9, 17]))
+        T = int(rng.choice([1, 3, 19, 40, 101]))
+        L = int(rng.choice([0, 5, 64, 130, 700]))
+        splits = int(rng.choice([0, 0, 2, 4, 7]))
+        vs.set_tuning(vs.TUNE_PREFILL_SPLITS, splits)
+        hk, hv = cache_rows(900 + case, s, L, 0.5)
+        q = draw(1000 + case, (F, T, hq, 128), 1.0, "bf16")
+        kf = draw(1100 + case, (F, T, hkv, 128), 0.5, "bf16")
+        vf = draw(1200 + case, (F, T, hkv, 128), 0.5, "bf16")
+        ref = oracle.frames_prefill(to_f64(q), to_f64(hk) if L else None, to_f64(hv) if L else None, to_f64(kf),
+                                    to_f64(vf), scale32(s))
+        k = torch.zeros((L + F, hkv, 128), dtype=torch.bfloat16, device=DEV)
+        v = torch.zeros_like(k)
+        if L:
+            k[:L].copy_(hk)
+            v[:L].copy_(hv)
+        cache = vs.Cache(k, v, L)
+        ws = torch.empty(max(vs.frames_workspace_bytes(vs_shape(s), F, T, L + F), 1 << 24), dtype=torch.uint8, device=DEV)
+        vs.workspace_init(vs_shape(s), ws)
+        out = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+        vs.frames_prefill_attn(vs_shape(s), cache, q.to(DEV), kf.to(DEV), vf.to(DEV), out, ws)
+        torch.cuda.synchronize()
+        check_close(out, ref, "bf16", f"case {case}: Hq/Hkv {hq}/{hkv} F={F} T={T} L={L} splits={splits}")
+        assert cache.len == L + F and same_bits(cache.k[L:], kf[:, T - 1]) and same_bits(cache.v[L:], vf[:, T - 1])
