@@ -91,7 +91,9 @@ def main():
     ap.add_argument("--parts", default="all",
                     help="comma list of: stream,decode,cfg2,cfg5,compaction,bank,frames,cpu (default all); "
                          "calib = only a 1 GiB device copy, the known-size kernel that the HBM "
-                         "counters of a rocprofv3 --pmc run are scaled by")
+                         "counters of a rocprofv3 --pmc run are scaled by; readprobe = only a read-only "
+                         "pass over as many bytes as a decode launch reads, the rate to hold the decode "
+                         "kernel against")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -118,6 +120,35 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         print(json.dumps({"calib": "4 device copies of 1 GiB (read 1 GiB, write 1 GiB each)"}))
+        return
+
+    if "readprobe" in parts:
+        # Reference for the HBM-bound kernels: a read-only pass (vs_probe_read_stream) over as many
+        # bytes as one cfg4 decode launch reads (159.5 MB), and over 336 MB, launches back to back
+        # over 16 distinct buffers (5.4 GB in all, so that no cache holds anything), timed with
+        # events on the launch stream around 256 launches.
+        st = vs.current_stream_handle()
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        rows = []
+        for nbytes in (159_481_856, 336_000_000):
+            bufs = [torch.randint(-2**31, 2**31 - 1, (nbytes // 4,), dtype=torch.int32, device=dev) for _ in range(16)]
+            for n_wg in (512, 1024, 2048):
+                for i in range(32):
+                    vs.probe_read_stream(bufs[i % 16], n_wg, sink, stream=st)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(256):
+                    vs.probe_read_stream(bufs[i % 16], n_wg, sink, stream=st)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 256
+                rows.append({"bytes": nbytes, "workgroups": n_wg, "us_per_launch": round(us, 2),
+                             "GB_per_s": round(nbytes / us * 1e-3, 1)})
+                log(f"[bench] read probe {nbytes / 1e6:.1f} MB, {n_wg} workgroups: {us:.2f} us per launch = "
+                    f"{nbytes / us * 1e-3:.0f} GB/s")
+            del bufs
+        print(json.dumps({"readprobe": rows}))
         return
 
     def shape_of(s):

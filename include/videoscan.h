@@ -273,6 +273,18 @@ typedef enum {
 } vs_tune_knob;
 vs_status vs_set_tuning(int32_t knob, int32_t value);
 
+/*
+ * Measurement aid, not part of the method: one read-only pass over `bytes` of device memory
+ * at src (16-byte aligned, a multiple of 16 bytes) by n_workgroups workgroups (1..65536) of
+ * 256 threads, each streaming an equal contiguous share with 16 loads of 16 bytes in flight
+ * per thread.  Nothing is computed or kept; sink (device, >= 4 bytes) exists only so that
+ * the loads are not dead code and is in practice never written.  Gives the rate at which a
+ * kernel of this library's kind can read HBM on the device at hand, as a reference for the
+ * decode kernel, which reads every K/V row once.
+ */
+vs_status vs_probe_read_stream(const void *src, size_t bytes, int32_t n_workgroups, void *sink,
+                               void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

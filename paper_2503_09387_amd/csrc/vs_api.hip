@@ -453,4 +453,13 @@ vs_status vs_carrier_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtyp
                ? VS_OK : VS_ERR_HIP;
 }
 
+vs_status vs_probe_read_stream(const void* src, size_t bytes, int32_t n_workgroups, void* sink,
+                               void* hip_stream) {
+    if (!src || !sink) return VS_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || n_workgroups < 1 || n_workgroups > 65536) return VS_ERR_SHAPE;
+    if (!aligned16(src)) return VS_ERR_ALIGN;
+    return launch_read_probe(src, bytes, n_workgroups, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? VS_OK : VS_ERR_HIP;
+}
+
 }  // extern "C"

@@ -87,4 +87,7 @@ hipError_t launch_bank_shift(int32_t n_tables, void* const* bases, const void* c
 hipError_t launch_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, void* c_out,
                             hipStream_t st);
 
+// measurement aid: a read-only pass over `bytes`
+hipError_t launch_read_probe(const void* src, size_t bytes, int32_t n_wg, void* sink, hipStream_t st);
+
 }  // namespace vs

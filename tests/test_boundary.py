@@ -151,6 +151,17 @@ def test_mean_pool_and_tuning_argument_errors():
     assert L.vs_set_tuning(99, 3) == 2 and L.vs_set_tuning(99, 0) == 0
 
 
+def test_read_probe_argument_errors():
+    L = vs.lib()
+    assert L.vs_probe_read_stream(None, 1024, 8, FAKE, None) == 1
+    assert L.vs_probe_read_stream(FAKE, 1024, 8, None, None) == 1
+    assert L.vs_probe_read_stream(FAKE, 0, 8, FAKE, None) == 2
+    assert L.vs_probe_read_stream(FAKE, 1000, 8, FAKE, None) == 2    # not a multiple of 16 bytes
+    assert L.vs_probe_read_stream(FAKE, 1024, 0, FAKE, None) == 2
+    assert L.vs_probe_read_stream(FAKE, 1024, 70000, FAKE, None) == 2
+    assert L.vs_probe_read_stream(ODD, 1024, 8, FAKE, None) == 6
+
+
 def test_memory_bank_argument_errors():
     L = vs.lib()
     assert L.vs_memory_bank_workspace_bytes(0) == 0 and L.vs_memory_bank_workspace_bytes(1025) == 0
