@@ -72,6 +72,14 @@ def lib():
         path = lib_path()
         if not os.path.exists(path):
             raise RuntimeError(f"{path} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # torch ships a HIP runtime of its own under the same soname as the one the library was
+        # linked against; whichever is loaded first serves both.  torch's has to be the one: with
+        # the system's loaded first, torch ends up on a mix of its own and the system's ROCm
+        # libraries and finds no device.  So torch, when installed, is imported before the library.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(path)
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         sp, cp, ip = ctypes.POINTER(Shape), ctypes.POINTER(_CCache), ctypes.POINTER(ctypes.c_int32)

@@ -6,6 +6,8 @@
 #include <algorithm>
 #include <vector>
 
+#include <cstdio>
+#include <cstdlib>
 #include "vs_internal.h"
 
 using namespace vs;
@@ -143,9 +145,14 @@ vs_status vs_workspace_init(const vs_shape* shape, void* workspace, size_t works
     if (workspace_bytes < control_block_bytes(*shape)) return VS_ERR_WORKSPACE;
     // the first call on a device also finds out how that device deals workgroups to its XCDs
     // (one tiny launch into the control block and a wait for it)
-    if (probe_xcd_mapping(workspace, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return VS_ERR_HIP;
-    return launch_zero_fill(workspace, control_block_bytes(*shape), static_cast<hipStream_t>(hip_stream)) ==
-                   hipSuccess ? VS_OK : VS_ERR_HIP;
+    hipError_t e = probe_xcd_mapping(workspace, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) {
+        if (getenv("VS_DEBUG")) fprintf(stderr, "vs_workspace_init: probe: %s\n", hipGetErrorString(e));
+        return VS_ERR_HIP;
+    }
+    e = launch_zero_fill(workspace, control_block_bytes(*shape), static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess && getenv("VS_DEBUG")) fprintf(stderr, "vs_workspace_init: fill: %s\n", hipGetErrorString(e));
+    return e == hipSuccess ? VS_OK : VS_ERR_HIP;
 }
 
 vs_status vs_frame_prefill_attn(const vs_shape* shape, const vs_cache* cache, const void* q,

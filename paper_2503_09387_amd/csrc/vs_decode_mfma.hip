@@ -58,6 +58,7 @@ struct DecodeParams {
     int nh, nsub;            // KV heads per workgroup (min(Hkv, 4)) and sub-ranges per share (4 / nh)
     int n_wg;                // workgroups along x
     int total_tiles;         // tile_prefix[n_streams]
+    int share_q, share_r;    // total_tiles = n_wg * share_q + share_r: the first share_r workgroups take share_q + 1 tiles
     float scale_log2e;
     LenTable lens;           // valid rows per stream, the appended row included
     int tile_prefix[kMaxStreamsPerLaunch + 1];  // tiles of the streams before this one
@@ -65,7 +66,7 @@ struct DecodeParams {
 
 // first flat tile of workgroup w (w = n_wg gives the end)
 __device__ __forceinline__ int wg_first_tile(const DecodeParams& p, int w) {
-    return (int)((int64_t)w * p.total_tiles / p.n_wg);
+    return w * p.share_q + min(w, p.share_r);
 }
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
@@ -163,18 +164,25 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
     const int64_t row_stride = (int64_t)p.Hkv * D;
     const int flat_end = wg_first_tile(p, blockIdx.x + 1);
     int flat = wg_first_tile(p, blockIdx.x);
+    // Lane i holds the end of stream i in flat tiles and its length: one fetch at the start, and
+    // whatever a segment needs of a stream is then read out of these registers (a fetch per
+    // segment would sit between the workgroup's start and its first K/V loads).
+    static_assert(kMaxStreamsPerLaunch <= 64, "one lane per stream");
+    const int end_of = p.tile_prefix[min(lane, kMaxStreamsPerLaunch - 1) + 1];
+    const int len_of = p.lens.v[min(lane, kMaxStreamsPerLaunch - 1)];
     // stream of the first tile: the number of streams that end at or before it
-    int s = __builtin_popcountll(__ballot(p.tile_prefix[lane + 1] <= flat));
+    int s = __builtin_popcountll(__ballot(end_of <= flat));
     __bf16* vs_w = reinterpret_cast<__bf16*>(smem) + wave * (TR * VSTR);
     const __bf16* vrd = &vs_w[(4 * kq + (i16 >> 2)) * VSTR + 4 * (i16 & 3)];
 
   for (; flat < flat_end; ++s) {
     // ---- one segment: tiles [seg_a, seg_b) of stream s; this wavefront takes the sub-range
     //      [tile_a, tile_b) of it for head g ----
-    const int len = p.lens.v[s];
-    const int stream_tiles = p.tile_prefix[s + 1] - p.tile_prefix[s];
-    const int seg_a = flat - p.tile_prefix[s];
-    const int seg_b = min(stream_tiles, flat_end - p.tile_prefix[s]);
+    const int len = __builtin_amdgcn_readlane(len_of, s);
+    const int first_of = s ? __builtin_amdgcn_readlane(end_of, s - 1) : 0;
+    const int stream_tiles = __builtin_amdgcn_readlane(end_of, s) - first_of;
+    const int seg_a = flat - first_of;
+    const int seg_b = min(stream_tiles, flat_end - first_of);
     const bool whole_stream = seg_a == 0 && seg_b == stream_tiles && p.nsub == 1;
     const int tile_a = seg_a + (seg_b - seg_a) * sub / p.nsub;
     const int tile_b = seg_a + (seg_b - seg_a) * (sub + 1) / p.nsub;
@@ -263,7 +271,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
         VS_OUT(o4, 4); VS_OUT(o5, 5); VS_OUT(o6, 6); VS_OUT(o7, 7);
 #undef VS_OUT
     }
-    flat = p.tile_prefix[s] + seg_b;  // next segment: the next stream
+    flat = first_of + seg_b;  // next segment: the next stream
   }
 }
 #undef VS_TILE_COMPUTE
@@ -287,10 +295,8 @@ __global__ __launch_bounds__(16 * kCombineGroups) void decode_combine_kernel(Dec
     const int tid = threadIdx.x, pg = tid >> 4, t = tid & 15, d8 = t * 8;
     // largest w with wg_first_tile(w) <= tile
     auto owner = [&](int tile) {
-        int w = (int)(((int64_t)tile * p.n_wg) / p.total_tiles);
-        while (w + 1 < p.n_wg && wg_first_tile(p, w + 1) <= tile) ++w;
-        while (w > 0 && wg_first_tile(p, w) > tile) --w;
-        return w;
+        const int big = p.share_r * (p.share_q + 1);  // tiles held by the workgroups with one tile more
+        return tile < big ? tile / (p.share_q + 1) : p.share_r + (tile - big) / max(p.share_q, 1);
     };
     const int w_first = owner(p.tile_prefix[s]), w_last = owner(p.tile_prefix[s + 1] - 1);
     if (w_first == w_last && p.nsub == 1) return;
@@ -411,6 +417,8 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     if (n_wg > kDecodeMaxWorkgroups) n_wg = kDecodeMaxWorkgroups;
     if (n_wg < 1) n_wg = 1;
     p.n_wg = (int)n_wg;
+    p.share_q = p.total_tiles / p.n_wg;
+    p.share_r = p.total_tiles % p.n_wg;
     const int per_slot = s.n_kv_heads < kWaves ? kWaves : s.n_kv_heads;
     const int64_t rows = ((int64_t)kDecodeMaxWorkgroups + n_streams) * per_slot * p.G;
     p.part_ml = (float*)workspace;

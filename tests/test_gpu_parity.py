@@ -680,3 +680,26 @@ def test_runs_of_frames_random_shapes_sweep():
         torch.cuda.synchronize()
         check_close(out, ref, "bf16", f"case {case}: Hq/Hkv {hq}/{hkv} F={F} T={T} L={L} splits={splits}")
         assert cache.len == L + F and same_bits(cache.k[L:], kf[:, T - 1]) and same_bits(cache.v[L:], vf[:, T - 1])
+
+
+def test_package_used_before_torch_is_imported():
+    """A fresh process that touches the library before it imports torch (here: a tuning call)
+    must still find the device afterwards: library and torch share one HIP runtime, torch's,
+    whichever of the two the program names first."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "import paper_2503_09387_amd as vs\n"
+        "vs.set_tuning(vs.TUNE_PREFILL_SPLITS, 0)\n"
+        "import torch\n"
+        "sh = vs.Shape.make(28, 4, 128, 'bf16', 0.0883883)\n"
+        "ws = vs.make_workspace(sh, 8, 64, 2, 'cuda:0')\n"
+        "e = torch.ones((4, 64), dtype=torch.float32, device='cuda:0'); c = torch.empty(64, device='cuda:0')\n"
+        "vs.carrier_mean_pool(e, c, 'f32'); torch.cuda.synchronize()\n"
+        "assert bool((c == 1).all())\n"
+        "print('ok')\n" % root)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=100)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
