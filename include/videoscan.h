@@ -96,6 +96,8 @@ size_t vs_workspace_bytes(const vs_shape *shape, int32_t max_q_tokens, int32_t m
  * Must have completed on the device (same stream, or
  * synchronised) before the first call that uses the workspace; needed once, not per
  * call.  A workspace is tied to the shape it was initialised with.
+ * With the environment variable VS_DEBUG set, a HIP error behind VS_ERR_HIP from this call
+ * is also printed on stderr as text.
  */
 vs_status vs_workspace_init(const vs_shape *shape, void *workspace, size_t workspace_bytes,
                             void *hip_stream);
