@@ -13,5 +13,6 @@ from .vs_oracle import (  # noqa: F401
     frames_prefill,
     mean_pool,
     num_threads,
+    query_prefill,
     OracleError,
 )

@@ -358,3 +358,35 @@ int vs_oracle_frames_prefill(const double *Q, const double *Kc, const double *Vc
     }
     return failed ? VSO_ERR_NOMEM : VSO_OK;
 }
+
+/*
+ * The question after the video (Section 3.3, decoding phase; mask of Section 3.4:
+ * text reaches the frames only through the retained carrier rows).  The Tq
+ * question tokens arrive in order; token j's K/V row is appended to the cache
+ * at row *len + j, then its query attends over every row present, its own
+ * included, and over nothing that comes later.  All Tq rows stay in the cache:
+ * the answer is decoded on top of them.  Written out token by token, as the
+ * sequence of events it is.  Q, O [Tq][Hq][D]; Kt, Vt [Tq][Hkv][D]; Kc, Vc
+ * [capacity][Hkv][D] modified in place; *len grows by Tq.
+ */
+int vs_oracle_query_prefill(const double *Q, double *Kc, double *Vc, int64_t capacity, int64_t *len,
+                            const double *Kt, const double *Vt, int64_t Tq,
+                            int32_t Hq, int32_t Hkv, int32_t D, double scale, double *O) {
+    if (!Q || !Kc || !Vc || !len || !Kt || !Vt || !O) return VSO_ERR_ARG;
+    if (Tq < 1 || *len < 0 || *len > capacity) return VSO_ERR_ARG;
+    if (*len + Tq > capacity) return VSO_ERR_CAPACITY;
+    const size_t row = (size_t)Hkv * D;
+    for (int64_t j = 0; j < Tq; ++j) {
+        const int64_t at = *len;
+        for (size_t e = 0; e < row; ++e) {
+            Kc[(size_t)at * row + e] = Kt[(size_t)j * row + e];
+            Vc[(size_t)at * row + e] = Vt[(size_t)j * row + e];
+        }
+        *len = at + 1;
+        int64_t vis = *len;
+        int rc = vs_oracle_attention(Q + (size_t)j * Hq * D, 1, Hq, Hkv, D, Kc, Vc, *len, &vis, scale,
+                                     O + (size_t)j * Hq * D, NULL);
+        if (rc != VSO_OK) return rc;
+    }
+    return VSO_OK;
+}

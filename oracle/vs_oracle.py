@@ -40,6 +40,7 @@ def _lib():
         lib.vs_oracle_decode.argtypes = [dp, dp, dp, i64, ip, dp, dp, i32, i32, i32, f64, dp]
         lib.vs_oracle_mean_pool.argtypes = [dp, i64, i64, dp]
         lib.vs_oracle_frames_prefill.argtypes = [dp, dp, dp, i64, dp, dp, i64, i64, i32, i32, i32, f64, dp]
+        lib.vs_oracle_query_prefill.argtypes = [dp, dp, dp, i64, ip, dp, dp, i64, i32, i32, i32, f64, dp]
         lib.vs_oracle_bank_victim.argtypes = [dp, i64, i64, dp, i32, dp, ip]
         lib.vs_oracle_bank_apply.argtypes = [dp, i64, i64, i64, i64, i64, i64, dp, ip]
         _LIB = lib
@@ -195,3 +196,22 @@ def frames_prefill(Q, Kc, Vc, Kf, Vf, scale):
     if rc:
         raise OracleError(rc, "frames_prefill")
     return O
+
+
+def query_prefill(Q, Kc, Vc, length, Kt, Vt, scale):
+    """The question's Tq tokens over the retained rows (Section 3.3, decoding phase): token j is
+    appended at row length + j and attends over every row up to and including its own.
+    Kc/Vc [capacity][Hkv][D] are modified in place.  Returns (O [Tq][Hq][D], new_len)."""
+    assert Kc.dtype == np.float64 and Vc.dtype == np.float64
+    assert Kc.flags.c_contiguous and Vc.flags.c_contiguous
+    Q, Kt, Vt = _c(Q), _c(Kt), _c(Vt)
+    Tq, Hq, D = Q.shape
+    cap, Hkv, D2 = Kc.shape
+    assert D2 == D and Kt.shape == (Tq, Hkv, D) and Vt.shape == Kt.shape and Vc.shape == Kc.shape
+    ln = ctypes.c_int64(int(length))
+    O = np.empty((Tq, Hq, D), dtype=np.float64)
+    rc = _lib().vs_oracle_query_prefill(_p(Q), _p(Kc), _p(Vc), cap, ctypes.byref(ln), _p(Kt), _p(Vt), Tq,
+                                        Hq, Hkv, D, float(scale), _p(O))
+    if rc:
+        raise OracleError(rc, "query_prefill")
+    return O, int(ln.value)

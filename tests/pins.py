@@ -495,6 +495,56 @@ def pin_frames_with_semantic_mask(impl):
     assert all(np.abs(O3[a] - O[a]).min() > 0 for a in (2, 3)) and np.abs(O3[1, T - 1] - O[1, T - 1]).min() > 0
 
 
+def pin_question_after_the_video(impl):
+    """Section 3.3, decoding phase: the question's tokens are appended in order, each attends over
+    everything up to itself, and all of them stay in the cache for the answer."""
+    r = _rng(53)
+    L, Tq, Hq, Hkv, D = 6, 5, 4, 2, 6
+    cap = L + Tq + 2
+    Kc, Vc = r.normal(size=(cap, Hkv, D)), r.normal(size=(cap, Hkv, D))   # rows >= L: junk that must not count
+    Q, Kt, Vt = r.normal(size=(Tq, Hq, D)), r.normal(size=(Tq, Hkv, D)), r.normal(size=(Tq, Hkv, D))
+    K0, V0 = Kc.copy(), Vc.copy()
+    O, n = impl.query_prefill(Q, Kc, Vc, L, Kt, Vt, 0.6)
+    assert n == L + Tq
+    assert np.array_equal(Kc[L:n], Kt) and np.array_equal(Vc[L:n], Vt), "all question rows stay, in order"
+    assert np.array_equal(Kc[:L], K0[:L]) and np.array_equal(Vc[:L], V0[:L])
+    assert np.array_equal(Kc[n:], K0[n:]) and np.array_equal(Vc[n:], V0[n:])
+    # the same numbers as a causal run over the old rows (the frame prefill, which keeps nothing) ...
+    _close(O, impl.frame_prefill(Q, K0[:L], V0[:L], Kt, Vt, 0.6), 1e-14, "question vs causal run")
+    # ... and as Tq decoding steps one after the other
+    K2, V2, m = K0.copy(), V0.copy(), L
+    for j in range(Tq):
+        o, m = impl.decode(Q[j], K2, V2, m, Kt[j], Vt[j], 0.6)
+        _close(O[j], o, 1e-14, f"question token {j} vs a decoding step")
+    assert m == n and np.array_equal(K2, Kc) and np.array_equal(V2, Vc)
+    # brute force for a few (token, head) pairs
+    for j, h in ((0, 0), (2, 3), (4, 1)):
+        g = h // (Hq // Hkv)
+        rows_k = [K0[i, g] for i in range(L)] + [Kt[i, g] for i in range(j + 1)]
+        rows_v = [V0[i, g] for i in range(L)] + [Vt[i, g] for i in range(j + 1)]
+        z = [0.6 * math.fsum(Q[j, h] * k) for k in rows_k]
+        mx = max(z)
+        w = [math.exp(x - mx) for x in z]
+        want = [math.fsum(w[i] * rows_v[i][d] for i in range(len(w))) / math.fsum(w) for d in range(D)]
+        _close(O[j, h], np.array(want), 1e-13, f"brute force ({j},{h})")
+    # the answer's first decoding step sees every question row
+    qd = r.normal(size=(Hq, D))
+    o1, _ = impl.decode(qd, Kc.copy(), Vc.copy(), n, None, None, 0.6)
+    for j in range(Tq):
+        Vp = Vc.copy()
+        Vp[L + j] += 3.0
+        o2, _ = impl.decode(qd, Kc.copy(), Vp, n, None, None, 0.6)
+        assert np.abs(o2 - o1).min() > 0, f"question row {j} is not seen by the answer"
+    # a full cache is refused and nothing is touched
+    Kf_, Vf_ = K0[:L + Tq - 1].copy(), V0[:L + Tq - 1].copy()
+    try:
+        impl.query_prefill(Q, Kf_, Vf_, L, Kt, Vt, 0.6)
+    except Exception:
+        assert np.array_equal(Kf_, K0[:L + Tq - 1]) and np.array_equal(Vf_, V0[:L + Tq - 1])
+    else:
+        raise AssertionError("a question that does not fit must be refused")
+
+
 ALL_PINS = [
     pin_golden_rational,
     pin_uniform_scores_mean_of_visible,
@@ -514,4 +564,5 @@ ALL_PINS = [
     pin_mean_pool,
     pin_memory_bank,
     pin_frames_with_semantic_mask,
+    pin_question_after_the_video,
 ]

@@ -87,6 +87,27 @@ class NumpyImpl:
         o = self.attention(np.asarray(q)[None], Kc[:seen], Vc[:seen], np.array([seen]), scale)[0]
         return o, n
 
+    def query_prefill(self, Q, Kc, Vc, length, Kt, Vt, scale):
+        Q, Kt, Vt = (np.asarray(a, dtype=np.float64) for a in (Q, Kt, Vt))
+        Tq = Q.shape[0]
+        if length + Tq > len(Kc) and self.bug != "question_no_capacity_check":
+            raise ValueError("cache full")
+        at = length + 1 if self.bug == "question_rows_off_by_one" else length
+        keep = range(Tq - 1, Tq) if self.bug == "question_keeps_last_token_only" else range(Tq)
+        Kall = np.concatenate([Kc[:length], Kt])
+        Vall = np.concatenate([Vc[:length], Vt])
+        if self.bug == "question_not_causal":
+            vis = np.full(Tq, length + Tq)
+        elif self.bug == "question_blind_to_itself":
+            vis = length + np.arange(Tq) + (np.arange(Tq) == 0)
+        else:
+            vis = length + np.arange(Tq) + 1
+        O = self.attention(Q, Kall, Vall, vis, scale)
+        for j in keep:
+            row = min(at + (j if len(keep) > 1 else 0), len(Kc) - 1)
+            Kc[row], Vc[row] = Kt[j], Vt[j]
+        return O, length + (len(keep) if self.bug != "question_length_plus_one" else 1)
+
     def mean_pool(self, E):
         E = np.asarray(E, dtype=np.float64)
         if self.bug == "pool_sum":
@@ -172,7 +193,8 @@ BUGS = ["gqa_interleaved", "scores_from_v", "no_scale", "scale_squared", "no_nor
         "bank_ignores_incoming", "bank_dot_not_cosine", "bank_least_similar", "bank_tie_last",
         "bank_drops_newer", "bank_overwrites_victim", "bank_new_row_off_by_one",
         "run_carrier_is_first_token", "run_sees_own_future", "run_no_semantic_mask", "run_no_earlier_carriers",
-        "run_sees_later_carriers"]
+        "run_sees_later_carriers", "question_rows_off_by_one", "question_keeps_last_token_only",
+        "question_not_causal", "question_blind_to_itself", "question_length_plus_one", "question_no_capacity_check"]
 
 
 def _failures(impl):
