@@ -89,7 +89,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--decode-steps", type=int, default=64)
     ap.add_argument("--parts", default="all",
-                    help="comma list of: stream,decode,cfg2,cfg5,compaction,bank,frames,cpu (default all); "
+                    help="comma list of: stream,decode,cfg2,cfg5,compaction,bank,frames,question,cpu (default all); "
                          "calib = only a 1 GiB device copy, the known-size kernel that the HBM "
                          "counters of a rocprofv3 --pmc run are scaled by; readprobe = only a read-only "
                          "pass over as many bytes as a decode launch reads, the rate to hold the decode "
@@ -97,7 +97,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
-    parts = set("stream,decode,cfg2,cfg5,compaction,bank,frames,cpu".split(",")) if args.parts == "all" \
+    parts = set("stream,decode,cfg2,cfg5,compaction,bank,frames,question,cpu".split(",")) if args.parts == "all" \
         else set(args.parts.split(","))
 
     import numpy as np
@@ -570,6 +570,49 @@ def main():
         extras["runs_of_frames"] = dict(**fr, note="vs_frames_prefill_attn over 28 layers, same inputs every call (warm), "
                                                   "HIP events around 6 x 28 calls; includes the carrier gather launch and "
                                                   "the merge; catch-up mode, not the streamed metric")
+
+    if "question" in parts:
+        # the question after the video (Section 3.3, decoding phase): Tq text tokens over the rows that
+        # cfg3's stream leaves behind (200 + 4096 + 256), all 28 layers, every K/V row of the question kept
+        qs = {}
+        for Tq in (16, 64, 256):
+            L0 = P0 + 256
+            qq = draw(31, (Tq, s.n_q_heads, s.head_dim), 0.5, "bf16").to(dev)
+            kq = draw(32, (Tq, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(dev)
+            vq = draw(33, (Tq, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(dev)
+            hk, hv = cache_rows(34, s, L0, 0.5)
+            qcaches = []
+            for l in range(NL):
+                kc = torch.zeros((L0 + Tq, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+                vc = torch.zeros_like(kc)
+                kc[:L0].copy_(hk)
+                vc[:L0].copy_(hv)
+                qcaches.append(vs.Cache(kc, vc, L0))
+            wsq = vs.make_workspace(sh, Tq, L0 + Tq, 0, dev)
+            oq = torch.empty_like(qq)
+
+            def ask(n):
+                for _ in range(n):
+                    for l in range(NL):
+                        qcaches[l].len = L0
+                        vs.question_prefill_append(sh, qcaches[l], qq, kq, vq, oq, wsq)
+            ask(2)
+            a, b = event_pair()
+            torch.cuda.synchronize()
+            a.record()
+            ask(8)
+            b.record()
+            torch.cuda.synchronize()
+            tq = a.elapsed_time(b) * 1e-3 / 8
+            flq = prefill_flops(s, L0, Tq) * NL
+            qs[f"Tq={Tq}"] = dict(questions_per_s=1 / tq, tokens_per_s=Tq / tq, us_per_layer_call=tq * 1e6 / NL,
+                                  tflops=flq / tq / 1e12)
+            log(f"[bench] question of {Tq} tokens over {L0} rows: {tq * 1e3:.3f} ms for 28 layers "
+                f"({tq * 1e6 / NL:.1f} us per layer call), {Tq / tq:.0f} tok/s, {flq / tq / 1e12:.0f} TFLOP/s")
+            del qcaches, wsq
+        extras["question_prefill"] = dict(**qs, note="vs_question_prefill_append over 28 layers (attention + all Tq rows "
+                                                     "appended in the same launch), same inputs every call, HIP events "
+                                                     "around 8 x 28 calls")
 
     if "bank" in parts:
         # memory bank at capacity (Section 3.3, memory mechanism; the paper evaluates M = 64 and 128):

@@ -153,6 +153,23 @@ vs_status vs_carrier_compact_append_batched(const vs_shape *shape, int32_t n_cac
                                             void *hip_stream);
 
 /*
+ * The question after the video (Section 3.3, decoding phase: the question's tokens attend
+ * over the retained carrier rows before the answer is decoded; Section 3.4: text reaches the
+ * frames only through their carriers, which at inference are exactly the rows kept).
+ *   q, out [n_tokens][Hq][D]; k_t, v_t [n_tokens][Hkv][D].
+ * Token i attends over the cache's `len` rows and tokens 0..i of the question (Eq. 1), as in
+ * vs_frame_prefill_attn; then ALL n_tokens K/V rows are copied bit for bit to cache rows
+ * len .. len+n_tokens-1 and cache->len grows by n_tokens, so that vs_decode_attn continues on
+ * top of them.  The result is what n_tokens decoding steps, one token each, would give.
+ * One launch for bf16.  VS_ERR_CAPACITY, with nothing launched and len unchanged, if
+ * len + n_tokens > capacity; other errors as vs_frame_prefill_attn.
+ */
+vs_status vs_question_prefill_append(const vs_shape *shape, vs_cache *cache, const void *q,
+                                     const void *k_t, const void *v_t, int32_t n_tokens,
+                                     void *out, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream);
+
+/*
  * Decode attention (Section 3.3, decoding phase; Eq. 1), one query token for each
  * of n_streams independent streams of one layer.
  *   k_slab / v_slab [n_streams][capacity][Hkv][D], stream s valid up to lens[s].

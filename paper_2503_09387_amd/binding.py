@@ -12,7 +12,7 @@ EXPORTS = [
     "vs_status_string", "vs_workspace_bytes", "vs_workspace_init", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
     "vs_carrier_compact_append", "vs_carrier_compact_append_batched", "vs_decode_attn",
     "vs_carrier_mean_pool", "vs_set_tuning", "vs_memory_bank_push", "vs_carrier_evict_append",
-    "vs_frames_prefill_attn", "vs_probe_read_stream", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
+    "vs_frames_prefill_attn", "vs_probe_read_stream", "vs_question_prefill_append", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
 ]
 
 
@@ -90,6 +90,7 @@ def lib():
         L.vs_workspace_init.argtypes = [sp, vp, sz, vp]
         L.vs_frame_prefill_attn.argtypes = [sp, cp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.vs_frame_prefill_compact.argtypes = [sp, cp, vp, vp, vp, i32, vp, ip, vp, sz, vp]
+        L.vs_question_prefill_append.argtypes = [sp, cp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.vs_carrier_compact_append.argtypes = [sp, cp, vp, vp, i32, i32, ip, vp]
         L.vs_carrier_compact_append_batched.argtypes = [sp, i32, vp, vp, i32, ip, vp, vp, i32, i32, ip,
                                                         vp, sz, vp]
@@ -179,6 +180,14 @@ def frame_prefill_compact(shape, cache, q, k_f, v_f, out, workspace, stream=None
                                           _ptr(v_f), q.shape[0], _ptr(out), ctypes.byref(row), wp, wb,
                                           _stream(stream)), "vs_frame_prefill_compact")
     return row.value
+
+
+def question_prefill_append(shape, cache, q, k_t, v_t, out, workspace, stream=None):
+    """The question's tokens over the retained rows; all their K/V rows are appended."""
+    wp, wb = _ws(workspace)
+    _check(lib().vs_question_prefill_append(ctypes.byref(shape), ctypes.byref(cache.c), _ptr(q), _ptr(k_t), _ptr(v_t),
+                                            q.shape[0], _ptr(out), wp, wb, _stream(stream)),
+           "vs_question_prefill_append")
 
 
 def carrier_compact_append(shape, cache, k_f, v_f, carrier_index=None, stream=None):

@@ -58,16 +58,20 @@ constexpr int32_t kMaxStreams = 1024;
 
 size_t round256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// append: the run's last row goes to the cache (a frame and its carrier); append_all: every row
+// of the run does (a question, whose tokens all stay for the answer)
 vs_status prefill_common(const vs_shape* shape, vs_cache* cache, bool append, const void* q,
                          const void* k_f, const void* v_f, int32_t n_tokens, void* out,
                          int32_t* row_written, void* workspace, size_t workspace_bytes,
-                         void* hip_stream) {
+                         void* hip_stream, bool append_all = false) {
     vs_status st = check_shape(shape);
     if (st != VS_OK) return st;
     st = check_cache(cache, append);
     if (st != VS_OK) return st;
     if (!q || !k_f || !v_f || !out) return VS_ERR_NULL;
     if (n_tokens < 1 || n_tokens > kMaxTokens) return VS_ERR_SHAPE;
+    const int32_t n_kept = append ? (append_all ? n_tokens : 1) : 0;
+    if (cache->len > cache->capacity - n_kept) return VS_ERR_CAPACITY;
     if (!aligned16(q) || !aligned16(k_f) || !aligned16(v_f) || !aligned16(out)) return VS_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t rb = row_bytes(shape);
@@ -81,21 +85,22 @@ vs_status prefill_common(const vs_shape* shape, vs_cache* cache, bool append, co
         if (!aligned16(workspace)) return VS_ERR_ALIGN;
         char* wsb = static_cast<char*>(workspace);
         e = launch_prefill_mfma(*shape, cache->k, cache->v, cache->len, q, k_f, v_f, n_tokens, out,
-                                kdst, vdst, wsb + prefill_counter_offset(*shape), wsb + ctrl, stream);
+                                kdst, vdst, wsb + prefill_counter_offset(*shape), wsb + ctrl, stream, 1, append_all);
     } else {
         e = launch_prefill_simple(*shape, cache->k, cache->v, cache->len, q, k_f, v_f, n_tokens, out,
                                   stream);
         if (e == hipSuccess && append) {
+            // (the kept rows are contiguous in the run and in the cache: one block of n_kept rows,
+            // handed to the row copy as a single long row at the destination itself)
             LenTable t{};
-            t.v[0] = cache->len;
-            e = launch_append_rows(1, cache->k, cache->v, 0, &t, nullptr, k_f, v_f, 0,
-                                   (int64_t)(n_tokens - 1) * rb, (int32_t)rb, stream);
+            e = launch_append_rows(1, kdst, vdst, 0, &t, nullptr, k_f, v_f, 0,
+                                   (int64_t)(n_tokens - n_kept) * rb, (int32_t)(n_kept * rb), stream);
         }
     }
     if (e != hipSuccess) return VS_ERR_HIP;
     if (append) {
         if (row_written) *row_written = cache->len;
-        cache->len += 1;
+        cache->len += n_kept;
     }
     return VS_OK;
 }
@@ -168,6 +173,13 @@ vs_status vs_frame_prefill_compact(const vs_shape* shape, vs_cache* cache, const
                                    void* hip_stream) {
     return prefill_common(shape, cache, true, q, k_f, v_f, n_tokens, out, row_written, workspace,
                           workspace_bytes, hip_stream);
+}
+
+vs_status vs_question_prefill_append(const vs_shape* shape, vs_cache* cache, const void* q,
+                                     const void* k_t, const void* v_t, int32_t n_tokens, void* out,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return prefill_common(shape, cache, true, q, k_t, v_t, n_tokens, out, nullptr, workspace,
+                          workspace_bytes, hip_stream, true);
 }
 
 vs_status vs_carrier_compact_append(const vs_shape* shape, vs_cache* cache, const void* k_f,

@@ -43,10 +43,11 @@ hipError_t launch_decode_simple(const vs_shape& s, int32_t n_streams, const void
 size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens);
 // n_frames > 1: q, kf, vf, out hold a run of frames [n_frames][n_tokens][..] under the semantic-aware
 // mask; k_append_dst / v_append_dst (row `len` of the cache) then receive all their carriers.
+// append_all (single run only): every row of the run goes to the cache, not just the last.
 hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc, int32_t len,
                                const void* q, const void* kf, const void* vf, int32_t n_tokens,
                                void* out, void* k_append_dst, void* v_append_dst, void* counters,
-                               void* workspace, hipStream_t st, int32_t n_frames = 1);
+                               void* workspace, hipStream_t st, int32_t n_frames = 1, bool append_all = false);
 size_t prefill_frames_workspace_bytes(const vs_shape& s, int32_t n_frames, int32_t n_tokens, int32_t nsplit);
 int prefill_frames_splits(const vs_shape& s, int32_t n_frames, int32_t n_tokens, int32_t len);
 

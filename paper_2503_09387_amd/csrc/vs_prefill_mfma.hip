@@ -73,8 +73,9 @@ struct PrefillParams {
     // [nsplit*Hkv][row tiles][4 row groups of 32][4 dim blocks][2][64 lanes] x 8 bf16
     __bf16* part_o;
     float* part_ml;  // [nsplit*Hkv][m_pad][2]: reference (log2 units), row sum
-    __bf16* k_append_dst;
+    __bf16* k_append_dst;    // frame rows append_first .. T-1 are copied here (null: none)
     __bf16* v_append_dst;
+    int append_first;        // T - 1: the carrier alone; 0: every row of the run (a question)
     int L, T, G, Hq, Hkv;
     int M, m_pad, nsplit, n_row_tiles;
     float scale_log2e;
@@ -546,13 +547,16 @@ void prefill_mfma_kernel(PrefillParams p) {
 
     asm volatile("; pipeline registers free");  // marker for the listing check of the build
 
-    // fused carrier compaction: one workgroup copies the last frame row into the cache (no
-    // workgroup of this launch reads that row)
-    if (p.k_append_dst && wg_id == 0) {
-        const int n16 = kv_row_bytes / 16;  // 16-byte chunks per row
-        const uint4* ksrc = reinterpret_cast<const uint4*>(kf + (int64_t)(T - 1) * kv_row_bytes);
-        const uint4* vsrc = reinterpret_cast<const uint4*>(vf + (int64_t)(T - 1) * kv_row_bytes);
-        for (int ch = tid; ch < n16; ch += kGroupThreads * NKG) {
+    // fused compaction: the frame rows that stay (the carrier, or all rows of a question) are
+    // copied into the cache, 16 bytes per thread, the workgroups of the launch taking turns (the
+    // carrier's 1 KB is done by the first one alone; no workgroup of this launch reads the
+    // cache rows written here)
+    if (p.k_append_dst) {
+        const int n16 = (T - p.append_first) * (kv_row_bytes / 16);
+        const uint4* ksrc = reinterpret_cast<const uint4*>(kf + (int64_t)p.append_first * kv_row_bytes);
+        const uint4* vsrc = reinterpret_cast<const uint4*>(vf + (int64_t)p.append_first * kv_row_bytes);
+        const int n_thr = kGroupThreads * NKG, n_wgs = p.n_row_tiles * nsplit * HF;
+        for (int ch = wg_id * n_thr + tid; ch < n16; ch += n_wgs * n_thr) {
             reinterpret_cast<uint4*>(p.k_append_dst)[ch] = ksrc[ch];
             reinterpret_cast<uint4*>(p.v_append_dst)[ch] = vsrc[ch];
         }
@@ -980,7 +984,7 @@ __global__ __launch_bounds__(64) void gather_carriers_kernel(const uint4* __rest
 hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc, int32_t len,
                                const void* q, const void* kf, const void* vf, int32_t n_tokens,
                                void* out, void* k_append_dst, void* v_append_dst, void* counters,
-                               void* workspace, hipStream_t st, int32_t n_frames) {
+                               void* workspace, hipStream_t st, int32_t n_frames, bool append_all) {
     const Plan pl = make_plan(s, n_tokens, len, n_frames);
     PrefillParams p;
     p.kc = (const __bf16*)kc;
@@ -991,6 +995,7 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
     p.out = (__bf16*)out;
     p.k_append_dst = (__bf16*)k_append_dst;
     p.v_append_dst = (__bf16*)v_append_dst;
+    p.append_first = append_all ? 0 : n_tokens - 1;
     p.L = len;
     p.T = n_tokens;
     p.G = s.n_q_heads / s.n_kv_heads;

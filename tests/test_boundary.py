@@ -79,6 +79,22 @@ def test_prefill_argument_errors():
     assert _prefill(s, _cache(), ws=ODD) == 6
 
 
+def test_question_prefill_argument_errors_leave_len_untouched():
+    s = _shape()
+
+    def call(c, q=FAKE, kt=FAKE, vt=FAKE, n=4, out=FAKE, ws=FAKE, wsb=1 << 30):
+        return vs.lib().vs_question_prefill_append(ctypes.byref(s), ctypes.byref(c), q, kt, vt, n, out, ws, wsb, None)
+
+    c = _cache(cap=8, ln=5)
+    assert call(c, n=4) == 4 and c.len == 5                # 5 + 4 rows do not fit 8
+    assert call(_cache(cap=8, ln=8), n=1) == 4
+    assert call(c, q=None) == 1 and call(c, kt=None, n=3) == 1 and call(c, out=None, n=3) == 1
+    assert call(c, n=0) == 2 and call(c, n=5000) == 2
+    assert call(c, vt=ODD, n=3) == 6 and call(c, ws=None, n=3) == 5 and call(c, wsb=16, n=3) == 5
+    assert call(_cache(k=None, cap=8, ln=0), n=3) == 1     # room is needed, so the cache must exist
+    assert c.len == 5
+
+
 def test_append_argument_errors_leave_len_untouched():
     s = _shape()
     L = vs.lib()

@@ -381,6 +381,52 @@ def test_decode_fp32_path():
     check_close(out, ref, "f32", "fp32 decode")
 
 
+# ---------------------------------------------------------------------------- the question after the video
+@pytest.mark.parametrize("L,Tq,dtype,splits", [(4424, 32, "bf16", 0), (200, 7, "bf16", 0), (0, 19, "bf16", 0),
+                                                (1500, 130, "bf16", 3), (700, 1, "bf16", 0), (300, 600, "bf16", 0),
+                                                (150, 9, "f32", 0)])
+def test_question_prefill_keeps_all_rows_and_decoding_continues(L, Tq, dtype, splits):
+    """vs_question_prefill_append against the oracle's token-by-token evaluation: outputs, the Tq
+    rows appended bit for bit, the length; then one decoding step on top of them."""
+    s = QW if dtype == "bf16" else AttnShape(4, 2, 64, "f32")
+    dt = torch_dtype(dtype)
+    cap = L + Tq + 4
+    hk, hv = cache_rows(61, s, L, 0.5)
+    q, kt, vt = frame_inputs(61, s, Tq, 0.5, q_gain=4)
+    Kc, Vc = np.zeros((cap, s.n_kv_heads, s.head_dim)), np.zeros((cap, s.n_kv_heads, s.head_dim))
+    if L:
+        Kc[:L], Vc[:L] = to_f64(hk), to_f64(hv)
+    ref, n = oracle.query_prefill(to_f64(q), Kc, Vc, L, to_f64(kt), to_f64(vt), scale32(s))
+    assert n == L + Tq
+    k = torch.full((cap, s.n_kv_heads, s.head_dim), 7.0, dtype=dt, device=DEV)  # junk beyond len must not count
+    v = torch.full_like(k, -7.0)
+    if L:
+        k[:L].copy_(hk)
+        v[:L].copy_(hv)
+    cache = vs.Cache(k, v, L)
+    ws = workspace(s, Tq, cap, 1)
+    vs.set_tuning(vs.TUNE_PREFILL_SPLITS, splits)
+    out = torch.full(q.shape, float("nan"), dtype=dt, device=DEV)
+    vs.question_prefill_append(vs_shape(s), cache, q.to(DEV), kt.to(DEV), vt.to(DEV), out, ws)
+    torch.cuda.synchronize()
+    vs.set_tuning(vs.TUNE_PREFILL_SPLITS, 0)
+    check_close(out, ref, dtype, f"question L={L} Tq={Tq}")
+    assert cache.len == L + Tq
+    assert same_bits(cache.k[L:L + Tq], kt) and same_bits(cache.v[L:L + Tq], vt)
+    assert bool((cache.k[L + Tq:] == 7.0).all()) and bool((cache.v[L + Tq:] == -7.0).all())
+    if L:
+        assert same_bits(cache.k[:L], hk) and same_bits(cache.v[:L], hv)
+    # the answer's first token
+    qd, kn, vn = decode_step_inputs(62, s, 1, 0.5, step=0)
+    o_ref, n2 = oracle.decode(to_f64(qd[0]), Kc, Vc, n, to_f64(kn[0]), to_f64(vn[0]), scale32(s))
+    lens = lens_array([cache.len])
+    od = torch.empty((1, s.n_q_heads, s.head_dim), dtype=dt, device=DEV)
+    vs.decode_attn(vs_shape(s), k[None], v[None], lens, qd.to(DEV), kn.to(DEV), vn.to(DEV), od, ws)
+    torch.cuda.synchronize()
+    check_close(od[0], o_ref, dtype, f"decoding step after the question, L={L} Tq={Tq}")
+    assert lens[0] == n2 == L + Tq + 1
+
+
 # ---------------------------------------------------------------------------- pool, batched append
 @pytest.mark.parametrize("n,d,dtype", [(169, 3584, "bf16"), (49, 256, "f32"), (1, 8, "bf16"), (7, 1000, "f32")])
 def test_mean_pool(n, d, dtype):
