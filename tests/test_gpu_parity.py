@@ -381,6 +381,34 @@ def test_decode_fp32_path():
     check_close(out, ref, "f32", "fp32 decode")
 
 
+# ---------------------------------------------------------------------------- the largest sizes the boundary accepts
+def test_prefill_largest_run_and_head_ratio():
+    """4096 tokens in one run (the limit), 8 query heads per KV head (the limit): 32768 query rows
+    per KV head, 256 row tiles; sampled tokens against the oracle."""
+    s = AttnShape(16, 2, 128, "bf16")
+    L, T = 300, 4096
+    hk, hv = cache_rows(71, s, L, 0.5)
+    q, kf, vf = frame_inputs(71, s, T, 0.5, q_gain=2)
+    tokens = np.array([0, 1, 63, 64, 127, 128, 1000, 2047, 2048, 3333, 4094, 4095])
+    ref = oracle_prefill_rows(s, q, hk, hv, L, kf, vf, tokens)
+    out, cache, row = run_prefill(s, hk, hv, L, q, kf, vf, capacity=L + 1, fused=True)
+    check_close(out[torch.from_numpy(tokens).to(DEV)], ref, "bf16", "4096-token run, 8 heads per KV head")
+    assert row == L and cache.len == L + 1 and same_bits(cache.k[L], kf[T - 1]) and same_bits(cache.v[L], vf[T - 1])
+    assert bool(torch.isfinite(out.float()).all())
+    c = vs.Cache(cache.k, cache.v, L)
+    too_many = torch.empty((4097, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(vs.VSError):
+        vs.frame_prefill_attn(vs_shape(s), c, too_many, too_many, too_many, too_many, workspace(s, 4096, L + 1, 0))
+
+
+def test_decode_longest_stream_mix():
+    """64 streams in one launch (the most one launch takes), lengths from 1 row to 12000 rows."""
+    s = QW
+    lens0 = [12000, 1, 2, 31, 32, 33] + [int(x) for x in np.random.default_rng(9).integers(1, 3000, size=58)]
+    out, ref, _ = _decode_case(s, lens0, 12008, 27, gain=4)
+    check_close(out, ref, "bf16", "64 streams, up to 12000 rows")
+
+
 # ---------------------------------------------------------------------------- the question after the video
 @pytest.mark.parametrize("L,Tq,dtype,splits", [(4424, 32, "bf16", 0), (200, 7, "bf16", 0), (0, 19, "bf16", 0),
                                                 (1500, 130, "bf16", 3), (700, 1, "bf16", 0), (300, 600, "bf16", 0),
