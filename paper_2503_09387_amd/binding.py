@@ -291,6 +291,7 @@ def probe_read_stream(src, n_workgroups, sink, stream=None):
 
 
 TUNE_PREFILL_SPLITS, TUNE_PREFILL_KV_GROUPS, TUNE_DECODE_CHUNK_ROWS, TUNE_SKIP_MERGE, TUNE_PREFILL_MERGE = 0, 1, 2, 3, 4
+TUNE_TIMESTAMPS = 99
 
 
 def set_tuning(knob, value):

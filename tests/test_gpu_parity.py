@@ -381,6 +381,31 @@ def test_decode_fp32_path():
     check_close(out, ref, "f32", "fp32 decode")
 
 
+def test_prefill_timestamps_knob():
+    """VS_TUNE_TIMESTAMPS = 7: every workgroup of a single-frame bf16 prefill leaves four clock
+    readings (start, pipeline start, pipeline end, end) in the last MiB of the workspace; the
+    output is the same bits as without them."""
+    s, L, T = QW, 1500, 170
+    hk, hv = cache_rows(33, s, L, 0.5)
+    q, kf, vf = frame_inputs(33, s, T, 0.5)
+    plain, _, _ = run_prefill(s, hk, hv, L, q, kf, vf)
+    nbytes = vs.workspace_bytes(vs_shape(s), T, 0, 0)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+    vs.workspace_init(vs_shape(s), ws)
+    vs.set_tuning(vs.TUNE_TIMESTAMPS, 7)
+    try:
+        stamped, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
+    finally:
+        vs.set_tuning(vs.TUNE_TIMESTAMPS, 0)
+    assert same_bits(stamped, plain.cpu())
+    t = ws[nbytes - (1 << 20):].view(torch.int64).cpu().numpy().reshape(-1, 4)
+    used = t[t[:, 0] != 0]
+    assert 4 <= len(used) <= 4096, len(used)            # one record per workgroup of the launch
+    assert (np.diff(used, axis=1) >= 0).all(), "clock readings of a workgroup must not go backwards"
+    span = (used[:, 3].max() - used[:, 0].min()) / 100.0  # the clock counts at 100 MHz
+    assert 1.0 < span < 1000.0, f"launch spans {span} us"
+
+
 # ---------------------------------------------------------------------------- the largest sizes the boundary accepts
 def test_prefill_largest_run_and_head_ratio():
     """4096 tokens in one run (the limit), 8 query heads per KV head (the limit): 32768 query rows
