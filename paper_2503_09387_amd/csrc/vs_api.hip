@@ -53,6 +53,11 @@ vs_status check_cache(const vs_cache* c, bool need_room) {
     return VS_OK;
 }
 
+// A launch is checked with hipGetLastError(), which also reports an error that some earlier
+// call of this thread left behind (another library's probing, say).  Every entry point that
+// launches starts by dropping such a leftover, so that what it reports is its own.
+inline void forget_stale_hip_error() { (void)hipGetLastError(); }
+
 constexpr int32_t kMaxTokens = 4096;
 constexpr int32_t kMaxStreams = 1024;
 
@@ -64,6 +69,7 @@ vs_status prefill_common(const vs_shape* shape, vs_cache* cache, bool append, co
                          const void* k_f, const void* v_f, int32_t n_tokens, void* out,
                          int32_t* row_written, void* workspace, size_t workspace_bytes,
                          void* hip_stream, bool append_all = false) {
+    forget_stale_hip_error();
     vs_status st = check_shape(shape);
     if (st != VS_OK) return st;
     st = check_cache(cache, append);
@@ -143,6 +149,7 @@ size_t vs_workspace_bytes(const vs_shape* shape, int32_t max_q_tokens, int32_t m
 
 vs_status vs_workspace_init(const vs_shape* shape, void* workspace, size_t workspace_bytes,
                             void* hip_stream) {
+    forget_stale_hip_error();
     vs_status st = check_shape(shape);
     if (st != VS_OK) return st;
     if (!workspace) return VS_ERR_NULL;
@@ -185,6 +192,7 @@ vs_status vs_question_prefill_append(const vs_shape* shape, vs_cache* cache, con
 vs_status vs_carrier_compact_append(const vs_shape* shape, vs_cache* cache, const void* k_f,
                                     const void* v_f, int32_t n_tokens, int32_t carrier_index,
                                     int32_t* row_written, void* hip_stream) {
+    forget_stale_hip_error();
     vs_status st = check_shape(shape);
     if (st != VS_OK) return st;
     if (!k_f || !v_f) return VS_ERR_NULL;
@@ -210,6 +218,7 @@ vs_status vs_carrier_compact_append_batched(const vs_shape* shape, int32_t n_cac
                                             int32_t carrier_index, int32_t* rows_written,
                                             void* workspace, size_t workspace_bytes,
                                             void* hip_stream) {
+    forget_stale_hip_error();
     vs_status st = check_shape(shape);
     if (st != VS_OK) return st;
     if (!k_slab || !v_slab || !lens || !k_f || !v_f) return VS_ERR_NULL;
@@ -253,6 +262,7 @@ vs_status vs_decode_attn(const vs_shape* shape, int32_t n_streams, void* k_slab,
                          int32_t capacity, int32_t* lens, const void* q, const void* k_new,
                          const void* v_new, void* out, void* workspace, size_t workspace_bytes,
                          void* hip_stream) {
+    forget_stale_hip_error();
     vs_status st = check_shape(shape);
     if (st != VS_OK) return st;
     if (!k_slab || !v_slab || !lens || !q || !out) return VS_ERR_NULL;
@@ -333,6 +343,7 @@ size_t vs_frames_workspace_bytes(const vs_shape* shape, int32_t n_frames, int32_
 vs_status vs_frames_prefill_attn(const vs_shape* shape, vs_cache* cache, const void* q, const void* k_f,
                                  const void* v_f, int32_t n_frames, int32_t n_tokens, void* out,
                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+    forget_stale_hip_error();
     vs_status st = check_shape(shape);
     if (st != VS_OK) return st;
     if (shape->dtype != VS_BF16) return VS_ERR_UNSUPPORTED;
@@ -366,6 +377,7 @@ size_t vs_memory_bank_workspace_bytes(int32_t capacity) {
 
 vs_status vs_memory_bank_push(vs_bank* bank, const void* e_new, int32_t policy, int32_t* victim,
                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    forget_stale_hip_error();
     if (!bank || !e_new || !victim || !bank->e) return VS_ERR_NULL;
     if (bank->dtype != VS_F32 && bank->dtype != VS_BF16) return VS_ERR_UNSUPPORTED;
     const int64_t rb = (int64_t)bank->d * (bank->dtype == VS_F32 ? 4 : 2);
@@ -394,6 +406,7 @@ vs_status vs_memory_bank_push(vs_bank* bank, const void* e_new, int32_t policy, 
 vs_status vs_carrier_evict_append(const vs_shape* shape, int32_t n_layers, vs_cache* caches, int32_t first_row,
                                   int32_t bank_capacity, const void* k_rows, const void* v_rows,
                                   int64_t layer_stride_bytes, const int32_t* victim, void* hip_stream) {
+    forget_stale_hip_error();
     vs_status st = check_shape(shape);
     if (st != VS_OK) return st;
     if (!caches || !k_rows || !v_rows || !victim) return VS_ERR_NULL;
@@ -463,6 +476,7 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
 
 vs_status vs_carrier_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, void* c_out,
                                void* hip_stream) {
+    forget_stale_hip_error();
     if (!e || !c_out) return VS_ERR_NULL;
     if (dtype != VS_F32 && dtype != VS_BF16) return VS_ERR_UNSUPPORTED;
     if (n < 1 || d < 1) return VS_ERR_SHAPE;
@@ -474,6 +488,7 @@ vs_status vs_carrier_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtyp
 
 vs_status vs_probe_read_stream(const void* src, size_t bytes, int32_t n_workgroups, void* sink,
                                void* hip_stream) {
+    forget_stale_hip_error();
     if (!src || !sink) return VS_ERR_NULL;
     if (bytes == 0 || bytes % 16 != 0 || n_workgroups < 1 || n_workgroups > 65536) return VS_ERR_SHAPE;
     if (!aligned16(src)) return VS_ERR_ALIGN;

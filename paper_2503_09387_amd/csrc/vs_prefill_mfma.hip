@@ -904,8 +904,11 @@ Plan make_plan(const vs_shape& s, int n_tokens, int len, int n_frames) {
 
 template <int KVG>
 hipError_t launch_kvg(const PrefillParams& p, const Plan& pl, int n_kv_heads, hipStream_t st) {
-    static bool attr_set = false;  // dynamic LDS above 64 KB has to be allowed once per kernel
+    static bool attr_set_on[16] = {};  // dynamic LDS above 64 KB has to be allowed once per kernel and device
     constexpr int kLds = KVG * kGroupLds;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+    bool& attr_set = attr_set_on[dev];
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<KVG>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
