@@ -495,11 +495,27 @@ def test_mean_pool(n, d, dtype):
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-30)
 
 
-@pytest.mark.parametrize("n_caches", [28, 4096])
-def test_batched_compaction(n_caches):
+@pytest.mark.parametrize("n_caches,pinned", [(28, False), (4096, False), (4096, True), (50, True)])
+def test_batched_compaction(n_caches, pinned):
     s, T, cap = QW, 6, 5
     rng = np.random.default_rng(5)
     lens0 = rng.integers(0, cap, size=n_caches).tolist()
+    if pinned:  # lengths in a pinned host tensor, row indices into a caller's array
+        lens_t = torch.tensor(lens0, dtype=torch.int32).pin_memory()
+        ks = torch.zeros((n_caches, cap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+        vsl = torch.zeros_like(ks)
+        kf = draw(41, (n_caches, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
+        vf = draw(42, (n_caches, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
+        rows_c = (ctypes.c_int32 * n_caches)()
+        got = vs.carrier_compact_append_batched(vs_shape(s), ks, vsl, lens_t, kf.to(DEV), vf.to(DEV),
+                                                workspace=workspace(s, 0, 0, n_caches), rows_out=rows_c)
+        torch.cuda.synchronize()
+        assert got is rows_c and list(rows_c) == lens0 and lens_t.tolist() == [n + 1 for n in lens0]
+        idx = torch.tensor(lens0)
+        ar = torch.arange(n_caches)
+        assert same_bits(ks[ar, idx], kf[:, T - 1]) and same_bits(vsl[ar, idx], vf[:, T - 1])
+        assert int((ks != 0).any(dim=-1).any(dim=-1).sum()) == n_caches  # one row per cache, no other
+        return
     ks = torch.zeros((n_caches, cap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
     vsl = torch.zeros_like(ks)
     kf = draw(41, (n_caches, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
