@@ -143,7 +143,9 @@ vs_status vs_frame_prefill_compact(const vs_shape *shape, vs_cache *cache, const
  * carrier_index of run i goes to row lens[i] of cache i and lens[i] += 1.
  * rows_written (host, [n_caches]) may be NULL.  If any cache is full nothing is
  * done.  Needs a workspace (vs_workspace_bytes with n_streams = n_caches) when
- * n_caches > 64.
+ * n_caches > 64: the lengths (host memory, 1 <= n_caches <= 2^20) are then copied
+ * into it on the stream before the launch; from pinned host memory that copy is
+ * asynchronous, from pageable memory the call returns once it has been staged.
  */
 vs_status vs_carrier_compact_append_batched(const vs_shape *shape, int32_t n_caches, void *k_slab,
                                             void *v_slab, int32_t capacity, int32_t *lens,
