@@ -500,7 +500,7 @@ def main():
             vf = draw(6, (n_c, Tn, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(dev)
             w = vs.make_workspace(sh, 0, 0, n_c, dev)
             lens_t = torch.zeros(n_c, dtype=torch.int32).pin_memory()
-            rows_c = (ctypes.c_int32 * n_c)()
+            rows_c = torch.zeros(n_c, dtype=torch.int32).pin_memory()
             times = []
             for r in range(12):
                 lens_t.fill_(r % 3)
@@ -512,7 +512,8 @@ def main():
                 torch.cuda.synchronize()
                 if r >= 2:
                     times.append(a.elapsed_time(b) * 1e-3)
-            assert int(lens_t[0]) == 11 % 3 + 1 and rows_c[n_c - 1] == 11 % 3
+            assert int(lens_t[0]) == 11 % 3 + 1 and int(rows_c[n_c - 1]) == 11 % 3
+            assert bool((ks[:, 11 % 3] == kf[:, Tn - 1]).all())  # the rows went where the old lengths said
             moved = n_c * 2 * 2 * s.n_kv_heads * s.head_dim * 2  # read + write, K and V
             tb = float(np.median(times))
             batched[f"caches={n_c}"] = dict(us=tb * 1e6, mbytes_moved=moved / 1e6, gbs=moved / tb / 1e9,

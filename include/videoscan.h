@@ -144,8 +144,11 @@ vs_status vs_frame_prefill_compact(const vs_shape *shape, vs_cache *cache, const
  * rows_written (host, [n_caches]) may be NULL.  If any cache is full nothing is
  * done.  Needs a workspace (vs_workspace_bytes with n_streams = n_caches) when
  * n_caches > 64: the lengths (host memory, 1 <= n_caches <= 2^20) are then copied
- * into it on the stream before the launch; from pinned host memory that copy is
- * asynchronous, from pageable memory the call returns once it has been staged.
+ * into it on the stream before the launch.  The copy is taken from rows_written if
+ * that is given (it holds the old lengths, which is what the device needs; leave it
+ * alone until the stream has passed this call if it is pinned memory), else from lens;
+ * pinned lens without rows_written makes the call wait for the stream, because lens
+ * is incremented before the call returns.
  */
 vs_status vs_carrier_compact_append_batched(const vs_shape *shape, int32_t n_caches, void *k_slab,
                                             void *v_slab, int32_t capacity, int32_t *lens,

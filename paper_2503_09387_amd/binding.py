@@ -203,18 +203,23 @@ def carrier_compact_append_batched(shape, k_slab, v_slab, lens, k_f, v_f, carrie
                                    workspace=None, stream=None, rows_out=None):
     """lens: int32 [n_caches] in host memory, updated in place: a ctypes array, or a CPU int32
     torch tensor (pinned memory makes the copy of more than 64 lengths to the device
-    asynchronous).  Returns the rows written as a list, or fills rows_out (ctypes int32 array)
-    and returns it, which costs no Python work per cache."""
+    asynchronous).  Returns the rows written as a list, or fills rows_out (ctypes int32 array or
+    CPU int32 tensor; pinned, it is what the device copy is taken from, so leave it alone until
+    the stream has passed the call) and returns it, which costs no Python work per cache."""
     n_caches, capacity = k_slab.shape[0], k_slab.shape[1]
     n = k_f.shape[1]
     rows = rows_out if rows_out is not None else (ctypes.c_int32 * n_caches)()
+
+    def host_i32(t):
+        assert t.device.type == "cpu" and t.numel() == n_caches and t.element_size() == 4 and t.is_contiguous()
+        return ctypes.cast(t.data_ptr(), ctypes.POINTER(ctypes.c_int32))
     if hasattr(lens, "data_ptr"):
-        assert lens.device.type == "cpu" and lens.numel() == n_caches and lens.element_size() == 4 and lens.is_contiguous()
-        lens = ctypes.cast(lens.data_ptr(), ctypes.POINTER(ctypes.c_int32))
+        lens = host_i32(lens)
+    rows_arg = host_i32(rows) if hasattr(rows, "data_ptr") else rows
     wp, wb = _ws(workspace)
     _check(lib().vs_carrier_compact_append_batched(
         ctypes.byref(shape), n_caches, _ptr(k_slab), _ptr(v_slab), capacity, lens, _ptr(k_f), _ptr(v_f),
-        n, n - 1 if carrier_index is None else carrier_index, rows, wp, wb, _stream(stream)),
+        n, n - 1 if carrier_index is None else carrier_index, rows_arg, wp, wb, _stream(stream)),
         "vs_carrier_compact_append_batched")
     return rows if rows_out is not None else list(rows)
 

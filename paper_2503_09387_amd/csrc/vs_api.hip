@@ -242,13 +242,29 @@ vs_status vs_carrier_compact_append_batched(const vs_shape* shape, int32_t n_cac
         if (!workspace || workspace_bytes < ctrl + sizeof(int32_t) * (size_t)n_caches) return VS_ERR_WORKSPACE;
         if (!aligned16(workspace)) return VS_ERR_ALIGN;
         void* staged = static_cast<char*>(workspace) + ctrl;
-        // lens is pageable host memory: the runtime stages the copy before returning
-        e = hipMemcpyAsync(staged, lens, sizeof(int32_t) * (size_t)n_caches, hipMemcpyHostToDevice, stream);
+        // The device needs the lengths as they are now, and lens is incremented below.  From
+        // pageable memory the runtime has taken its copy when hipMemcpyAsync returns; from
+        // pinned memory it reads later, whenever the stream gets there.  So the copy is taken
+        // from rows_written when the caller gives one (filled here with the old lengths and
+        // not touched again), and otherwise, if lens turns out to be pinned, the stream is
+        // waited for before lens changes.
+        const int32_t* from = lens;
+        bool wait = false;
+        if (rows_written) {
+            for (int32_t i = 0; i < n_caches; ++i) rows_written[i] = lens[i];
+            from = rows_written;
+        } else {
+            hipPointerAttribute_t attr;
+            if (hipPointerGetAttributes(&attr, lens) == hipSuccess) wait = attr.type != hipMemoryTypeUnregistered;
+            else (void)hipGetLastError();  // ordinary pageable memory is unknown to the runtime
+        }
+        e = hipMemcpyAsync(staged, from, sizeof(int32_t) * (size_t)n_caches, hipMemcpyHostToDevice, stream);
         if (e == hipSuccess)
             e = launch_append_rows(n_caches, k_slab, v_slab, (int64_t)capacity * rb, nullptr,
                                    static_cast<const int32_t*>(staged), k_f, v_f,
                                    (int64_t)n_tokens * rb, (int64_t)carrier_index * rb, (int32_t)rb,
                                    stream);
+        if (e == hipSuccess && wait) e = hipStreamSynchronize(stream);
     }
     if (e != hipSuccess) return VS_ERR_HIP;
     for (int32_t i = 0; i < n_caches; ++i) {

@@ -495,7 +495,7 @@ def test_mean_pool(n, d, dtype):
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-30)
 
 
-@pytest.mark.parametrize("n_caches,pinned", [(28, False), (4096, False), (4096, True), (50, True)])
+@pytest.mark.parametrize("n_caches,pinned", [(28, False), (4096, False), (4095, True), (4096, True), (4097, True), (50, True)])
 def test_batched_compaction(n_caches, pinned):
     s, T, cap = QW, 6, 5
     rng = np.random.default_rng(5)
@@ -506,11 +506,14 @@ def test_batched_compaction(n_caches, pinned):
         vsl = torch.zeros_like(ks)
         kf = draw(41, (n_caches, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
         vf = draw(42, (n_caches, T, s.n_kv_heads, s.head_dim), 0.5, "bf16")
-        rows_c = (ctypes.c_int32 * n_caches)()
+        # rows into a pinned tensor (the device copy is taken from it), into a plain array, or
+        # nowhere (then the call waits for the stream, lens being pinned)
+        rows_c = [torch.zeros(n_caches, dtype=torch.int32).pin_memory(), (ctypes.c_int32 * n_caches)(), None][n_caches % 3]
         got = vs.carrier_compact_append_batched(vs_shape(s), ks, vsl, lens_t, kf.to(DEV), vf.to(DEV),
                                                 workspace=workspace(s, 0, 0, n_caches), rows_out=rows_c)
         torch.cuda.synchronize()
-        assert got is rows_c and list(rows_c) == lens0 and lens_t.tolist() == [n + 1 for n in lens0]
+        assert (got is rows_c if rows_c is not None else got == lens0) and lens_t.tolist() == [n + 1 for n in lens0]
+        assert rows_c is None or [int(x) for x in rows_c] == lens0
         idx = torch.tensor(lens0)
         ar = torch.arange(n_caches)
         assert same_bits(ks[ar, idx], kf[:, T - 1]) and same_bits(vsl[ar, idx], vf[:, T - 1])
