@@ -10,6 +10,7 @@ from .vs_oracle import (  # noqa: F401
     compact_append,
     decode,
     frame_prefill,
+    frame_qkv,
     frames_prefill,
     mean_pool,
     num_threads,

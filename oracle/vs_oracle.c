@@ -390,3 +390,34 @@ int vs_oracle_query_prefill(const double *Q, double *Kc, double *Vc, int64_t cap
     }
     return VSO_OK;
 }
+
+/*
+ * The frame's rows and their projections (Section 3.1: Q = X W_Q, K = X W_K,
+ * V = X W_V; Section 3.3: the carrier's input embedding is the mean of the
+ * frame's N token embeddings; Section 3.2: it is the frame's last token).
+ * X has N + 1 rows: E[0..N-1], then C = (1/N) sum_i E[i].  W holds one row of d
+ * weights per output feature (n_out of them: the caller stacks W_Q, W_K, W_V),
+ * so Y[t][n] = sum_k X[t][k] W[n][k], summed in index order.  Y [N+1][n_out].
+ */
+int vs_oracle_frame_qkv(const double *E, int64_t N, int64_t d, const double *W, int64_t n_out, double *Y) {
+    if (!E || !W || !Y || N < 1 || d < 1 || n_out < 1) return VSO_ERR_ARG;
+    double *c = (double *)malloc((size_t)d * sizeof(double));
+    if (!c) return VSO_ERR_NOMEM;
+    int rc = vs_oracle_mean_pool(E, N, d, c);
+    if (rc == VSO_OK) {
+#ifdef _OPENMP
+#pragma omp parallel for collapse(2) schedule(static)
+#endif
+        for (int64_t t = 0; t <= N; ++t) {
+            for (int64_t n = 0; n < n_out; ++n) {
+                const double *x = t < N ? E + (size_t)t * d : c;
+                const double *w = W + (size_t)n * d;
+                double s = 0.0;
+                for (int64_t k = 0; k < d; ++k) s += x[k] * w[k];
+                Y[(size_t)t * n_out + n] = s;
+            }
+        }
+    }
+    free(c);
+    return rc;
+}

@@ -41,6 +41,7 @@ def _lib():
         lib.vs_oracle_mean_pool.argtypes = [dp, i64, i64, dp]
         lib.vs_oracle_frames_prefill.argtypes = [dp, dp, dp, i64, dp, dp, i64, i64, i32, i32, i32, f64, dp]
         lib.vs_oracle_query_prefill.argtypes = [dp, dp, dp, i64, ip, dp, dp, i64, i32, i32, i32, f64, dp]
+        lib.vs_oracle_frame_qkv.argtypes = [dp, i64, i64, dp, i64, dp]
         lib.vs_oracle_bank_victim.argtypes = [dp, i64, i64, dp, i32, dp, ip]
         lib.vs_oracle_bank_apply.argtypes = [dp, i64, i64, i64, i64, i64, i64, dp, ip]
         _LIB = lib
@@ -215,3 +216,21 @@ def query_prefill(Q, Kc, Vc, length, Kt, Vt, scale):
     if rc:
         raise OracleError(rc, "query_prefill")
     return O, int(ln.value)
+
+
+def frame_qkv(E, W, n_q_heads, n_kv_heads, head_dim):
+    """The frame's N token embeddings E [N][d] plus the carrier (their mean, appended last)
+    projected with W [(Hq + 2 Hkv) D][d] (rows: the features of W_Q, then W_K, then W_V; Section
+    3.1).  Returns Q [N+1][Hq][D], K, V [N+1][Hkv][D]."""
+    E, W = _c(E), _c(W)
+    N, d = E.shape
+    n_out = (n_q_heads + 2 * n_kv_heads) * head_dim
+    assert W.shape == (n_out, d)
+    Y = np.empty((N + 1, n_out), dtype=np.float64)
+    rc = _lib().vs_oracle_frame_qkv(_p(E), N, d, _p(W), n_out, _p(Y))
+    if rc:
+        raise OracleError(rc, "frame_qkv")
+    nq, nk = n_q_heads * head_dim, n_kv_heads * head_dim
+    return (Y[:, :nq].reshape(N + 1, n_q_heads, head_dim).copy(),
+            Y[:, nq:nq + nk].reshape(N + 1, n_kv_heads, head_dim).copy(),
+            Y[:, nq + nk:].reshape(N + 1, n_kv_heads, head_dim).copy())

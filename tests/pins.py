@@ -545,6 +545,52 @@ def pin_question_after_the_video(impl):
         raise AssertionError("a question that does not fit must be refused")
 
 
+def pin_frame_rows_and_their_projections(impl):
+    """Section 3.1 (Q = X W_Q, K = X W_K, V = X W_V) on the frame's rows, the carrier = mean of the
+    token embeddings appended last (Sections 3.2, 3.3)."""
+    r = _rng(67)
+    N, d, Hq, Hkv, D = 5, 7, 4, 2, 3
+    n_out = (Hq + 2 * Hkv) * D
+    E, W = r.normal(size=(N, d)), r.normal(size=(n_out, d))
+    Q, K, V = impl.frame_qkv(E, W, Hq, Hkv, D)
+    assert Q.shape == (N + 1, Hq, D) and K.shape == (N + 1, Hkv, D) and V.shape == K.shape
+    Y = np.concatenate([Q.reshape(N + 1, -1), K.reshape(N + 1, -1), V.reshape(N + 1, -1)], axis=1)
+    # brute force, every entry: feature n of row t is the dot product of X[t] with W's row n
+    X = [list(E[t]) for t in range(N)] + [[math.fsum(E[:, k]) / N for k in range(d)]]
+    for t in range(N + 1):
+        for n in range(n_out):
+            assert abs(Y[t, n] - math.fsum(X[t][k] * W[n, k] for k in range(d))) < 1e-13, (t, n)
+    # a projection is linear: the carrier's Q/K/V are the means of the tokens' Q/K/V
+    _close(Y[N], Y[:N].mean(axis=0), 1e-13, "carrier row vs mean of the projected tokens")
+    # weights that pick single input features (not symmetric): outputs are copies of those features,
+    # so rows, features and the carrier's place are all visible
+    d2, Hq2, Hkv2, D2 = 8, 2, 1, 2          # n_out = 8 = d2
+    perm = [3, 0, 7, 1, 6, 2, 5, 4]
+    P = np.zeros((8, d2))
+    for n, k in enumerate(perm):
+        P[n, k] = 1.0
+    E2 = r.normal(size=(4, d2))
+    Q2, K2, V2 = impl.frame_qkv(E2, P, Hq2, Hkv2, D2)
+    X2 = np.concatenate([E2, E2.mean(axis=0, keepdims=True)])
+    _close(Q2.reshape(5, 4), X2[:, perm[:4]], 1e-15, "Q picks features 3, 0, 7, 1")
+    _close(K2.reshape(5, 2), X2[:, perm[4:6]], 1e-15, "K picks features 6, 2")
+    _close(V2.reshape(5, 2), X2[:, perm[6:]], 1e-15, "V picks features 5, 4")
+    # a single token: the carrier equals it
+    Q1, K1, V1 = impl.frame_qkv(E[:1], W, Hq, Hkv, D)
+    assert np.array_equal(Q1[0], Q1[1]) and np.array_equal(V1[0], V1[1])
+    # what comes out is what the frame prefill takes: attention of the carrier over the frame,
+    # worked out from E and W alone
+    O = impl.frame_prefill(Q, None, None, K, V, 0.7)
+    h, g = 3, 1
+    qc = [math.fsum(X[N][k] * W[h * D + j, k] for k in range(d)) for j in range(D)]
+    keys = [[math.fsum(X[t][k] * W[Hq * D + g * D + j, k] for k in range(d)) for j in range(D)] for t in range(N + 1)]
+    vals = [[math.fsum(X[t][k] * W[(Hq + Hkv) * D + g * D + j, k] for k in range(d)) for j in range(D)] for t in range(N + 1)]
+    z = [0.7 * math.fsum(a * b for a, b in zip(qc, kk)) for kk in keys]
+    w = [math.exp(x - max(z)) for x in z]
+    want = [math.fsum(w[t] * vals[t][j] for t in range(N + 1)) / math.fsum(w) for j in range(D)]
+    _close(O[N, h], np.array(want), 1e-12, "carrier's attention from E and W")
+
+
 ALL_PINS = [
     pin_golden_rational,
     pin_uniform_scores_mean_of_visible,
@@ -565,4 +611,5 @@ ALL_PINS = [
     pin_memory_bank,
     pin_frames_with_semantic_mask,
     pin_question_after_the_video,
+    pin_frame_rows_and_their_projections,
 ]

@@ -108,6 +108,28 @@ class NumpyImpl:
             Kc[row], Vc[row] = Kt[j], Vt[j]
         return O, length + (len(keep) if self.bug != "question_length_plus_one" else 1)
 
+    def frame_qkv(self, E, W, n_q_heads, n_kv_heads, head_dim):
+        E, W = np.asarray(E, dtype=np.float64), np.asarray(W, dtype=np.float64)
+        N = E.shape[0]
+        c = E.sum(axis=0) if self.bug == "proj_carrier_is_sum" else E.mean(axis=0)
+        if self.bug == "proj_carrier_is_last_token":
+            c = E[-1]
+        X = np.concatenate([c[None], E]) if self.bug == "proj_carrier_first" else np.concatenate([E, c[None]])
+        if self.bug == "proj_weights_transposed" and W.shape[0] == W.shape[1]:
+            Y = X @ W
+        elif self.bug == "proj_weights_transposed":
+            Y = X @ W.T.reshape(W.shape).T   # the same numbers read in the other order
+        else:
+            Y = X @ W.T
+        nq, nk = n_q_heads * head_dim, n_kv_heads * head_dim
+        parts = [Y[:, :nq], Y[:, nq:nq + nk], Y[:, nq + nk:]]
+        if self.bug == "proj_k_and_v_swapped":
+            parts[1], parts[2] = parts[2], parts[1]
+        if self.bug == "proj_heads_interleaved":
+            parts[0] = parts[0].reshape(N + 1, head_dim, n_q_heads).transpose(0, 2, 1).reshape(N + 1, nq)
+        return (parts[0].reshape(N + 1, n_q_heads, head_dim).copy(), parts[1].reshape(N + 1, n_kv_heads, head_dim).copy(),
+                parts[2].reshape(N + 1, n_kv_heads, head_dim).copy())
+
     def mean_pool(self, E):
         E = np.asarray(E, dtype=np.float64)
         if self.bug == "pool_sum":
@@ -194,7 +216,9 @@ BUGS = ["gqa_interleaved", "scores_from_v", "no_scale", "scale_squared", "no_nor
         "bank_drops_newer", "bank_overwrites_victim", "bank_new_row_off_by_one",
         "run_carrier_is_first_token", "run_sees_own_future", "run_no_semantic_mask", "run_no_earlier_carriers",
         "run_sees_later_carriers", "question_rows_off_by_one", "question_keeps_last_token_only",
-        "question_not_causal", "question_blind_to_itself", "question_length_plus_one", "question_no_capacity_check"]
+        "question_not_causal", "question_blind_to_itself", "question_length_plus_one", "question_no_capacity_check",
+        "proj_carrier_is_sum", "proj_carrier_is_last_token", "proj_carrier_first", "proj_weights_transposed",
+        "proj_k_and_v_swapped", "proj_heads_interleaved"]
 
 
 def _failures(impl):
