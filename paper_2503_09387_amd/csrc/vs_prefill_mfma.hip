@@ -927,6 +927,8 @@ hipError_t launch_kvg(const PrefillParams& p, const Plan& pl, int n_kv_heads, hi
 
 }  // namespace
 
+int xcd_shift_of_device(int dev) { return dev >= 0 && dev < 16 ? g_xcd_shift[dev] : -1; }
+
 hipError_t probe_xcd_mapping(void* scratch, hipStream_t st) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);

@@ -480,6 +480,78 @@ def test_question_prefill_keeps_all_rows_and_decoding_continues(L, Tq, dtype, sp
     assert lens[0] == n2 == L + Tq + 1
 
 
+# ---------------------------------------------------------------------------- the frame's rows and their projections
+def _projection_case(s, N, d, seed, splits=0):
+    e = draw(seed, (N, d), 1.0, "bf16")
+    n_out = (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim
+    w = draw(seed + 1, (n_out, d), d ** -0.5, "bf16")
+    rq, rk, rv = oracle.frame_qkv(to_f64(e), to_f64(w), s.n_q_heads, s.n_kv_heads, s.head_dim)
+    sh = vs_shape(s)
+    ws = torch.empty(vs.frame_qkv_workspace_bytes(sh, d), dtype=torch.uint8, device=DEV)
+    vs.workspace_init(sh, ws)
+    q = torch.full((N + 1, s.n_q_heads, s.head_dim), float("nan"), dtype=torch.bfloat16, device=DEV)
+    k = torch.full((N + 1, s.n_kv_heads, s.head_dim), float("nan"), dtype=torch.bfloat16, device=DEV)
+    v = torch.full_like(k, float("nan"))
+    c = torch.full((d,), float("nan"), dtype=torch.bfloat16, device=DEV)
+    vs.set_tuning(vs.TUNE_QKV_SPLITS, splits)
+    outs = []
+    try:
+        for rep in range(3):  # the arrival counters return to zero
+            vs.frame_qkv_project(sh, e.to(DEV), w.to(DEV), q, k, v, ws, c_out=c)
+            torch.cuda.synchronize()
+            outs.append((q.clone(), k.clone(), v.clone()))
+    finally:
+        vs.set_tuning(vs.TUNE_QKV_SPLITS, 0)
+    for o in outs[1:]:
+        assert all(same_bits(a, b.cpu()) for a, b in zip(o, outs[0]))
+    return (q, k, v, c), (rq, rk, rv), (e, w)
+
+
+@pytest.mark.parametrize("N,d,heads,splits", [(169, 3584, (28, 4), 0), (169, 3584, (28, 4), 18), (169, 3584, (28, 4), 1),
+                                               (49, 256, (8, 2), 0), (1, 64, (8, 8), 0), (191, 448, (16, 2), 3),
+                                               (16, 128, (8, 1), 12), (100, 1024, (12, 4), 5)])
+def test_frame_projection_matches_oracle(N, d, heads, splits):
+    """vs_frame_qkv_project against the oracle: every row incl. the carrier's, Q/K/V in the layouts
+    the prefill takes; the carrier embedding equals vs_carrier_mean_pool bit for bit."""
+    s = AttnShape(heads[0], heads[1], 128, "bf16")
+    (q, k, v, c), (rq, rk, rv), (e, w) = _projection_case(s, N, d, 500 + N, splits)
+    check_close(q, rq, "bf16", f"Q N={N} d={d} splits={splits}")
+    check_close(k, rk, "bf16", f"K N={N} d={d} splits={splits}")
+    check_close(v, rv, "bf16", f"V N={N} d={d} splits={splits}")
+    pooled = torch.empty(d, dtype=torch.bfloat16, device=DEV)
+    vs.carrier_mean_pool(e.to(DEV), pooled, "bf16")
+    torch.cuda.synchronize()
+    assert same_bits(c, pooled.cpu())
+
+
+def test_frame_projection_split_counts_agree():
+    """Any number of slices of the input features, waiting or not: the slices are added in index
+    order, so only their number can change the rounding, and then only within fp32 noise."""
+    s = QW
+    base = None
+    for splits in (0, 8, 18, 4, 14, 2, 1):
+        (q, k, v, c), refs, _ = _projection_case(s, 169, 3584, 77, splits)
+        if splits in (0, 8, 18):   # the same 8 slices, merged by shares or by the last one alone
+            if base is None:
+                base = (q.clone(), k.clone(), v.clone())
+            assert all(same_bits(a, b.cpu()) for a, b in zip((q, k, v), base)), splits
+        else:
+            for a, b in zip((q, k, v), base):
+                assert (a.float() - b.float()).abs().max().item() <= 2 ** -7 * b.float().abs().max().item()
+
+
+def test_frame_projection_feeds_the_prefill():
+    """E and W in, attention out: projection, then prefill with compaction, against the oracle's
+    projection followed by its prefill (inputs of the second stage rounded to bf16 on both sides)."""
+    s, N, d, L = QW, 169, 3584, 300
+    (q, k, v, c), (rq, rk, rv), _ = _projection_case(s, N, d, 91)
+    hk, hv = cache_rows(92, s, L, 0.5)
+    out, cache, row = run_prefill(s, hk, hv, L, q.cpu(), k.cpu(), v.cpu(), capacity=L + 1, fused=True)
+    ref = oracle_prefill_rows(s, q.cpu(), hk, hv, L, k.cpu(), v.cpu())
+    check_close(out, ref, "bf16", "prefill on projected rows")
+    assert row == L and same_bits(cache.k[L], k[N].cpu()) and same_bits(cache.v[L], v[N].cpu())
+
+
 # ---------------------------------------------------------------------------- pool, batched append
 @pytest.mark.parametrize("n,d,dtype", [(169, 3584, "bf16"), (49, 256, "f32"), (1, 8, "bf16"), (7, 1000, "f32")])
 def test_mean_pool(n, d, dtype):
