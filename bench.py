@@ -89,7 +89,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--decode-steps", type=int, default=64)
     ap.add_argument("--parts", default="all",
-                    help="comma list of: stream,decode,cfg2,cfg5,compaction,bank,frames,question,cpu (default all); "
+                    help="comma list of: stream,decode,cfg2,cfg5,compaction,bank,frames,question,projection,cpu (default all); "
                          "calib = only a 1 GiB device copy, the known-size kernel that the HBM "
                          "counters of a rocprofv3 --pmc run are scaled by; readprobe = only a read-only "
                          "pass over as many bytes as a decode launch reads, the rate to hold the decode "
@@ -97,7 +97,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
-    parts = set("stream,decode,cfg2,cfg5,compaction,bank,frames,question,cpu".split(",")) if args.parts == "all" \
+    parts = set("stream,decode,cfg2,cfg5,compaction,bank,frames,question,projection,cpu".split(",")) if args.parts == "all" \
         else set(args.parts.split(","))
 
     import numpy as np
@@ -627,6 +627,41 @@ def main():
         extras["question_prefill"] = dict(**qs, note="vs_question_prefill_append over 28 layers (attention + all Tq rows "
                                                      "appended in the same launch), same inputs every call, HIP events "
                                                      "around 8 x 28 calls")
+
+    if "projection" in parts:
+        # the step upstream of the prefill (Sections 3.1 - 3.3): 169 token embeddings + their mean as
+        # carrier row, times [W_Q; W_K; W_V] of the 7B shape (d = 3584, 4608 output features), one
+        # weight matrix per layer so that nothing is served from a cache
+        d_model, n_out = 3584, (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim
+        wl = [draw(700 + l, (n_out, d_model), d_model ** -0.5, "bf16").to(dev) for l in range(4)]
+        wl = [wl[l % 4] if l < 4 else wl[l % 4].clone() for l in range(NL)]
+        el = [draw(750 + f, (T - 1, d_model), 1.0, "bf16").to(dev) for f in range(4)]
+        qo = torch.empty((T, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+        ko = torch.empty((T, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+        vo = torch.empty_like(ko)
+
+        def project(n):
+            for f in range(n):
+                for l in range(NL):
+                    vs.frame_qkv_project(sh, el[f % 4], wl[l], qo, ko, vo)
+        project(2)
+        a, b = event_pair()
+        torch.cuda.synchronize()
+        a.record()
+        project(16)
+        b.record()
+        torch.cuda.synchronize()
+        tpj = a.elapsed_time(b) * 1e-3 / (16 * NL)
+        bytes_pj = (n_out * d_model + (T - 1) * d_model + T * n_out) * 2
+        flops_pj = 2 * T * d_model * n_out
+        extras["frame_projection"] = dict(
+            us_per_launch=tpj * 1e6, algorithmic_mbytes=bytes_pj / 1e6, gbs=bytes_pj / tpj / 1e9,
+            frac_hbm=bytes_pj / tpj / 1e9 / PEAK_HBM_GBS, tflops=flops_pj / tpj / 1e12,
+            frac_mfma=flops_pj / tpj / 1e12 / PEAK_BF16_TFLOPS,
+            note="vs_frame_qkv_project, 28 distinct weight matrices in turn, HIP events around 16 x 28 launches back "
+                 "to back; bytes = weights + embeddings + outputs once")
+        log(f"[bench] frame projection (170 x 3584 -> 4608): {tpj * 1e6:.1f} us per launch = {bytes_pj / tpj / 1e9:.0f} GB/s "
+            f"({100 * bytes_pj / tpj / 1e9 / PEAK_HBM_GBS:.1f}% of HBM peak), {flops_pj / tpj / 1e12:.0f} TFLOP/s")
 
     if "bank" in parts:
         # memory bank at capacity (Section 3.3, memory mechanism; the paper evaluates M = 64 and 128):

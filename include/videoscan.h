@@ -282,10 +282,6 @@ vs_status vs_carrier_evict_append(const vs_shape *shape, int32_t n_layers, vs_ca
  *                             affected: there is no second kernel to leave out.)
  *   VS_TUNE_PREFILL_MERGE     2 = prefill always merges split results with the second kernel,
  *                             never inside the attention kernel
- *   VS_TUNE_QKV_SPLITS        slices of the input features per 144 output features in
- *                             vs_frame_qkv_project, 1..8 (0 = chosen per device); 11..18 = 1..8
- *                             slices with nobody waiting for the others: the last slice to
- *                             finish adds up all of them (exercises that path).  Same bits.
  *   VS_TUNE_TIMESTAMPS        7 = the bf16 prefill kernel of single-frame calls records four clock
  *                             readings per workgroup in the last MiB of the prefill part of the
  *                             workspace (vs_workspace_bytes always includes that MiB).
@@ -297,7 +293,6 @@ typedef enum {
     VS_TUNE_DECODE_CHUNK_ROWS = 2,
     VS_TUNE_SKIP_MERGE = 3,
     VS_TUNE_PREFILL_MERGE = 4,
-    VS_TUNE_QKV_SPLITS = 5,
     VS_TUNE_TIMESTAMPS = 99
 } vs_tune_knob;
 vs_status vs_set_tuning(int32_t knob, int32_t value);
@@ -313,17 +308,14 @@ vs_status vs_set_tuning(int32_t knob, int32_t value);
  *          to the tokens, row n_visual to the carrier; exactly what vs_frame_prefill_attn and
  *          vs_frame_prefill_compact take as q, k_f, v_f
  *   c_out  [d_model] or NULL: the carrier embedding itself, the same bits as vs_carrier_mean_pool
- * fp32 accumulation; the carrier embedding is rounded to bf16 before it is projected (it is a
- * row of X like the others); outputs rounded to bf16 once.  d_model a multiple of 64; at most
- * 9216 output features.  workspace: vs_frame_qkv_workspace_bytes, prepared by vs_workspace_init
- * with the same shape (the kernel counts arrivals in its control block and leaves them zero).
- * Position encoding is not part of the paper's statement and not applied.
+ * fp32 accumulation, outputs rounded to bf16 once.  The carrier's row is obtained as the mean of
+ * the token rows' fp32 sums (the projection is linear), i.e. the mean enters unrounded; c_out is
+ * that mean rounded to bf16.  d_model a multiple of 64.  No workspace.  Position encoding is not
+ * part of the paper's statement and not applied.
  */
-size_t vs_frame_qkv_workspace_bytes(const vs_shape *shape, int32_t d_model);
 vs_status vs_frame_qkv_project(const vs_shape *shape, const void *e, int32_t n_visual,
                                int32_t d_model, const void *w_qkv, void *q_out, void *k_out,
-                               void *v_out, void *c_out, void *workspace, size_t workspace_bytes,
-                               void *hip_stream);
+                               void *v_out, void *c_out, void *hip_stream);
 
 /*
  * Measurement aid, not part of the method: one read-only pass over `bytes` of device memory

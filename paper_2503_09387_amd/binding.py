@@ -12,7 +12,7 @@ EXPORTS = [
     "vs_status_string", "vs_workspace_bytes", "vs_workspace_init", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
     "vs_carrier_compact_append", "vs_carrier_compact_append_batched", "vs_decode_attn",
     "vs_carrier_mean_pool", "vs_set_tuning", "vs_memory_bank_push", "vs_carrier_evict_append",
-    "vs_frames_prefill_attn", "vs_probe_read_stream", "vs_question_prefill_append", "vs_frame_qkv_project", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes", "vs_frame_qkv_workspace_bytes",
+    "vs_frames_prefill_attn", "vs_probe_read_stream", "vs_question_prefill_append", "vs_frame_qkv_project", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
 ]
 
 
@@ -105,10 +105,8 @@ def lib():
         L.vs_frames_prefill_attn.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
         L.vs_frames_workspace_bytes.argtypes = [sp, i32, i32, i32]
         L.vs_frames_workspace_bytes.restype = sz
-        L.vs_frame_qkv_project.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
-        L.vs_frame_qkv_workspace_bytes.argtypes = [sp, i32]
-        L.vs_frame_qkv_workspace_bytes.restype = sz
-        for name in EXPORTS[2:-3]:
+        L.vs_frame_qkv_project.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        for name in EXPORTS[2:-2]:
             getattr(L, name).restype = ctypes.c_int
         _LIB = L
     return _LIB
@@ -193,15 +191,10 @@ def question_prefill_append(shape, cache, q, k_t, v_t, out, workspace, stream=No
            "vs_question_prefill_append")
 
 
-def frame_qkv_workspace_bytes(shape, d_model):
-    return lib().vs_frame_qkv_workspace_bytes(ctypes.byref(shape), int(d_model))
-
-
-def frame_qkv_project(shape, e, w_qkv, q_out, k_out, v_out, workspace, c_out=None, stream=None):
+def frame_qkv_project(shape, e, w_qkv, q_out, k_out, v_out, c_out=None, stream=None):
     """e [N][d] -> q_out [N+1][Hq][D], k_out / v_out [N+1][Hkv][D] (carrier = mean of e, last row)."""
-    wp, wb = _ws(workspace)
     _check(lib().vs_frame_qkv_project(ctypes.byref(shape), _ptr(e), e.shape[0], e.shape[1], _ptr(w_qkv), _ptr(q_out),
-                                      _ptr(k_out), _ptr(v_out), _ptr(c_out), wp, wb, _stream(stream)),
+                                      _ptr(k_out), _ptr(v_out), _ptr(c_out), _stream(stream)),
            "vs_frame_qkv_project")
 
 
@@ -317,7 +310,6 @@ def probe_read_stream(src, n_workgroups, sink, stream=None):
 
 
 TUNE_PREFILL_SPLITS, TUNE_PREFILL_KV_GROUPS, TUNE_DECODE_CHUNK_ROWS, TUNE_SKIP_MERGE, TUNE_PREFILL_MERGE = 0, 1, 2, 3, 4
-TUNE_QKV_SPLITS = 5
 TUNE_TIMESTAMPS = 99
 
 

@@ -19,8 +19,6 @@ int g_tune_decode_chunk_rows = 0;
 int g_tune_debug_mode = 0;
 int g_tune_skip_merge = 0;
 int g_tune_prefill_merge = 0;
-int g_tune_qkv_splits = 0;
-int g_tune_qkv_nowait = 0;
 }  // namespace vs
 
 namespace {
@@ -478,11 +476,6 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
             if (value > 1) return VS_ERR_SHAPE;
             g_tune_skip_merge = value;
             return VS_OK;
-        case VS_TUNE_QKV_SPLITS:
-            if (value > 18 || value == 9 || value == 10) return VS_ERR_SHAPE;
-            g_tune_qkv_nowait = value > 10;
-            g_tune_qkv_splits = value > 10 ? value - 10 : value;
-            return VS_OK;
         case VS_TUNE_PREFILL_MERGE:
             if (value != 0 && value != 2) return VS_ERR_SHAPE;
             g_tune_prefill_merge = value;
@@ -509,33 +502,19 @@ vs_status vs_carrier_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtyp
                ? VS_OK : VS_ERR_HIP;
 }
 
-size_t vs_frame_qkv_workspace_bytes(const vs_shape* shape, int32_t d_model) {
-    if (check_shape(shape) != VS_OK || shape->dtype != VS_BF16 || d_model < 64 || d_model % 64 != 0) return 0;
-    const int n_out = (shape->n_q_heads + 2 * shape->n_kv_heads) * shape->head_dim;
-    if ((n_out + 143) / 144 > kMaxQkvUnits) return 0;
-    return control_block_bytes(*shape) + frame_qkv_workspace_bytes(n_out, d_model);
-}
-
 vs_status vs_frame_qkv_project(const vs_shape* shape, const void* e, int32_t n_visual, int32_t d_model,
                                const void* w_qkv, void* q_out, void* k_out, void* v_out, void* c_out,
-                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+                               void* hip_stream) {
     forget_stale_hip_error();
     vs_status st = check_shape(shape);
     if (st != VS_OK) return st;
     if (shape->dtype != VS_BF16) return VS_ERR_UNSUPPORTED;
     if (!e || !w_qkv || !q_out || !k_out || !v_out) return VS_ERR_NULL;
     if (n_visual < 1 || n_visual > 191 || d_model < 64 || d_model % 64 != 0 || d_model > (1 << 20)) return VS_ERR_SHAPE;
-    const int n_out = (shape->n_q_heads + 2 * shape->n_kv_heads) * shape->head_dim;
-    if ((n_out + 143) / 144 > kMaxQkvUnits) return VS_ERR_SHAPE;
     if (!aligned16(e) || !aligned16(w_qkv) || !aligned16(q_out) || !aligned16(k_out) || !aligned16(v_out) ||
         !aligned16(c_out))
         return VS_ERR_ALIGN;
-    const size_t ctrl = control_block_bytes(*shape);
-    if (!workspace || workspace_bytes < ctrl + frame_qkv_workspace_bytes(n_out, d_model)) return VS_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return VS_ERR_ALIGN;
-    char* wsb = static_cast<char*>(workspace);
     return launch_frame_qkv(*shape, e, n_visual, d_model, w_qkv, q_out, k_out, v_out, c_out,
-                            wsb + qkv_counter_offset(*shape), wsb + ctrl,
                             static_cast<hipStream_t>(hip_stream)) == hipSuccess ? VS_OK : VS_ERR_HIP;
 }
 

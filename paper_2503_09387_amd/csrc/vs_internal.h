@@ -17,8 +17,6 @@ extern int g_tune_prefill_kv_groups;
 extern int g_tune_decode_chunk_rows;
 extern int g_tune_debug_mode;
 extern int g_tune_skip_merge;
-extern int g_tune_qkv_splits;   // 0 automatic, 1..8 slices of the input features in the projection kernel
-extern int g_tune_qkv_nowait;   // 1: in that kernel nobody waits for the other slices (the last one adds up everything)
 extern int g_tune_prefill_merge;  // 0 automatic, 2 always by the second kernel
 
 struct LenTable {
@@ -68,10 +66,6 @@ size_t control_block_bytes(const vs_shape& s);
 inline size_t prefill_counter_offset(const vs_shape& s) {
     return (size_t)kMaxStreamsPerLaunch * s.n_kv_heads * sizeof(unsigned int);
 }
-inline size_t qkv_counter_offset(const vs_shape& s) {
-    return (size_t)(kMaxStreamsPerLaunch + kMaxRowTiles) * s.n_kv_heads * sizeof(unsigned int);
-}
-constexpr int kMaxQkvUnits = 64;  // 144-feature units of the projection kernel: one counter each
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t st);
 // log2 of the number of XCDs workgroup ids are dealt to in turn on this device, -1 if unknown
 int xcd_shift_of_device(int dev);
@@ -99,10 +93,8 @@ hipError_t launch_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, 
 // measurement aid: a read-only pass over `bytes`
 hipError_t launch_read_probe(const void* src, size_t bytes, int32_t n_wg, void* sink, hipStream_t st);
 
-// frame rows and their Q/K/V projections (Sections 3.1 - 3.3); arrivals: kMaxQkvUnits zeroed words
-size_t frame_qkv_workspace_bytes(int n_out, int d);
+// frame rows and their Q/K/V projections (Sections 3.1 - 3.3)
 hipError_t launch_frame_qkv(const vs_shape& s, const void* e, int32_t n_visual, int32_t d, const void* w,
-                            void* q, void* k, void* v, void* c_out, void* arrivals, void* workspace,
-                            hipStream_t st);
+                            void* q, void* k, void* v, void* c_out, hipStream_t st);
 
 }  // namespace vs

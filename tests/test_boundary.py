@@ -170,20 +170,14 @@ def test_mean_pool_and_tuning_argument_errors():
 def test_frame_projection_argument_errors():
     s = _shape()
 
-    def call(e=FAKE, n=169, d=3584, w=FAKE, q=FAKE, k=FAKE, v=FAKE, c=None, ws=FAKE, wsb=1 << 30, shape=s):
-        return vs.lib().vs_frame_qkv_project(ctypes.byref(shape), e, n, d, w, q, k, v, c, ws, wsb, None)
+    def call(e=FAKE, n=169, d=3584, w=FAKE, q=FAKE, k=FAKE, v=FAKE, c=None, shape=s):
+        return vs.lib().vs_frame_qkv_project(ctypes.byref(shape), e, n, d, w, q, k, v, c, None)
 
     assert call(e=None) == 1 and call(w=None) == 1 and call(q=None) == 1 and call(v=None) == 1
     assert call(n=0) == 2 and call(n=192) == 2                 # the carrier makes it at most 192 rows
     assert call(d=0) == 2 and call(d=100) == 2                 # multiples of 64
     assert call(shape=_shape(hq=4, hkv=2, d=64, dt=vs.VS_F32)) == 3
-    assert call(e=ODD) == 6 and call(c=ODD) == 6 and call(ws=ODD) == 6
-    assert call(ws=None) == 5 and call(wsb=4096) == 5
-    need = vs.frame_qkv_workspace_bytes(s, 3584)
-    assert need > 8 * 32 * 4 * 27 * 1024 and call(wsb=need - 1) == 5
-    assert vs.frame_qkv_workspace_bytes(s, 100) == 0
-    assert vs.lib().vs_set_tuning(5, 9) == 2 and vs.lib().vs_set_tuning(5, 19) == 2
-    assert vs.lib().vs_set_tuning(5, 13) == 0 and vs.lib().vs_set_tuning(5, 0) == 0
+    assert call(e=ODD) == 6 and call(c=ODD) == 6 and call(k=ODD) == 6
 
 
 def test_read_probe_argument_errors():

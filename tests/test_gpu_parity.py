@@ -481,63 +481,44 @@ def test_question_prefill_keeps_all_rows_and_decoding_continues(L, Tq, dtype, sp
 
 
 # ---------------------------------------------------------------------------- the frame's rows and their projections
-def _projection_case(s, N, d, seed, splits=0):
+def _projection_case(s, N, d, seed):
     e = draw(seed, (N, d), 1.0, "bf16")
     n_out = (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim
     w = draw(seed + 1, (n_out, d), d ** -0.5, "bf16")
     rq, rk, rv = oracle.frame_qkv(to_f64(e), to_f64(w), s.n_q_heads, s.n_kv_heads, s.head_dim)
     sh = vs_shape(s)
-    ws = torch.empty(vs.frame_qkv_workspace_bytes(sh, d), dtype=torch.uint8, device=DEV)
-    vs.workspace_init(sh, ws)
     q = torch.full((N + 1, s.n_q_heads, s.head_dim), float("nan"), dtype=torch.bfloat16, device=DEV)
     k = torch.full((N + 1, s.n_kv_heads, s.head_dim), float("nan"), dtype=torch.bfloat16, device=DEV)
     v = torch.full_like(k, float("nan"))
     c = torch.full((d,), float("nan"), dtype=torch.bfloat16, device=DEV)
-    vs.set_tuning(vs.TUNE_QKV_SPLITS, splits)
     outs = []
-    try:
-        for rep in range(3):  # the arrival counters return to zero
-            vs.frame_qkv_project(sh, e.to(DEV), w.to(DEV), q, k, v, ws, c_out=c)
-            torch.cuda.synchronize()
-            outs.append((q.clone(), k.clone(), v.clone()))
-    finally:
-        vs.set_tuning(vs.TUNE_QKV_SPLITS, 0)
-    for o in outs[1:]:
-        assert all(same_bits(a, b.cpu()) for a, b in zip(o, outs[0]))
+    for rep in range(2):
+        vs.frame_qkv_project(sh, e.to(DEV), w.to(DEV), q, k, v, c_out=c)
+        torch.cuda.synchronize()
+        outs.append((q.clone(), k.clone(), v.clone()))
+    assert all(same_bits(a, b.cpu()) for a, b in zip(outs[1], outs[0])), "the same call twice gives the same bits"
     return (q, k, v, c), (rq, rk, rv), (e, w)
 
 
-@pytest.mark.parametrize("N,d,heads,splits", [(169, 3584, (28, 4), 0), (169, 3584, (28, 4), 18), (169, 3584, (28, 4), 1),
-                                               (49, 256, (8, 2), 0), (1, 64, (8, 8), 0), (191, 448, (16, 2), 3),
-                                               (16, 128, (8, 1), 12), (100, 1024, (12, 4), 5)])
-def test_frame_projection_matches_oracle(N, d, heads, splits):
+@pytest.mark.parametrize("N,d,heads", [(169, 3584, (28, 4)), (49, 256, (8, 2)), (1, 64, (8, 8)), (191, 448, (16, 2)),
+                                        (16, 128, (8, 1)), (100, 1024, (12, 4)), (160, 64, (3, 1)), (17, 192, (7, 1))])
+def test_frame_projection_matches_oracle(N, d, heads):
     """vs_frame_qkv_project against the oracle: every row incl. the carrier's, Q/K/V in the layouts
     the prefill takes; the carrier embedding equals vs_carrier_mean_pool bit for bit."""
     s = AttnShape(heads[0], heads[1], 128, "bf16")
-    (q, k, v, c), (rq, rk, rv), (e, w) = _projection_case(s, N, d, 500 + N, splits)
-    check_close(q, rq, "bf16", f"Q N={N} d={d} splits={splits}")
-    check_close(k, rk, "bf16", f"K N={N} d={d} splits={splits}")
-    check_close(v, rv, "bf16", f"V N={N} d={d} splits={splits}")
+    (q, k, v, c), (rq, rk, rv), (e, w) = _projection_case(s, N, d, 500 + N)
+    check_close(q, rq, "bf16", f"Q N={N} d={d}")
+    check_close(k, rk, "bf16", f"K N={N} d={d}")
+    check_close(v, rv, "bf16", f"V N={N} d={d}")
     pooled = torch.empty(d, dtype=torch.bfloat16, device=DEV)
     vs.carrier_mean_pool(e.to(DEV), pooled, "bf16")
     torch.cuda.synchronize()
     assert same_bits(c, pooled.cpu())
-
-
-def test_frame_projection_split_counts_agree():
-    """Any number of slices of the input features, waiting or not: the slices are added in index
-    order, so only their number can change the rounding, and then only within fp32 noise."""
-    s = QW
-    base = None
-    for splits in (0, 8, 18, 4, 14, 2, 1):
-        (q, k, v, c), refs, _ = _projection_case(s, 169, 3584, 77, splits)
-        if splits in (0, 8, 18):   # the same 8 slices, merged by shares or by the last one alone
-            if base is None:
-                base = (q.clone(), k.clone(), v.clone())
-            assert all(same_bits(a, b.cpu()) for a, b in zip((q, k, v), base)), splits
-        else:
-            for a, b in zip((q, k, v), base):
-                assert (a.float() - b.float()).abs().max().item() <= 2 ** -7 * b.float().abs().max().item()
+    # without the embedding asked for, the same Q/K/V
+    q2, k2, v2 = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    vs.frame_qkv_project(vs_shape(s), e.to(DEV), w.to(DEV), q2, k2, v2)
+    torch.cuda.synchronize()
+    assert same_bits(q2, q.cpu()) and same_bits(k2, k.cpu()) and same_bits(v2, v.cpu())
 
 
 def test_frame_projection_feeds_the_prefill():
