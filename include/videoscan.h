@@ -55,7 +55,8 @@ typedef enum {
     VS_ERR_CAPACITY = 4,    /* append into a full cache, or len > capacity */
     VS_ERR_WORKSPACE = 5,   /* workspace missing or too small */
     VS_ERR_ALIGN = 6,       /* a device pointer is not 16-byte aligned */
-    VS_ERR_HIP = 7          /* the HIP runtime reported a launch failure */
+    VS_ERR_HIP = 7,         /* the HIP runtime reported a launch failure */
+    VS_ERR_PLACEMENT = 8    /* see vs_workspace_init: results of earlier prefill calls are in doubt */
 } vs_status;
 
 typedef enum { VS_F32 = 0, VS_BF16 = 1 } vs_dtype;
@@ -98,6 +99,21 @@ size_t vs_workspace_bytes(const vs_shape *shape, int32_t max_q_tokens, int32_t m
  * call.  A workspace is tied to the shape it was initialised with.
  * With the environment variable VS_DEBUG set, a HIP error behind VS_ERR_HIP from this call
  * is also printed on stderr as text.
+ *
+ * What the probe is for.  When a bf16 prefill call splits the keys of a row tile over several
+ * workgroups, the last of them to finish merges their partial results inside the same launch,
+ * through the L2 cache that the compute units of one XCD (accelerator die) share; the library
+ * therefore gives all those workgroups ids that the device deals to one XCD, which it learns
+ * from the probe (ids go to the XCDs in turn).  Every workgroup of every such launch checks that
+ * it really runs on the XCD the probe saw for its id.  If one does not (another partition mode,
+ * masked compute units), it sets a word of pinned host memory (64 bytes per device, allocated by
+ * the first vs_workspace_init on the device and kept until the process ends).  The next bf16
+ * prefill call on that device (vs_frame_prefill_attn, vs_frame_prefill_compact,
+ * vs_question_prefill_append, vs_frames_prefill_attn) then launches nothing and returns
+ * VS_ERR_PLACEMENT, once: the outputs of the bf16 prefill calls enqueued since the last one that
+ * returned VS_OK after a synchronisation are in doubt and should be repeated.  From then on the
+ * partial results are merged by a second kernel, which needs no such placement, until a later
+ * vs_workspace_init probes the device again.
  */
 vs_status vs_workspace_init(const vs_shape *shape, void *workspace, size_t workspace_bytes,
                             void *hip_stream);
@@ -142,13 +158,13 @@ vs_status vs_frame_prefill_compact(const vs_shape *shape, vs_cache *cache, const
  * frame runs in k_f / v_f [n_caches][n_tokens][Hkv][D].  For every i, row
  * carrier_index of run i goes to row lens[i] of cache i and lens[i] += 1.
  * rows_written (host, [n_caches]) may be NULL.  If any cache is full nothing is
- * done.  Needs a workspace (vs_workspace_bytes with n_streams = n_caches) when
- * n_caches > 64: the lengths (host memory, 1 <= n_caches <= 2^20) are then copied
- * into it on the stream before the launch.  The copy is taken from rows_written if
- * that is given (it holds the old lengths, which is what the device needs; leave it
- * alone until the stream has passed this call if it is pinned memory), else from lens;
- * pinned lens without rows_written makes the call wait for the stream, because lens
- * is incremented before the call returns.
+ * done.  With n_caches > 64 (at most 2^20) the kernel reads the old lengths from memory: from
+ * rows_written if that is given (it is filled with them before the launch), else from lens.
+ * If that array is pinned host memory the kernel reads it in place, so leave rows_written
+ * alone until the stream has passed this call; with pinned lens and no rows_written the call
+ * waits for the stream, because lens is incremented before the call returns.  Pageable
+ * memory is copied into the workspace first (vs_workspace_bytes with n_streams = n_caches;
+ * no workspace is needed otherwise).
  */
 vs_status vs_carrier_compact_append_batched(const vs_shape *shape, int32_t n_caches, void *k_slab,
                                             void *v_slab, int32_t capacity, int32_t *lens,
@@ -182,6 +198,10 @@ vs_status vs_question_prefill_append(const vs_shape *shape, vs_cache *cache, con
  * If k_new is given, row lens[s] of stream s receives it first and lens[s] += 1;
  * the query then attends over all valid rows, the new one included.  Every stream
  * must end with at least one valid row.  1 <= n_streams <= 1024.
+ * Streams are launched in groups of 64.  Should a launch fail (VS_ERR_HIP) after earlier
+ * groups have been enqueued, lens has advanced for exactly those earlier groups, whose rows
+ * are written and whose outputs are valid; the failed group and the ones behind it are
+ * untouched, so the call can be repeated for them alone.
  */
 vs_status vs_decode_attn(const vs_shape *shape, int32_t n_streams, void *k_slab, void *v_slab,
                          int32_t capacity, int32_t *lens, const void *q, const void *k_new,
@@ -237,7 +257,7 @@ size_t vs_memory_bank_workspace_bytes(int32_t capacity);
  * the older carrier is dropped).  With room left the embedding is appended, bank->len
  * grows by one and -1 is written to *victim.  With the bank full the cosines of the
  * `capacity` adjacent pairs of the sequence e[0], .., e[capacity-1], e_new are taken
- * (fp32 sums; a vector of norm 0 has cosine 0), the pair (i, i+1) with the largest one
+ * (fp64 sums; a vector of norm 0 has cosine 0), the pair (i, i+1) with the largest one
  * names the victim i (of equal cosines the smallest i; policy 1: the i with the largest
  * cosine to e_new instead), row i is removed, the rows behind it move up, e_new becomes the
  * last row, bank->len stays, and i is written to *victim.  `victim` is DEVICE memory (one
@@ -275,25 +295,17 @@ vs_status vs_carrier_evict_append(const vs_shape *shape, int32_t n_layers, vs_ca
  *   VS_TUNE_PREFILL_SPLITS    workgroups sharing one row tile's keys, 1..32
  *   VS_TUNE_PREFILL_KV_GROUPS  key groups (sets of 4 wavefronts) per prefill workgroup, 1 or 2
  *   VS_TUNE_DECODE_CHUNK_ROWS rows of a stream per decode workgroup share, a multiple of 32
- *   VS_TUNE_SKIP_MERGE        1 = do not launch the kernels that merge split results, so that
- *                             the attention kernels can be timed alone; outputs of calls whose
- *                             keys were split are then NOT written.  Measurement only.
- *                             (Prefill calls that merge inside the attention kernel are not
- *                             affected: there is no second kernel to leave out.)
  *   VS_TUNE_PREFILL_MERGE     2 = prefill always merges split results with the second kernel,
- *                             never inside the attention kernel
- *   VS_TUNE_TIMESTAMPS        7 = the bf16 prefill kernel of single-frame calls records four clock
- *                             readings per workgroup in the last MiB of the prefill part of the
- *                             workspace (vs_workspace_bytes always includes that MiB).
- *                             Measurement only.
+ *                             never inside the attention kernel; 3 = for tests of the placement
+ *                             guard (see vs_workspace_init): the kernels are told the probed XCD
+ *                             order rotated by one, so every workgroup reports itself misplaced
+ *                             while the results stay correct
  */
 typedef enum {
     VS_TUNE_PREFILL_SPLITS = 0,
     VS_TUNE_PREFILL_KV_GROUPS = 1,
     VS_TUNE_DECODE_CHUNK_ROWS = 2,
-    VS_TUNE_SKIP_MERGE = 3,
-    VS_TUNE_PREFILL_MERGE = 4,
-    VS_TUNE_TIMESTAMPS = 99
+    VS_TUNE_PREFILL_MERGE = 4
 } vs_tune_knob;
 vs_status vs_set_tuning(int32_t knob, int32_t value);
 
@@ -316,18 +328,6 @@ vs_status vs_set_tuning(int32_t knob, int32_t value);
 vs_status vs_frame_qkv_project(const vs_shape *shape, const void *e, int32_t n_visual,
                                int32_t d_model, const void *w_qkv, void *q_out, void *k_out,
                                void *v_out, void *c_out, void *hip_stream);
-
-/*
- * Measurement aid, not part of the method: one read-only pass over `bytes` of device memory
- * at src (16-byte aligned, a multiple of 16 bytes) by n_workgroups workgroups (1..65536) of
- * 256 threads, each streaming an equal contiguous share with 16 loads of 16 bytes in flight
- * per thread.  Nothing is computed or kept; sink (device, >= 4 bytes) exists only so that
- * the loads are not dead code and is in practice never written.  Gives the rate at which a
- * kernel of this library's kind can read HBM on the device at hand, as a reference for the
- * decode kernel, which reads every K/V row once.
- */
-vs_status vs_probe_read_stream(const void *src, size_t bytes, int32_t n_workgroups, void *sink,
-                               void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -12,7 +12,7 @@ EXPORTS = [
     "vs_status_string", "vs_workspace_bytes", "vs_workspace_init", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
     "vs_carrier_compact_append", "vs_carrier_compact_append_batched", "vs_decode_attn",
     "vs_carrier_mean_pool", "vs_set_tuning", "vs_memory_bank_push", "vs_carrier_evict_append",
-    "vs_frames_prefill_attn", "vs_probe_read_stream", "vs_question_prefill_append", "vs_frame_qkv_project", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
+    "vs_frames_prefill_attn", "vs_question_prefill_append", "vs_frame_qkv_project", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
 ]
 
 
@@ -96,7 +96,6 @@ def lib():
                                                         vp, sz, vp]
         L.vs_decode_attn.argtypes = [sp, i32, vp, vp, i32, ip, vp, vp, vp, vp, vp, sz, vp]
         L.vs_carrier_mean_pool.argtypes = [vp, i32, i32, i32, vp, vp]
-        L.vs_probe_read_stream.argtypes = [vp, sz, i32, vp, vp]
         L.vs_set_tuning.argtypes = [i32, i32]
         L.vs_memory_bank_push.argtypes = [vp, vp, i32, vp, vp, sz, vp]
         L.vs_carrier_evict_append.argtypes = [sp, i32, vp, i32, i32, vp, vp, ctypes.c_int64, vp, vp]
@@ -303,14 +302,7 @@ def carrier_mean_pool(e, c_out, dtype, stream=None):
            "vs_carrier_mean_pool")
 
 
-def probe_read_stream(src, n_workgroups, sink, stream=None):
-    """Measurement aid: one read-only pass over the tensor src (contiguous)."""
-    _check(lib().vs_probe_read_stream(_ptr(src), ctypes.c_size_t(src.numel() * src.element_size()), int(n_workgroups),
-                                      _ptr(sink), _stream(stream)), "vs_probe_read_stream")
-
-
-TUNE_PREFILL_SPLITS, TUNE_PREFILL_KV_GROUPS, TUNE_DECODE_CHUNK_ROWS, TUNE_SKIP_MERGE, TUNE_PREFILL_MERGE = 0, 1, 2, 3, 4
-TUNE_TIMESTAMPS = 99
+TUNE_PREFILL_SPLITS, TUNE_PREFILL_KV_GROUPS, TUNE_DECODE_CHUNK_ROWS, TUNE_PREFILL_MERGE = 0, 1, 2, 4
 
 
 def set_tuning(knob, value):

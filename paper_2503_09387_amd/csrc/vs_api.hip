@@ -16,8 +16,6 @@ namespace vs {
 int g_tune_prefill_splits = 0;
 int g_tune_prefill_kv_groups = 0;
 int g_tune_decode_chunk_rows = 0;
-int g_tune_debug_mode = 0;
-int g_tune_skip_merge = 0;
 int g_tune_prefill_merge = 0;
 }  // namespace vs
 
@@ -58,6 +56,13 @@ vs_status check_cache(const vs_cache* c, bool need_room) {
 // launches starts by dropping such a leftover, so that what it reports is its own.
 inline void forget_stale_hip_error() { (void)hipGetLastError(); }
 
+// Has a workgroup of an earlier bf16 prefill launch on the current device found itself on an
+// XCD other than the one its unit's merge relies on?  (Reported once; see videoscan.h.)
+inline bool placement_fault_reported() {
+    int dev = 0;
+    return hipGetDevice(&dev) == hipSuccess && prefill_placement_fault(dev);
+}
+
 constexpr int32_t kMaxTokens = 4096;
 constexpr int32_t kMaxStreams = 1024;
 
@@ -89,6 +94,7 @@ vs_status prefill_common(const vs_shape* shape, vs_cache* cache, bool append, co
         const size_t need = ctrl + prefill_mfma_workspace_bytes(*shape, n_tokens);
         if (!workspace || workspace_bytes < need) return VS_ERR_WORKSPACE;
         if (!aligned16(workspace)) return VS_ERR_ALIGN;
+        if (placement_fault_reported()) return VS_ERR_PLACEMENT;
         char* wsb = static_cast<char*>(workspace);
         e = launch_prefill_mfma(*shape, cache->k, cache->v, cache->len, q, k_f, v_f, n_tokens, out,
                                 kdst, vdst, wsb + prefill_counter_offset(*shape), wsb + ctrl, stream, 1, append_all);
@@ -125,6 +131,7 @@ const char* vs_status_string(vs_status s) {
         case VS_ERR_WORKSPACE: return "workspace missing or too small";
         case VS_ERR_ALIGN: return "device pointer not 16-byte aligned";
         case VS_ERR_HIP: return "HIP launch failure";
+        case VS_ERR_PLACEMENT: return "an earlier prefill launch was not placed on the XCDs as probed";
     }
     return "unknown status";
 }
@@ -238,39 +245,47 @@ vs_status vs_carrier_compact_append_batched(const vs_shape* shape, int32_t n_cac
         e = launch_append_rows(n_caches, k_slab, v_slab, (int64_t)capacity * rb, &t, nullptr, k_f, v_f,
                                (int64_t)n_tokens * rb, (int64_t)carrier_index * rb, (int32_t)rb, stream);
     } else {
-        const size_t ctrl = control_block_bytes(*shape);
-        if (!workspace || workspace_bytes < ctrl + sizeof(int32_t) * (size_t)n_caches) return VS_ERR_WORKSPACE;
-        if (!aligned16(workspace)) return VS_ERR_ALIGN;
-        void* staged = static_cast<char*>(workspace) + ctrl;
-        // The device needs the lengths as they are now, and lens is incremented below.  From
-        // pageable memory the runtime has taken its copy when hipMemcpyAsync returns; from
-        // pinned memory it reads later, whenever the stream gets there.  So the copy is taken
-        // from rows_written when the caller gives one (filled here with the old lengths and
-        // not touched again), and otherwise, if lens turns out to be pinned, the stream is
-        // waited for before lens changes.
-        const int32_t* from = lens;
-        bool wait = false;
-        if (rows_written) {
-            for (int32_t i = 0; i < n_caches; ++i) rows_written[i] = lens[i];
-            from = rows_written;
+        // The device needs the lengths as they are now, and lens is incremented below.  The
+        // kernel takes them from rows_written when the caller gives one (filled here with the old
+        // lengths and not touched again), else from lens.  Pinned host memory is read by the
+        // kernel in place, 32 bytes per batch of rows, next to the rows' own loads; if that
+        // memory is lens itself, the stream is waited for before lens changes.  Pageable memory
+        // is staged in the workspace: the runtime has taken its copy when hipMemcpyAsync returns.
+        const int32_t* from = rows_written ? rows_written : lens;
+        const int32_t* on_device = nullptr;
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, from) == hipSuccess) {
+            if (attr.type == hipMemoryTypeHost && attr.devicePointer)
+                on_device = static_cast<const int32_t*>(attr.devicePointer);
         } else {
-            hipPointerAttribute_t attr;
-            if (hipPointerGetAttributes(&attr, lens) == hipSuccess) wait = attr.type != hipMemoryTypeUnregistered;
-            else (void)hipGetLastError();  // ordinary pageable memory is unknown to the runtime
+            (void)hipGetLastError();  // ordinary pageable memory is unknown to the runtime
         }
-        e = hipMemcpyAsync(staged, from, sizeof(int32_t) * (size_t)n_caches, hipMemcpyHostToDevice, stream);
+        bool wait = on_device && from == lens;
+        void* staged = nullptr;
+        if (!on_device) {
+            const size_t ctrl = control_block_bytes(*shape);
+            if (!workspace || workspace_bytes < ctrl + sizeof(int32_t) * (size_t)n_caches) return VS_ERR_WORKSPACE;
+            if (!aligned16(workspace)) return VS_ERR_ALIGN;
+            staged = static_cast<char*>(workspace) + ctrl;
+            if (!rows_written && hipPointerGetAttributes(&attr, lens) == hipSuccess) wait = attr.type != hipMemoryTypeUnregistered;
+            else (void)hipGetLastError();
+        }
+        if (rows_written)
+            for (int32_t i = 0; i < n_caches; ++i) rows_written[i] = lens[i];
+        e = hipSuccess;
+        if (staged) {
+            e = hipMemcpyAsync(staged, from, sizeof(int32_t) * (size_t)n_caches, hipMemcpyHostToDevice, stream);
+            on_device = static_cast<const int32_t*>(staged);
+        }
         if (e == hipSuccess)
-            e = launch_append_rows(n_caches, k_slab, v_slab, (int64_t)capacity * rb, nullptr,
-                                   static_cast<const int32_t*>(staged), k_f, v_f,
-                                   (int64_t)n_tokens * rb, (int64_t)carrier_index * rb, (int32_t)rb,
-                                   stream);
+            e = launch_append_rows(n_caches, k_slab, v_slab, (int64_t)capacity * rb, nullptr, on_device, k_f, v_f,
+                                   (int64_t)n_tokens * rb, (int64_t)carrier_index * rb, (int32_t)rb, stream);
         if (e == hipSuccess && wait) e = hipStreamSynchronize(stream);
     }
     if (e != hipSuccess) return VS_ERR_HIP;
-    for (int32_t i = 0; i < n_caches; ++i) {
-        if (rows_written) rows_written[i] = lens[i];
-        lens[i] += 1;
-    }
+    if (rows_written && n_caches <= kMaxStreamsPerLaunch)
+        for (int32_t i = 0; i < n_caches; ++i) rows_written[i] = lens[i];
+    for (int32_t i = 0; i < n_caches; ++i) lens[i] += 1;
     return VS_OK;
 }
 
@@ -326,15 +341,17 @@ vs_status vs_decode_attn(const vs_shape* shape, int32_t n_streams, void* k_slab,
                 for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i];
                 e = launch_append_rows(ns, ks, vs_, (int64_t)capacity * rb, &t, nullptr, kn, vn, rb, 0,
                                        (int32_t)rb, stream);
-                if (e != hipSuccess) return VS_ERR_HIP;
+                if (e != hipSuccess) return VS_ERR_HIP;  // (a row copy that did not start leaves nothing behind)
             }
             for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i] + add;
             e = launch_decode_simple(*shape, ns, ks, vs_, capacity, t, qs, os, stream);
         }
         if (e != hipSuccess) return VS_ERR_HIP;
+        // the lengths follow the launches group by group: after a failure in a later group, lens
+        // still says exactly which rows have been written
+        if (add)
+            for (int32_t i = 0; i < ns; ++i) lens[s0 + i] += 1;
     }
-    if (add)
-        for (int32_t s = 0; s < n_streams; ++s) lens[s] += 1;
     return VS_OK;
 }
 
@@ -374,6 +391,7 @@ vs_status vs_frames_prefill_attn(const vs_shape* shape, vs_cache* cache, const v
     const size_t need = ctrl + prefill_frames_workspace_bytes(*shape, n_frames, n_tokens, ns);
     if (!workspace || workspace_bytes < need) return VS_ERR_WORKSPACE;
     if (!aligned16(workspace)) return VS_ERR_ALIGN;
+    if (placement_fault_reported()) return VS_ERR_PLACEMENT;
     const int64_t rb = row_bytes(shape);
     char* wsb = static_cast<char*>(workspace);
     char* kdst = static_cast<char*>(cache->k) + (int64_t)cache->len * rb;
@@ -388,7 +406,7 @@ vs_status vs_frames_prefill_attn(const vs_shape* shape, vs_cache* cache, const v
 
 size_t vs_memory_bank_workspace_bytes(int32_t capacity) {
     if (capacity < 1 || capacity > 1024) return 0;
-    return round256(sizeof(float) * (size_t)capacity);
+    return round256(sizeof(double) * (size_t)capacity);
 }
 
 vs_status vs_memory_bank_push(vs_bank* bank, const void* e_new, int32_t policy, int32_t* victim,
@@ -412,7 +430,7 @@ vs_status vs_memory_bank_push(vs_bank* bank, const void* e_new, int32_t policy, 
         bank->len += 1;
         return VS_OK;
     }
-    float* cosines = static_cast<float*>(workspace);
+    double* cosines = static_cast<double*>(workspace);
     if (launch_bank_cosines(bank->e, e_new, bank->capacity, bank->d, bank->dtype, policy, cosines, st) != hipSuccess)
         return VS_ERR_HIP;
     return launch_bank_shift(1, &base, &row, rb, 0, bank->capacity, -1, cosines, victim, st) == hipSuccess
@@ -472,20 +490,12 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
             if (value % 32 != 0) return VS_ERR_SHAPE;
             g_tune_decode_chunk_rows = value;
             return VS_OK;
-        case VS_TUNE_SKIP_MERGE:
-            if (value > 1) return VS_ERR_SHAPE;
-            g_tune_skip_merge = value;
-            return VS_OK;
         case VS_TUNE_PREFILL_MERGE:
-            if (value != 0 && value != 2) return VS_ERR_SHAPE;
-            g_tune_prefill_merge = value;
+            if (value != 0 && value != 2 && value != 3) return VS_ERR_SHAPE;
+            g_tune_prefill_merge = value == 2 ? 2 : 0;
+            prefill_guard_test_mode(value == 3);
             return VS_OK;
         default: break;
-    }
-    if (knob == VS_TUNE_TIMESTAMPS) {
-        if (value != 0 && value != 7) return VS_ERR_SHAPE;
-        g_tune_debug_mode = value;
-        return VS_OK;
     }
     return VS_ERR_SHAPE;
 }
@@ -516,16 +526,6 @@ vs_status vs_frame_qkv_project(const vs_shape* shape, const void* e, int32_t n_v
         return VS_ERR_ALIGN;
     return launch_frame_qkv(*shape, e, n_visual, d_model, w_qkv, q_out, k_out, v_out, c_out,
                             static_cast<hipStream_t>(hip_stream)) == hipSuccess ? VS_OK : VS_ERR_HIP;
-}
-
-vs_status vs_probe_read_stream(const void* src, size_t bytes, int32_t n_workgroups, void* sink,
-                               void* hip_stream) {
-    forget_stale_hip_error();
-    if (!src || !sink) return VS_ERR_NULL;
-    if (bytes == 0 || bytes % 16 != 0 || n_workgroups < 1 || n_workgroups > 65536) return VS_ERR_SHAPE;
-    if (!aligned16(src)) return VS_ERR_ALIGN;
-    return launch_read_probe(src, bytes, n_workgroups, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess
-               ? VS_OK : VS_ERR_HIP;
 }
 
 }  // extern "C"

@@ -6,7 +6,9 @@
 // carrier is largest).  A vector of norm 0 has cosine 0 with everything.
 //
 // Two steps on the device, no host round trip in between:
-//   1. bank_cosine_kernel: one workgroup per pair, fp32 sums in a fixed order;
+//   1. bank_cosine_kernel: one workgroup per pair, fp64 sums in a fixed order (the products of
+//      bf16 or fp32 values are exact in fp64, so the cosines agree with a plain fp64 evaluation
+//      to ~1e-13 and the victim is the same unless two cosines are that close);
 //   2. bank_shift_kernel: every workgroup finds the victim from the M cosines (or reads the
 //      index an earlier call left in device memory), then a table of per-carrier rows (the
 //      embeddings, or one layer's K or V rows) drops that row, closes the gap and takes the
@@ -21,7 +23,7 @@ namespace {
 constexpr int kShiftThreads = 256;   // 4 rows of 64 16-byte pieces per step
 constexpr int kShiftSteps = 32;      // rows per thread and pass: 128 rows per pass
 
-__device__ __forceinline__ float block_sum(float x, float* lds) {  // fixed order, every thread gets the sum
+__device__ __forceinline__ double block_sum(double x, double* lds) {  // fixed order, every thread gets the sum
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
     const int w = threadIdx.x >> 6;
@@ -33,14 +35,14 @@ __device__ __forceinline__ float block_sum(float x, float* lds) {  // fixed orde
 
 template <typename T>
 __global__ __launch_bounds__(256) void bank_cosine_kernel(const T* __restrict__ e, const T* __restrict__ e_new,
-                                                          int M, int d, int policy, float* __restrict__ cosines) {
-    __shared__ float lds[4];
+                                                          int M, int d, int policy, double* __restrict__ cosines) {
+    __shared__ double lds[4];
     const int i = blockIdx.x;
     const T* a = e + (int64_t)i * d;
     const T* b = (policy == 1 || i + 1 == M) ? e_new : e + (int64_t)(i + 1) * d;
-    float ab = 0.f, aa = 0.f, bb = 0.f;
+    double ab = 0.0, aa = 0.0, bb = 0.0;
     for (int j = threadIdx.x; j < d; j += 256) {
-        const float x = to_f32(a[j]), y = to_f32(b[j]);
+        const double x = (double)to_f32(a[j]), y = (double)to_f32(b[j]);
         ab += x * y;
         aa += x * x;
         bb += y * y;
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(256) void bank_cosine_kernel(const T* __restrict__ 
     ab = block_sum(ab, lds);
     aa = block_sum(aa, lds);
     bb = block_sum(bb, lds);
-    if (threadIdx.x == 0) cosines[i] = (aa > 0.f && bb > 0.f) ? ab / (sqrtf(aa) * sqrtf(bb)) : 0.f;
+    if (threadIdx.x == 0) cosines[i] = (aa > 0.0 && bb > 0.0) ? ab / (sqrt(aa) * sqrt(bb)) : 0.0;
 }
 
 struct ShiftTables {
@@ -62,7 +64,7 @@ struct ShiftParams {
     int first;              // rows in front of the carriers
     int M;                  // carriers of a full bank
     int append_at;          // >= 0: room left, the new row goes to first + append_at; -1: drop the victim
-    const float* cosines;   // [M], or null: the victim's index is read from victim_io
+    const double* cosines;  // [M], or null: the victim's index is read from victim_io
     int* victim_io;         // device int (may be null when cosines are given)
 };
 
@@ -86,9 +88,9 @@ __global__ __launch_bounds__(kShiftThreads) void bank_shift_kernel(ShiftParams p
         // largest cosine, of equal ones the smallest index: every thread scans the same M values
         if (tid == 0) {
             int best = 0;
-            float best_cos = p.cosines[0];
+            double best_cos = p.cosines[0];
             for (int i = 1; i < p.M; ++i) {
-                const float c = p.cosines[i];
+                const double c = p.cosines[i];
                 if (c > best_cos) {
                     best = i;
                     best_cos = c;
@@ -127,7 +129,7 @@ __global__ __launch_bounds__(kShiftThreads) void bank_shift_kernel(ShiftParams p
 }  // namespace
 
 hipError_t launch_bank_cosines(const void* e, const void* e_new, int32_t M, int32_t d, int32_t dtype,
-                               int32_t policy, float* cosines, hipStream_t st) {
+                               int32_t policy, double* cosines, hipStream_t st) {
     if (dtype == VS_F32)
         bank_cosine_kernel<float><<<M, 256, 0, st>>>((const float*)e, (const float*)e_new, M, d, policy, cosines);
     else
@@ -136,7 +138,7 @@ hipError_t launch_bank_cosines(const void* e, const void* e_new, int32_t M, int3
 }
 
 hipError_t launch_bank_shift(int32_t n_tables, void* const* bases, const void* const* new_rows, int64_t row_bytes,
-                             int32_t first, int32_t M, int32_t append_at, const float* cosines, int32_t* victim_io,
+                             int32_t first, int32_t M, int32_t append_at, const double* cosines, int32_t* victim_io,
                              hipStream_t st) {
     for (int32_t t0 = 0; t0 < n_tables; t0 += kBankMaxTables) {
         const int32_t n = n_tables - t0 < kBankMaxTables ? n_tables - t0 : kBankMaxTables;

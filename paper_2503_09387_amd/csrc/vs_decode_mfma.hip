@@ -55,7 +55,7 @@ struct DecodeParams {
     float* part_ml;       // [slot][Hkv][nsub][G][2]: reference (log2 units), sum
     int64_t stream_stride;   // elements between streams in the slabs
     int n_streams, G, Hq, Hkv;
-    int nh, nsub;            // KV heads per workgroup (min(Hkv, 4)) and sub-ranges per share (4 / nh)
+    int nh, nsub;            // KV heads per workgroup (1, 2 or 4) and sub-ranges per share (4 / nh)
     int n_wg;                // workgroups along x
     int total_tiles;         // tile_prefix[n_streams]
     int share_q, share_r;    // total_tiles = n_wg * share_q + share_r: the first share_r workgroups take share_q + 1 tiles
@@ -372,13 +372,21 @@ __global__ __launch_bounds__(16 * kCombineGroups) void decode_combine_kernel(Dec
 
 constexpr int kDecodeMaxWorkgroups = 1024;
 
+// KV heads per workgroup (one wavefront each): the largest of 1, 2, 4 that divides Hkv; the
+// other wavefronts take sub-ranges of the share.  One rule for the sizing and the launch.
+int heads_per_workgroup(int n_kv_heads) { return n_kv_heads % 4 == 0 ? 4 : (n_kv_heads % 2 == 0 ? 2 : 1); }
+
+// Rows of partial results: a slot per (workgroup + stream of the segment), each with one row per
+// (KV head, sub-range, query head of the group).
+int64_t partial_rows(const vs_shape& s, int32_t n_streams) {
+    const int G = s.n_q_heads / s.n_kv_heads, nsub = kWaves / heads_per_workgroup(s.n_kv_heads);
+    return ((int64_t)kDecodeMaxWorkgroups + n_streams) * s.n_kv_heads * nsub * G;
+}
+
 }  // namespace
 
 size_t decode_mfma_workspace_bytes(const vs_shape& s, int32_t n_streams, int32_t /*max_rows*/) {
-    const int G = s.n_q_heads / s.n_kv_heads;
-    const int per_slot = s.n_kv_heads < kWaves ? kWaves : s.n_kv_heads;  // Hkv * nsub
-    const int64_t rows = ((int64_t)kDecodeMaxWorkgroups + n_streams) * per_slot * G;
-    return (size_t)(rows * (D * sizeof(__bf16) + 2 * sizeof(float)));
+    return (size_t)(partial_rows(s, n_streams) * (D * sizeof(__bf16) + 2 * sizeof(float)));
 }
 
 hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab, void* v_slab,
@@ -397,9 +405,7 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     p.G = s.n_q_heads / s.n_kv_heads;
     p.Hq = s.n_q_heads;
     p.Hkv = s.n_kv_heads;
-    p.nh = s.n_kv_heads < kWaves ? s.n_kv_heads : kWaves;
-    while (kWaves % p.nh != 0) --p.nh;  // 1, 2 or 4 heads per workgroup
-    if (s.n_kv_heads % p.nh != 0) p.nh = 1;
+    p.nh = heads_per_workgroup(s.n_kv_heads);
     p.nsub = kWaves / p.nh;
     p.scale_log2e = s.softmax_scale * kLog2e;
     p.lens = lens;
@@ -419,14 +425,15 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     p.n_wg = (int)n_wg;
     p.share_q = p.total_tiles / p.n_wg;
     p.share_r = p.total_tiles % p.n_wg;
-    const int per_slot = s.n_kv_heads < kWaves ? kWaves : s.n_kv_heads;
-    const int64_t rows = ((int64_t)kDecodeMaxWorkgroups + n_streams) * per_slot * p.G;
+    // the largest slot a wavefront can name is (n_wg - 1) + (n_streams - 1)
+    const int64_t rows = partial_rows(s, n_streams);
+    if ((int64_t)(p.n_wg + n_streams - 1) * s.n_kv_heads * p.nsub * p.G > rows) return hipErrorInvalidValue;
     p.part_ml = (float*)workspace;
     p.part_o = (__bf16*)(p.part_ml + rows * 2);
     const dim3 grid(p.n_wg, groups_y);
     decode_mfma_kernel<<<grid, kThreads, 0, st>>>(p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || g_tune_skip_merge) return e;
+    if (e != hipSuccess) return e;
     decode_combine_kernel<<<dim3(n_streams, s.n_q_heads), 16 * kCombineGroups, 0, st>>>(p);
     return hipGetLastError();
 }

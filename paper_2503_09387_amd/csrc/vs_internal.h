@@ -15,8 +15,6 @@ constexpr int kMaxGroup = 8;              // query heads per KV head
 extern int g_tune_prefill_splits;
 extern int g_tune_prefill_kv_groups;
 extern int g_tune_decode_chunk_rows;
-extern int g_tune_debug_mode;
-extern int g_tune_skip_merge;
 extern int g_tune_prefill_merge;  // 0 automatic, 2 always by the second kernel
 
 struct LenTable {
@@ -72,6 +70,10 @@ int xcd_shift_of_device(int dev);
 // Finds out once per device how workgroup ids are dealt to the XCDs (scratch: 256 bytes of device
 // memory; synchronises the stream the first time).
 hipError_t probe_xcd_mapping(void* scratch, hipStream_t st);
+// True once after a workgroup of an in-kernel-merge launch on this device has reported that it ran
+// on another XCD than probed; in-kernel merging is then off for the device until it is probed again.
+bool prefill_placement_fault(int dev);
+void prefill_guard_test_mode(int on);
 
 // row copies
 hipError_t launch_append_rows(int32_t n_caches, void* k_slab, void* v_slab, int64_t cache_stride_bytes,
@@ -82,16 +84,13 @@ hipError_t launch_append_rows(int32_t n_caches, void* k_slab, void* v_slab, int6
 // memory bank (Section 3.3, memory mechanism)
 constexpr int kBankMaxTables = 64;  // tables (layers x {K, V}) per launch: their pointers travel by value
 hipError_t launch_bank_cosines(const void* e, const void* e_new, int32_t M, int32_t d, int32_t dtype,
-                               int32_t policy, float* cosines, hipStream_t st);
+                               int32_t policy, double* cosines, hipStream_t st);
 hipError_t launch_bank_shift(int32_t n_tables, void* const* bases, const void* const* new_rows, int64_t row_bytes,
-                             int32_t first, int32_t M, int32_t append_at, const float* cosines, int32_t* victim_io,
+                             int32_t first, int32_t M, int32_t append_at, const double* cosines, int32_t* victim_io,
                              hipStream_t st);
 
 hipError_t launch_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, void* c_out,
                             hipStream_t st);
-
-// measurement aid: a read-only pass over `bytes`
-hipError_t launch_read_probe(const void* src, size_t bytes, int32_t n_wg, void* sink, hipStream_t st);
 
 // frame rows and their Q/K/V projections (Sections 3.1 - 3.3)
 hipError_t launch_frame_qkv(const vs_shape& s, const void* e, int32_t n_visual, int32_t d, const void* w,

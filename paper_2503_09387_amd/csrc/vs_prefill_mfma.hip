@@ -41,6 +41,7 @@
 #include <type_traits>
 
 #include "vs_internal.h"
+#include "vs_prefill_map.h"
 
 namespace vs {
 namespace {
@@ -86,13 +87,17 @@ struct PrefillParams {
     unsigned* arrivals;       // [Hkv][row tiles], zero between launches
     int xcd_shift;            // log2 of the number of XCDs workgroup ids are dealt to in turn
     int units_per_xcd;
+    // the guard of that placement: the XCC_ID the probe read for every residue of the id (4 bits
+    // each, residue 0 lowest), and the word in pinned host memory that a workgroup finding itself
+    // on another XCD sets (the host looks at it before every launch)
+    unsigned long long xcc_of_residue;
+    unsigned* misplaced;
     float inv_row_tiles;
     // A run of F frames (semantic-aware mask, Section 3.4): frame a has its own T rows of q, kf,
     // vf and out, and sees L + a retained rows (the carriers of the frames before it have been
     // appended to the cache ahead of this launch).  F = 1: the single frame.
     int F;
     float inv_frame_tiles;    // 1 / (F * row tiles)
-    unsigned long long* dbg;  // tuning aid: per-workgroup timestamps, normally null
 };
 
 typedef __attribute__((address_space(1))) const void* global_cptr;
@@ -110,16 +115,6 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
 // (dst is the same for the whole wavefront); completion is counted by vmcnt.
 __device__ __forceinline__ void load_to_lds16(const char* src, char* dst) {
     __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)dst, 16, 0, 0);
-}
-
-// floor(x / d) for 0 <= x < 2^22 and d >= 1, given inv_d = 1.0f / d: the float product is within
-// one of the quotient, two corrections make it exact.  (A 32-bit integer division costs some
-// twenty instructions here, and the prologue of this kernel is on the critical path.)
-__device__ __forceinline__ int div_small(int x, int d, float inv_d) {
-    int qd = (int)((float)x * inv_d);
-    if (qd * d > x) --qd;
-    if ((qd + 1) * d <= x) ++qd;
-    return qd;
 }
 
 // The matrix instructions are issued from hand-scheduled blocks of inline assembly
@@ -144,8 +139,7 @@ void prefill_mfma_kernel(PrefillParams p) {
     const int T = p.T, G = p.G, M = p.M, Hkv = p.Hkv, nsplit = p.nsplit;
     const float inv_G = p.inv_G, inv_nsplit = p.inv_nsplit;
     asm volatile("" : : "s"(kc), "s"(vc), "s"(kf), "s"(vf), "s"(qbase), "s"(L), "s"(T), "s"(G), "s"(M), "s"(Hkv),
-                 "s"(nsplit), "s"(inv_G), "s"(inv_nsplit), "s"(p.Hq), "s"(p.scale_log2e), "s"(p.dbg));
-    const unsigned long long t_start = p.dbg ? wall_clock64() : 0;
+                 "s"(nsplit), "s"(inv_G), "s"(inv_nsplit), "s"(p.Hq), "s"(p.scale_log2e));
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -159,11 +153,18 @@ void prefill_mfma_kernel(PrefillParams p) {
         // all splits of a unit take ids of one residue: XCD x holds units x*units_per_xcd ..
         // (consecutive units: the same KV head, whose K/V that L2 then holds once), each with
         // nsplit consecutive slots.
-        const int x = blockIdx.x & ((1 << p.xcd_shift) - 1), slot = blockIdx.x >> p.xcd_shift;
-        const int j = div_small(slot, nsplit, inv_nsplit);
-        const int unit = x * p.units_per_xcd + j;
-        if (j >= p.units_per_xcd || unit >= p.n_row_tiles * p.F * Hkv) return;  // spare ids
-        split = slot - j * nsplit;
+        const PrefillSlot at = prefill_slot_of_id(blockIdx.x, p.n_row_tiles * p.F * Hkv, p.units_per_xcd, nsplit,
+                                                  inv_nsplit, p.xcd_shift);
+        if (at.unit < 0) return;  // spare ids
+        // Guard: is this workgroup on the XCD that ids of its residue were seen on when the
+        // device was probed?  If not, the splits of its unit may not share an L2, and the merge
+        // below cannot be trusted: say so where the host sees it before its next launch.
+        unsigned xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        if ((xcc & 15u) != (unsigned)((p.xcc_of_residue >> (4 * at.xcd)) & 15u) && threadIdx.x == 0)
+            __hip_atomic_store(p.misplaced, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        const int unit = at.unit;
+        split = at.split;
         g = div_small(unit, p.n_row_tiles * p.F, p.inv_frame_tiles);
         const int ft = unit - g * p.n_row_tiles * p.F;
         frame = div_small(ft, p.n_row_tiles, p.inv_row_tiles);
@@ -444,7 +445,6 @@ void prefill_mfma_kernel(PrefillParams p) {
         commit(n, sum0_, sum1_, flag_);                                                              \
     } while (0)
 
-    const unsigned long long t_loop = p.dbg ? wall_clock64() : 0;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): K(0) and Q have landed
     __syncthreads();                     // K(0) of every group is staged
     if (n_my > 0) {
@@ -561,7 +561,6 @@ void prefill_mfma_kernel(PrefillParams p) {
             reinterpret_cast<uint4*>(p.v_append_dst)[ch] = vsrc[ch];
         }
     }
-    const unsigned long long t_epi = p.dbg ? wall_clock64() : 0;
     f32x16 o[2][4];
     asm volatile(VS_ASM_READ_O
                  : "={v[0:15]}"(o[0][0]), "={v[16:31]}"(o[0][1]), "={v[32:47]}"(o[0][2]), "={v[48:63]}"(o[0][3]),
@@ -762,10 +761,6 @@ void prefill_mfma_kernel(PrefillParams p) {
             }
         }
     }
-    if (p.dbg && tid == 0) {
-        unsigned long long* d = p.dbg + (size_t)wg_id * 4;
-        d[0] = t_start; d[1] = t_loop; d[2] = t_epi; d[3] = wall_clock64();
-    }
 }
 
 // Merge of the per-split partials: out = sum_s w_s l_s Ohat_s / sum_s w_s l_s with
@@ -849,8 +844,16 @@ struct Plan {
 
 // How this device deals workgroup ids to its XCDs, found once per device by xcd_probe_kernel:
 // log2 of the number of XCDs if ids go to them in turn (id mod count), -1 if not (or not yet
-// probed): then the splits are merged by the second kernel.
+// probed, or after a workgroup has reported that it ran elsewhere): then the splits are merged
+// by the second kernel.
 int g_xcd_shift[16] = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1};
+unsigned long long g_xcc_of_residue[16] = {};  // XCC_ID read for ids of residue r: bits 4r .. 4r+3
+// One word of pinned host memory per device (allocated by the probe, kept until the process
+// ends), set by any workgroup of an in-kernel-merge launch that finds itself on an XCD other
+// than the probed one.
+unsigned* g_misplaced[16] = {};      // as the host addresses it
+unsigned* g_misplaced_dev[16] = {};  // as the kernels address it
+int g_tune_guard_test = 0;  // tests: the next probe-derived table is handed to the kernels rotated by one XCD
 
 __global__ void xcd_probe_kernel(unsigned* out) {
     unsigned x;
@@ -898,7 +901,7 @@ Plan make_plan(const vs_shape& s, int n_tokens, int len, int n_frames) {
     pl.nsplit = ns;
     int dev = 0;
     pl.merge_inside = g_tune_prefill_merge != 2 && ns > 1 && ns <= 8 && pl.n_row_tiles * n_frames <= kMaxRowTiles &&
-                      hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && g_xcd_shift[dev] >= 0;
+                      hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && g_xcd_shift[dev] >= 0 && g_misplaced[dev];
     return pl;
 }
 
@@ -916,11 +919,11 @@ hipError_t launch_kvg(const PrefillParams& p, const Plan& pl, int n_kv_heads, hi
         attr_set = true;
     }
     // x runs fastest in dispatch order: all workgroups that read one K/V slice are neighbours
-    const dim3 grid = p.arrivals ? dim3((unsigned)((p.units_per_xcd * pl.nsplit) << p.xcd_shift))
+    const dim3 grid = p.arrivals ? dim3(prefill_grid_ids(pl.n_row_tiles * p.F * n_kv_heads, pl.nsplit, p.xcd_shift))
                                  : dim3(n_kv_heads, pl.nsplit, pl.n_row_tiles * p.F);
     prefill_mfma_kernel<KVG><<<grid, kGroupThreads * KVG, kLds, st>>>(p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.nsplit == 1 || g_tune_skip_merge || p.arrivals) return e;
+    if (e != hipSuccess || pl.nsplit == 1 || p.arrivals) return e;
     prefill_combine_kernel<<<dim3(pl.n_row_tiles * 4 * 4 * 2, n_kv_heads, p.F), 64, 0, st>>>(p);
     return hipGetLastError();
 }
@@ -946,6 +949,18 @@ hipError_t probe_xcd_mapping(void* scratch, hipStream_t st) {
         for (int i = 0; i < n && ok; ++i)
             for (int j = 0; j < i && ok; ++j) ok = ids[i] != ids[j];                // n different XCDs
         if (ok) {
+            unsigned long long table = 0;
+            for (int i = 0; i < n; ++i) table |= (unsigned long long)(ids[i] & 15u) << (4 * i);
+            if (!g_misplaced[dev]) {
+                void* flag = nullptr;
+                void* flag_dev = nullptr;
+                if ((e = hipHostMalloc(&flag, 64, hipHostMallocMapped)) != hipSuccess) return e;
+                *static_cast<unsigned*>(flag) = 0u;
+                if ((e = hipHostGetDevicePointer(&flag_dev, flag, 0)) != hipSuccess) return e;
+                g_misplaced[dev] = static_cast<unsigned*>(flag);
+                g_misplaced_dev[dev] = static_cast<unsigned*>(flag_dev);
+            }
+            g_xcc_of_residue[dev] = table;
             g_xcd_shift[dev] = shift;
             break;
         }
@@ -953,12 +968,22 @@ hipError_t probe_xcd_mapping(void* scratch, hipStream_t st) {
     return hipSuccess;
 }
 
+bool prefill_placement_fault(int dev) {
+    if (dev < 0 || dev >= 16 || !g_misplaced[dev]) return false;
+    if (*static_cast<volatile unsigned*>(g_misplaced[dev]) == 0u) return false;
+    g_xcd_shift[dev] = -1;  // from now on the second kernel merges
+    *static_cast<volatile unsigned*>(g_misplaced[dev]) = 0u;
+    return true;
+}
+
+void prefill_guard_test_mode(int on) { g_tune_guard_test = on; }
+
 size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens) {
     const int G = s.n_q_heads / s.n_kv_heads;
     const int64_t M = (int64_t)max_q_tokens * G;
     const int64_t m_pad = ((M + BM - 1) / BM) * BM;
     const int64_t slots = (int64_t)kMaxPrefillSplits * s.n_kv_heads * m_pad;
-    return (size_t)(slots * (D * sizeof(__bf16) + 2 * sizeof(float))) + (1u << 20);  // + tuning-aid block
+    return (size_t)(slots * (D * sizeof(__bf16) + 2 * sizeof(float)));
 }
 
 // Bytes the partial results of a run of n_frames frames can take (the plan's own choice of
@@ -1015,6 +1040,8 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
     p.inv_nsplit = 1.0f / (float)pl.nsplit;
     p.arrivals = nullptr;
     p.xcd_shift = p.units_per_xcd = 0;
+    p.xcc_of_residue = 0;
+    p.misplaced = nullptr;
     p.inv_row_tiles = 1.0f / (float)pl.n_row_tiles;
     p.F = n_frames;
     p.inv_frame_tiles = 1.0f / (float)(pl.n_row_tiles * n_frames);
@@ -1033,15 +1060,15 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
         (void)hipGetDevice(&dev);
         p.arrivals = (unsigned*)counters;
         p.xcd_shift = g_xcd_shift[dev];
-        const int units = pl.n_row_tiles * s.n_kv_heads * n_frames, n_xcd = 1 << p.xcd_shift;
-        p.units_per_xcd = (units + n_xcd - 1) / n_xcd;
+        p.units_per_xcd = prefill_units_per_xcd(pl.n_row_tiles * s.n_kv_heads * n_frames, p.xcd_shift);
+        p.xcc_of_residue = g_xcc_of_residue[dev];
+        if (g_tune_guard_test && p.xcd_shift > 0)  // entry r names the XCD of residue r + 1: every workgroup is "misplaced"
+            p.xcc_of_residue = (p.xcc_of_residue >> 4) | ((p.xcc_of_residue & 15ull) << (4 * ((1 << p.xcd_shift) - 1)));
+        p.misplaced = g_misplaced_dev[dev];
     }
     const int64_t slots = (int64_t)pl.nsplit * s.n_kv_heads * n_frames * pl.m_pad;
     p.part_ml = (float*)workspace;
     p.part_o = (__bf16*)(p.part_ml + slots * 2);
-    p.dbg = g_tune_debug_mode == 7 && n_frames == 1
-                ? (unsigned long long*)((char*)workspace + prefill_mfma_workspace_bytes(s, n_tokens) - (1 << 20))
-                : nullptr;
     return pl.kvg == 1 ? launch_kvg<1>(p, pl, s.n_kv_heads, st) : launch_kvg<2>(p, pl, s.n_kv_heads, st);
 }
 

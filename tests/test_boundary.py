@@ -151,6 +151,17 @@ def test_decode_argument_errors():
     assert list(ok_lens) == [5, 7] and list(empty) == [0, 3]
 
 
+def test_decode_workspace_holds_every_partial_slot():
+    """The decode workspace has a slot per (workgroup + stream of the segment), each with a row per
+    (KV head, sub-range of the share, query head of the group): 4 wavefronts per workgroup are 1, 2
+    or 4 KV heads, the rest sub-ranges.  Shapes whose KV head count is not a multiple of 4 used to
+    be sized short."""
+    for hq, hkv in ((28, 4), (6, 3), (12, 6), (8, 1), (16, 2), (7, 7), (40, 5), (64, 8)):
+        nh = 4 if hkv % 4 == 0 else 2 if hkv % 2 == 0 else 1
+        rows = (1024 + 16) * hkv * (4 // nh) * (hq // hkv)
+        assert vs.workspace_bytes(_shape(hq, hkv, 128, vs.VS_BF16), 0, 1000, 16) >= rows * (128 * 2 + 8), (hq, hkv)
+
+
 def test_mean_pool_and_tuning_argument_errors():
     L = vs.lib()
     assert L.vs_carrier_mean_pool(None, 4, 8, 0, FAKE, None) == 1
@@ -161,10 +172,10 @@ def test_mean_pool_and_tuning_argument_errors():
     assert L.vs_carrier_mean_pool(ODD, 4, 8, 0, FAKE, None) == 6
     assert L.vs_set_tuning(0, 33) == 2 and L.vs_set_tuning(1, 3) == 2
     assert L.vs_set_tuning(2, 100) == 2 and L.vs_set_tuning(9, 1) == 2
-    assert L.vs_set_tuning(3, 2) == 2 and L.vs_set_tuning(3, 1) == 0 and L.vs_set_tuning(3, 0) == 0
+    assert L.vs_set_tuning(3, 1) == 2 and L.vs_set_tuning(3, 0) == 2      # no such knob
     assert L.vs_set_tuning(0, 4) == 0 and L.vs_set_tuning(0, 0) == 0
     assert L.vs_set_tuning(4, 1) == 2 and L.vs_set_tuning(4, 2) == 0 and L.vs_set_tuning(4, 0) == 0
-    assert L.vs_set_tuning(99, 3) == 2 and L.vs_set_tuning(99, 0) == 0
+    assert L.vs_set_tuning(99, 7) == 2 and L.vs_set_tuning(99, 0) == 2    # no such knob
 
 
 def test_frame_projection_argument_errors():
@@ -180,21 +191,10 @@ def test_frame_projection_argument_errors():
     assert call(e=ODD) == 6 and call(c=ODD) == 6 and call(k=ODD) == 6
 
 
-def test_read_probe_argument_errors():
-    L = vs.lib()
-    assert L.vs_probe_read_stream(None, 1024, 8, FAKE, None) == 1
-    assert L.vs_probe_read_stream(FAKE, 1024, 8, None, None) == 1
-    assert L.vs_probe_read_stream(FAKE, 0, 8, FAKE, None) == 2
-    assert L.vs_probe_read_stream(FAKE, 1000, 8, FAKE, None) == 2    # not a multiple of 16 bytes
-    assert L.vs_probe_read_stream(FAKE, 1024, 0, FAKE, None) == 2
-    assert L.vs_probe_read_stream(FAKE, 1024, 70000, FAKE, None) == 2
-    assert L.vs_probe_read_stream(ODD, 1024, 8, FAKE, None) == 6
-
-
 def test_memory_bank_argument_errors():
     L = vs.lib()
     assert L.vs_memory_bank_workspace_bytes(0) == 0 and L.vs_memory_bank_workspace_bytes(1025) == 0
-    assert L.vs_memory_bank_workspace_bytes(128) >= 4 * 128
+    assert L.vs_memory_bank_workspace_bytes(128) >= 8 * 128
 
     def bank(e=FAKE, cap=4, ln=0, d=8, dt=vs.VS_BF16):
         return binding._CBank(e, cap, ln, d, dt)
@@ -266,3 +266,16 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))
     with pytest.raises(RuntimeError):
         binding.lib()
+
+
+def test_prefill_workgroup_placement_map(tmp_path):
+    """The id -> (unit, split, XCD) mapping behind the in-kernel merge of the bf16 prefill, checked on
+    the host for every (units, splits, XCD count) the planner can emit (tests/prefill_map_check.cpp
+    includes the header the kernel uses)."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "map_check")
+    subprocess.run(["g++", "-O2", "-std=c++17", "-I", os.path.join(root, "paper_2503_09387_amd", "csrc"),
+                    os.path.join(root, "tests", "prefill_map_check.cpp"), "-o", exe], check=True)
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.startswith("ok"), r.stdout + r.stderr

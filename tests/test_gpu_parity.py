@@ -22,7 +22,7 @@ QW = CONFIGS["cfg2"]["shape"]
 @pytest.fixture(autouse=True)
 def _reset_tuning():
     yield
-    for knob in (0, 1, 2, 3, 4):
+    for knob in (0, 1, 2, 4):
         vs.set_tuning(knob, 0)
 
 
@@ -98,50 +98,68 @@ def test_cfg2_stream_of_64_frames(fused):
 
 
 # ---------------------------------------------------------------------------- cfg3
-def test_cfg3_long_stream_28_layers_sampled():
-    """Full shapes (28 layers, 4296 retained rows, 170-token frames), the stream shortened to 3
-    frames placed at the start, middle and end of the 256-frame run via the initial length.
-    Indices, lengths and appended bytes on every (frame, layer); floats on sampled layers and
-    sampled tokens."""
+def test_cfg3_whole_stream_all_frames_all_layers():
+    """The whole long stream: 256 frames x 28 layers through vs_frame_prefill_compact, starting from
+    4296 retained rows per layer.  Row index and length of EVERY (frame, layer) call are compared
+    with oracle.compact_append run beside it, and at the end every cache byte (retained rows,
+    the 256 appended carrier rows, untouched tail) with the oracle's arrays.  Floats are checked
+    against the oracle on frames whose cache length is 0, 1 and 63 past a multiple of the kernel's
+    64-row tile (and the first, a middle and the last frame), three layers, eight tokens each.
+    The frames' Q/K/V come from a pool of 8 distinct frames per layer (frame f uses f % 8), as in
+    bench.py: the draw of 7168 frame-layers would take minutes, and the retained state does not
+    depend on which values move."""
     c = CONFIGS["cfg3"]
-    s, T, NL = c["shape"], c["n_visual"] + 1, c["layers"]
+    s, T, NL, P0, F = c["shape"], c["n_visual"] + 1, c["layers"], c["prefix"], c["frames"]
     sh = vs_shape(s)
-    cap = c["prefix"] + c["frames"]
+    cap = P0 + F
+    POOL = 8
     ws = workspace(s, T, cap, 0)
-    sample_layers = {0, 13, 27}
+    sample_layers = (0, 13, 27)
+    float_frames = {0, 55, 56, 57, 128, 255}          # 4296 + f = 63, 0, 1 (mod 64) at f = 55, 56, 57
+    assert [(P0 + f) % 64 for f in (55, 56, 57)] == [63, 0, 1]
     tokens = np.array([0, 1, 37, 84, 85, 127, 168, 169])
-    for start_frame in (0, 127, 253):
-        caches, host = [], []
+    tok_dev = torch.from_numpy(tokens).to(DEV)
+    pool_host = [[frame_inputs(c["seed"], s, T, c["sigma"], frame=f, layer=l) for l in range(NL)] for f in range(POOL)]
+    pool_dev = [[tuple(x.to(DEV) for x in fl) for fl in fr] for fr in pool_host]
+    pool_kv64 = [[(to_f64(fl[1]), to_f64(fl[2])) for fl in fr] for fr in pool_host]
+    caches, ok, ov, olen = [], [], [], []
+    for l in range(NL):
+        hk, hv = cache_rows(c["seed"], s, P0, c["sigma"], layer=l)
+        kc = torch.zeros((cap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+        vc = torch.zeros_like(kc)
+        kc[:P0].copy_(hk)
+        vc[:P0].copy_(hv)
+        caches.append(vs.Cache(kc, vc, P0))
+        k64, v64 = np.zeros((cap, s.n_kv_heads, s.head_dim)), np.zeros((cap, s.n_kv_heads, s.head_dim))
+        k64[:P0], v64[:P0] = to_f64(hk), to_f64(hv)
+        ok.append(k64)
+        ov.append(v64)
+        olen.append(P0)
+    outs = [torch.empty((T, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=DEV) for _ in sample_layers]
+    unchecked = torch.empty_like(outs[0])
+    for f in range(F):
+        pending = []
         for l in range(NL):
-            L0 = c["prefix"] + start_frame
-            hk, hv = cache_rows(c["seed"], s, L0, c["sigma"], layer=l)
-            kc = torch.zeros((cap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
-            vc = torch.zeros_like(kc)
-            kc[:L0].copy_(hk)
-            vc[:L0].copy_(hv)
-            caches.append(vs.Cache(kc, vc, L0))
-            host.append([hk, hv])
-        for f in range(start_frame, start_frame + 3):
-            for l in range(NL):
-                q, kf, vf = frame_inputs(c["seed"], s, T, c["sigma"], frame=f, layer=l)
-                qd, kfd, vfd = q.to(DEV), kf.to(DEV), vf.to(DEV)
-                out = torch.empty_like(qd)
-                L = caches[l].len
-                row = vs.frame_prefill_compact(sh, caches[l], qd, kfd, vfd, out, ws)
-                assert row == c["prefix"] + f and caches[l].len == row + 1
-                if l in sample_layers:
-                    ref = oracle_prefill_rows(s, q, host[l][0], host[l][1], L, kf, vf, tokens)
-                    torch.cuda.synchronize()
-                    check_close(out[torch.from_numpy(tokens).to(DEV)], ref, "bf16", f"cfg3 frame {f} layer {l}")
-                host[l][0] = torch.cat([host[l][0], kf[T - 1:]])
-                host[l][1] = torch.cat([host[l][1], vf[T - 1:]])
-        torch.cuda.synchronize()
-        for l in range(NL):
-            n = caches[l].len
-            assert n == c["prefix"] + start_frame + 3
-            assert same_bits(caches[l].k[:n], host[l][0]) and same_bits(caches[l].v[:n], host[l][1])
-            assert not caches[l].k[n:].any() and not caches[l].v[n:].any()
-    assert c["prefix"] + c["frames"] == 4552
+            qd, kfd, vfd = pool_dev[f % POOL][l]
+            sampled = f in float_frames and l in sample_layers
+            out = outs[sample_layers.index(l)] if sampled else unchecked
+            if sampled:  # the oracle's view of the cache before this frame
+                q, kf, vf = pool_host[f % POOL][l]
+                ref = oracle.attention(to_f64(q)[tokens], np.concatenate([ok[l][:olen[l]], to_f64(kf)]),
+                                       np.concatenate([ov[l][:olen[l]], to_f64(vf)]), olen[l] + tokens + 1, scale32(s))
+                pending.append((l, out, ref))
+            row = vs.frame_prefill_compact(sh, caches[l], qd, kfd, vfd, out, ws)
+            orow, olen[l] = oracle.compact_append(ok[l], ov[l], olen[l], *pool_kv64[f % POOL][l])
+            assert (row, caches[l].len) == (orow, olen[l]) == (P0 + f, P0 + f + 1), f"frame {f} layer {l}"
+        if pending:
+            torch.cuda.synchronize()
+            for l, out, ref in pending:
+                check_close(out[tok_dev], ref, "bf16", f"cfg3 whole stream, frame {f} layer {l}")
+    torch.cuda.synchronize()
+    for l in range(NL):
+        assert caches[l].len == olen[l] == 4552
+        assert np.array_equal(caches[l].k.double().cpu().numpy(), ok[l]), f"K cache of layer {l}"
+        assert np.array_equal(caches[l].v.double().cpu().numpy(), ov[l]), f"V cache of layer {l}"
 
 
 # ---------------------------------------------------------------------------- cfg4
@@ -181,6 +199,73 @@ def test_cfg4_decode_16_ragged_streams():
         for i in range(S):
             assert np.array_equal(ks[i].double().cpu().numpy(), ok[i])
             assert np.array_equal(vsl[i].double().cpu().numpy(), ov[i])
+
+
+def test_cfg4_whole_decode_64_steps_28_layers():
+    """All 64 steps on all 28 layers of the 16 ragged streams.  After every call the lengths are
+    compared with the oracle's; at the end every appended row (64 per stream and layer) is compared
+    bit for bit with what oracle.compact_append put there, and the rows in front of them and behind
+    them with what was there before.  Floats against oracle.decode for all 16 streams at
+    (layer, step) = (0, 0), (13, 31) and (27, 63), the last step included.
+    The oracle's row copy works on a window of each stream's cache that starts at the stream's
+    initial length (an append is the same operation wherever the row sits; whole caches in fp64
+    would take 30 GB).  Four distinct layer slabs are drawn and copied to the 28 layers, as in
+    bench.py; the inputs of every (step, layer) are drawn on their own."""
+    c = CONFIGS["cfg4"]
+    s, S, NL, steps = c["shape"], c["streams"], c["layers"], c["steps"]
+    sh = vs_shape(s)
+    lens0 = decode_lengths(c["seed"], S, c["carrier_lo"], c["carrier_hi"], c["text_hist"])
+    cap = c["carrier_hi"] + c["text_hist"] + steps
+    ws = workspace(s, 0, cap, S)
+    DISTINCT = 4
+    base_host, base_dev = [], []
+    for l in range(DISTINCT):
+        k = torch.zeros((S, cap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16)
+        v = torch.zeros_like(k)
+        for i in range(S):
+            hk, hv = cache_rows(c["seed"], s, lens0[i], c["sigma"], layer=l, stream=i)
+            k[i, :lens0[i]], v[i, :lens0[i]] = hk, hv
+        base_host.append((k, v))
+        base_dev.append((k.to(DEV), v.to(DEV)))
+    slabs = [(base_dev[l % DISTINCT][0].clone(), base_dev[l % DISTINCT][1].clone()) for l in range(NL)]
+    lens = [lens_array(lens0) for _ in range(NL)]
+    # oracle state: the rows appended to (layer, stream), as a window starting at the initial length
+    wk = [[np.zeros((steps, s.n_kv_heads, s.head_dim)) for _ in range(S)] for _ in range(NL)]
+    wv = [[np.zeros((steps, s.n_kv_heads, s.head_dim)) for _ in range(S)] for _ in range(NL)]
+    wlen = [[0] * S for _ in range(NL)]
+    float_at = {(0, 0), (13, 31), (27, steps - 1)}
+    out = torch.empty((S, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+    for step in range(steps):
+        for l in range(NL):
+            q, kn, vn = decode_step_inputs(c["seed"], s, S, c["sigma"], step=step, layer=l)
+            kn64, vn64 = to_f64(kn), to_f64(vn)
+            ref = None
+            if (l, step) in float_at:
+                ref = np.zeros((S, s.n_q_heads, s.head_dim))
+                for i in range(S):
+                    n0 = lens0[i]
+                    k_all = np.concatenate([to_f64(base_host[l % DISTINCT][0][i, :n0]), wk[l][i][:step], np.zeros((1, s.n_kv_heads, s.head_dim))])
+                    v_all = np.concatenate([to_f64(base_host[l % DISTINCT][1][i, :n0]), wv[l][i][:step], np.zeros((1, s.n_kv_heads, s.head_dim))])
+                    ref[i], n_after = oracle.decode(to_f64(q[i]), k_all, v_all, n0 + step, kn64[i], vn64[i], scale32(s))
+                    assert n_after == n0 + step + 1
+            vs.decode_attn(sh, slabs[l][0], slabs[l][1], lens[l], q.to(DEV), kn.to(DEV), vn.to(DEV), out, ws)
+            for i in range(S):
+                row, wlen[l][i] = oracle.compact_append(wk[l][i], wv[l][i], wlen[l][i], kn64[i:i + 1], vn64[i:i + 1])
+                assert row == step
+            assert list(lens[l]) == [lens0[i] + wlen[l][i] for i in range(S)], f"lengths after step {step}, layer {l}"
+            if ref is not None:
+                torch.cuda.synchronize()
+                check_close(out, ref, "bf16", f"cfg4 whole decode, layer {l} step {step}")
+    torch.cuda.synchronize()
+    for l in range(NL):
+        kd, vd = slabs[l][0].cpu(), slabs[l][1].cpu()
+        for i in range(S):
+            n0 = lens0[i]
+            assert lens[l][i] == n0 + steps
+            assert np.array_equal(to_f64(kd[i, n0:n0 + steps]), wk[l][i]), f"appended K rows, layer {l} stream {i}"
+            assert np.array_equal(to_f64(vd[i, n0:n0 + steps]), wv[l][i]), f"appended V rows, layer {l} stream {i}"
+            assert torch.equal(kd[i, :n0], base_host[l % DISTINCT][0][i, :n0]) and torch.equal(vd[i, :n0], base_host[l % DISTINCT][1][i, :n0])
+            assert not kd[i, n0 + steps:].any() and not vd[i, n0 + steps:].any()
 
 
 # ---------------------------------------------------------------------------- cfg5
@@ -260,6 +345,67 @@ def test_prefill_merge_inside_the_kernel_equals_the_second_kernel(L, T, splits):
     for rep in range(3):
         inside, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
         assert same_bits(inside, two_kernels.cpu()), f"merge inside the kernel differs (call {rep})"
+
+
+@pytest.mark.parametrize("F,T,L,splits", [(2, 170, 4296, 0), (2, 170, 4296, 5), (3, 170, 2000, 4), (4, 60, 900, 2),
+                                          (8, 21, 700, 3)])
+def test_runs_of_frames_merge_inside_the_kernel_equals_the_second_kernel(F, T, L, splits):
+    """The same for runs of frames: units are (KV head, frame, row tile), every frame reads its own
+    number of retained rows; both ways of merging give the same bits, call after call."""
+    s = QW
+    sh = vs_shape(s)
+    hk, hv = cache_rows(71, s, L, 0.5)
+    q = draw(72, (F, T, s.n_q_heads, s.head_dim), 1.5, "bf16").to(DEV)
+    kf = draw(73, (F, T, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(DEV)
+    vf = draw(74, (F, T, s.n_kv_heads, s.head_dim), 0.5, "bf16").to(DEV)
+    kc = torch.zeros((L + F, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=DEV)
+    vc = torch.zeros_like(kc)
+    kc[:L].copy_(hk)
+    vc[:L].copy_(hv)
+    ws = torch.empty(vs.frames_workspace_bytes(sh, F, T, L + F), dtype=torch.uint8, device=DEV)
+    vs.workspace_init(sh, ws)
+    vs.set_tuning(vs.TUNE_PREFILL_SPLITS, splits)
+
+    def run():
+        cache = vs.Cache(kc, vc, L)
+        out = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+        vs.frames_prefill_attn(sh, cache, q, kf, vf, out, ws)
+        torch.cuda.synchronize()
+        return out
+    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 2)
+    two_kernels = run()
+    assert bool(torch.isfinite(two_kernels.float()).all())
+    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
+    for rep in range(3):
+        assert torch.equal(run().view(torch.int16), two_kernels.view(torch.int16)), f"call {rep}"
+
+
+def test_prefill_placement_guard_reports_and_falls_back():
+    """Every workgroup of an in-kernel-merge launch checks that it runs on the XCD that the probe
+    saw for its id.  With the probed order handed over rotated by one (tuning value 3) all of them
+    report themselves misplaced: the launch itself is still right (the real placement is
+    unchanged), the next call launches nothing and returns VS_ERR_PLACEMENT, the calls after it merge
+    with the second kernel and give the same bits, and a new vs_workspace_init probes again and
+    brings the in-kernel merge back."""
+    s, L, T = QW, 1500, 170
+    hk, hv = cache_rows(75, s, L, 0.5)
+    q, kf, vf = frame_inputs(75, s, T, 0.5, q_gain=4)
+    ws = workspace(s, T, L, 0)
+    good, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
+    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 3)
+    flagged, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)      # runs, reports, result still right
+    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
+    assert same_bits(flagged, good.cpu())
+    with pytest.raises(vs.VSError) as err:
+        run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
+    assert err.value.code == 8
+    for _ in range(2):                                                # second-kernel merge from now on
+        after, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
+        assert same_bits(after, good.cpu())
+    ws2 = workspace(s, T, L, 0)                                       # probes the device again
+    again, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws2)
+    assert same_bits(again, good.cpu())
+    run_prefill(s, hk, hv, L, q, kf, vf, ws=ws2)                      # and nothing is reported this time
 
 
 @pytest.mark.parametrize("L", [130, 1500])
@@ -366,6 +512,19 @@ def test_decode_result_does_not_depend_on_the_chunking():
         assert (out.float() - ref_out).abs().max().item() <= 2 ** -7 * ref_out.abs().max().item()
 
 
+@pytest.mark.parametrize("hq,hkv", [(6, 3), (12, 6), (5, 5), (16, 2), (8, 1), (24, 8)])
+@pytest.mark.parametrize("chunk", [0, 32])
+def test_decode_other_kv_head_counts(hq, hkv, chunk):
+    """KV head counts that are not multiples of 4 (a workgroup then takes 1 or 2 heads and its spare
+    wavefronts take sub-ranges of the share), with the library's own shares and with the smallest
+    ones (one tile per share: the most workgroups, the highest partial-result slots)."""
+    s = AttnShape(hq, hkv, 128, "bf16")
+    vs.set_tuning(vs.TUNE_DECODE_CHUNK_ROWS, chunk)
+    lens0 = [3000, 1, 129, 64, 700, 33] + [40 + 37 * i for i in range(20)]
+    out, ref, _ = _decode_case(s, lens0, 3072, 26, gain=4)
+    check_close(out, ref, "bf16", f"decode Hq={hq} Hkv={hkv} chunk_rows={chunk}")
+
+
 def test_decode_equals_one_token_prefill():
     s, L = QW, 900
     out, ref, (q, kn, vn) = _decode_case(s, [L], 1024, 24, gain=4)
@@ -381,32 +540,6 @@ def test_decode_fp32_path():
     check_close(out, ref, "f32", "fp32 decode")
 
 
-def test_prefill_timestamps_knob():
-    """VS_TUNE_TIMESTAMPS = 7: every workgroup of a single-frame bf16 prefill leaves four clock
-    readings (start, pipeline start, pipeline end, end) in the last MiB of the workspace; the
-    output is the same bits as without them."""
-    s, L, T = QW, 1500, 170
-    hk, hv = cache_rows(33, s, L, 0.5)
-    q, kf, vf = frame_inputs(33, s, T, 0.5)
-    plain, _, _ = run_prefill(s, hk, hv, L, q, kf, vf)
-    nbytes = vs.workspace_bytes(vs_shape(s), T, 0, 0)
-    ws = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
-    vs.workspace_init(vs_shape(s), ws)
-    vs.set_tuning(vs.TUNE_TIMESTAMPS, 7)
-    try:
-        stamped, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
-    finally:
-        vs.set_tuning(vs.TUNE_TIMESTAMPS, 0)
-    assert same_bits(stamped, plain.cpu())
-    t = ws[nbytes - (1 << 20):].view(torch.int64).cpu().numpy().reshape(-1, 4)
-    used = t[t[:, 0] != 0]
-    assert 4 <= len(used) <= 4096, len(used)            # one record per workgroup of the launch
-    assert (np.diff(used, axis=1) >= 0).all(), "clock readings of a workgroup must not go backwards"
-    span = (used[:, 3].max() - used[:, 0].min()) / 100.0  # the clock counts at 100 MHz
-    assert 1.0 < span < 1000.0, f"launch spans {span} us"
-
-
-# ---------------------------------------------------------------------------- the largest sizes the boundary accepts
 def test_prefill_largest_run_and_head_ratio():
     """4096 tokens in one run (the limit), 8 query heads per KV head (the limit): 32768 query rows
     per KV head, 256 row tiles; sampled tokens against the oracle."""
@@ -593,9 +726,9 @@ def test_batched_compaction(n_caches, pinned):
                                               ("bf16", 5, 8, 0), ("f32", 130, 64, 0)])
 def test_memory_bank_stream(dtype, M, d, policy):
     """Carriers arrive one by one: the bank fills, then drops the older carrier of the most similar
-    adjacent pair.  Victim indices against the fp64 oracle (equal whenever the two best cosines
-    differ by more than the fp32 summation error), embeddings and the K/V rows of three layers
-    bit for bit."""
+    adjacent pair.  Victim indices against the fp64 oracle (the device sums in fp64 too, in another
+    order: equal whenever the two best cosines differ by more than 1e-6, far above what the order of
+    summation can move), embeddings and the K/V rows of three layers bit for bit."""
     s = AttnShape(4, 2, 64, "f32") if dtype == "f32" else QW
     n_layers, first, extra = 3, 5, 40
     n = M + extra
@@ -627,8 +760,8 @@ def test_memory_bank_stream(dtype, M, d, policy):
         else:
             want, cos = oracle.bank_victim(o_emb, e64, policy)
             top = np.sort(cos)[::-1]
-            assert 0 <= got < M and cos[got] >= top[0] - 1e-5, f"carrier {t}: victim {got}, cosine {cos[got]} vs best {top[0]}"
-            if top[0] - top[1] > 1e-5:
+            assert 0 <= got < M and cos[got] >= top[0] - 1e-6, f"carrier {t}: victim {got}, cosine {cos[got]} vs best {top[0]}"
+            if top[0] - top[1] > 1e-6:
                 assert got == want, f"carrier {t}: victim {got}, oracle {want}"
             else:
                 near_ties += 1
@@ -738,7 +871,7 @@ def test_stream_with_memory_bank_prefill_reads_the_bank():
         if o_n == M:
             want, cos = oracle.bank_victim(o_emb, e64)
             top = np.sort(cos)[::-1]
-            assert got == want or top[0] - top[1] <= 1e-5
+            assert got == want or top[0] - top[1] <= 1e-6
         else:
             assert got == -1
         for l in range(n_layers):
