@@ -209,6 +209,24 @@ vs_status vs_decode_attn(const vs_shape *shape, int32_t n_streams, void *k_slab,
                          void *hip_stream);
 
 /*
+ * vs_decode_attn without a workspace argument, for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid allocation).  Same
+ * arguments, same results bit for bit, same errors; the partial results of the row shares go
+ * into an array of vs_decode_static_scratch_bytes() = 16 MiB that is part of the library's
+ * code object on every device (each GPU the library runs on holds it until the process ends).
+ * Neither this call nor anything it calls allocates or frees memory.  VS_ERR_WORKSPACE if the
+ * call would need more than the array holds (vs_workspace_bytes(shape, 0, capacity, n_streams)
+ * is the measure: 28 query / 4 KV heads of 128 fit with room to spare; 64 query heads per
+ * launch group of 64 streams do not).  All calls on one GPU share that GPU's array, which keeps
+ * what the last call left in it (nothing in it has to be cleared for this call): two calls
+ * that overlap in time on one GPU, on different streams, race; order them.
+ */
+size_t vs_decode_static_scratch_bytes(void);
+vs_status vs_decode_attn_static(const vs_shape *shape, int32_t n_streams, void *k_slab, void *v_slab,
+                                int32_t capacity, int32_t *lens, const void *q, const void *k_new,
+                                const void *v_new, void *out, void *hip_stream);
+
+/*
  * Carrier embedding (Section 3.3: C^t = (1/N) sum_i E^t_i).  e [n][d] -> c_out [d],
  * storage type `dtype`, fp32 accumulation in row order, one rounding at the end.
  * d must be a multiple of 8 (bf16) or 4 (fp32).

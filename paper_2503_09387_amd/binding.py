@@ -12,7 +12,8 @@ EXPORTS = [
     "vs_status_string", "vs_workspace_bytes", "vs_workspace_init", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
     "vs_carrier_compact_append", "vs_carrier_compact_append_batched", "vs_decode_attn",
     "vs_carrier_mean_pool", "vs_set_tuning", "vs_memory_bank_push", "vs_carrier_evict_append",
-    "vs_frames_prefill_attn", "vs_question_prefill_append", "vs_frame_qkv_project", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
+    "vs_frames_prefill_attn", "vs_decode_attn_static", "vs_question_prefill_append", "vs_frame_qkv_project", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
+    "vs_decode_static_scratch_bytes",
 ]
 
 
@@ -96,6 +97,9 @@ def lib():
                                                         vp, sz, vp]
         L.vs_decode_attn.argtypes = [sp, i32, vp, vp, i32, ip, vp, vp, vp, vp, vp, sz, vp]
         L.vs_carrier_mean_pool.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.vs_decode_attn_static.argtypes = [sp, i32, vp, vp, i32, ip, vp, vp, vp, vp, vp]
+        L.vs_decode_static_scratch_bytes.argtypes = []
+        L.vs_decode_static_scratch_bytes.restype = sz
         L.vs_set_tuning.argtypes = [i32, i32]
         L.vs_memory_bank_push.argtypes = [vp, vp, i32, vp, vp, sz, vp]
         L.vs_carrier_evict_append.argtypes = [sp, i32, vp, i32, i32, vp, vp, ctypes.c_int64, vp, vp]
@@ -105,7 +109,7 @@ def lib():
         L.vs_frames_workspace_bytes.argtypes = [sp, i32, i32, i32]
         L.vs_frames_workspace_bytes.restype = sz
         L.vs_frame_qkv_project.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
-        for name in EXPORTS[2:-2]:
+        for name in EXPORTS[2:-3]:
             getattr(L, name).restype = ctypes.c_int
         _LIB = L
     return _LIB
@@ -238,6 +242,18 @@ def decode_attn(shape, k_slab, v_slab, lens, q, k_new, v_new, out, workspace, st
     _check(lib().vs_decode_attn(ctypes.byref(shape), n_streams, _ptr(k_slab), _ptr(v_slab), capacity, lens,
                                 _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), wp, wb, _stream(stream)),
            "vs_decode_attn")
+
+
+def decode_attn_static(shape, k_slab, v_slab, lens, q, k_new, v_new, out, stream=None):
+    """decode_attn over the library's own scratch array (no workspace, nothing allocated)."""
+    n_streams, capacity = k_slab.shape[0], k_slab.shape[1]
+    _check(lib().vs_decode_attn_static(ctypes.byref(shape), n_streams, _ptr(k_slab), _ptr(v_slab), capacity, lens,
+                                       _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _stream(stream)),
+           "vs_decode_attn_static")
+
+
+def decode_static_scratch_bytes():
+    return int(lib().vs_decode_static_scratch_bytes())
 
 
 def frames_workspace_bytes(shape, n_frames, n_tokens, max_cache_rows):

@@ -119,6 +119,73 @@ vs_status prefill_common(const vs_shape* shape, vs_cache* cache, bool append, co
 
 }  // namespace
 
+// vs_decode_attn, and the entry point that brings its own scratch memory.
+vs_status vs::decode_entry(const vs_shape* shape, int32_t n_streams, void* k_slab, void* v_slab,
+                           int32_t capacity, int32_t* lens, const void* q, const void* k_new,
+                           const void* v_new, void* out, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+    forget_stale_hip_error();
+    vs_status st = check_shape(shape);
+    if (st != VS_OK) return st;
+    if (!k_slab || !v_slab || !lens || !q || !out) return VS_ERR_NULL;
+    if ((k_new == nullptr) != (v_new == nullptr)) return VS_ERR_NULL;
+    if (n_streams < 1 || n_streams > kMaxStreams || capacity < 1) return VS_ERR_SHAPE;
+    if (!aligned16(k_slab) || !aligned16(v_slab) || !aligned16(q) || !aligned16(out) ||
+        !aligned16(k_new) || !aligned16(v_new))
+        return VS_ERR_ALIGN;
+    const int add = k_new ? 1 : 0;
+    int32_t max_rows = 0;
+    for (int32_t s = 0; s < n_streams; ++s) {
+        if (lens[s] < 0) return VS_ERR_SHAPE;
+        if (lens[s] > capacity || lens[s] + add > capacity) return VS_ERR_CAPACITY;
+        if (lens[s] + add < 1) return VS_ERR_SHAPE;
+        if (lens[s] + add > max_rows) max_rows = lens[s] + add;
+    }
+    const bool mfma = shape->dtype == VS_BF16;
+    const size_t ctrl = control_block_bytes(*shape);
+    if (mfma) {
+        const int chunk = n_streams < kMaxStreamsPerLaunch ? n_streams : kMaxStreamsPerLaunch;
+        if (!workspace || workspace_bytes < ctrl + decode_mfma_workspace_bytes(*shape, chunk, max_rows))
+            return VS_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return VS_ERR_ALIGN;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t rb = row_bytes(shape);
+    const int64_t qo_stride = (int64_t)shape->n_q_heads * shape->head_dim * (int64_t)elem_bytes(shape);
+    for (int32_t s0 = 0; s0 < n_streams; s0 += kMaxStreamsPerLaunch) {
+        const int32_t ns = (n_streams - s0) < kMaxStreamsPerLaunch ? (n_streams - s0) : kMaxStreamsPerLaunch;
+        char* ks = static_cast<char*>(k_slab) + (int64_t)s0 * capacity * rb;
+        char* vs_ = static_cast<char*>(v_slab) + (int64_t)s0 * capacity * rb;
+        const char* kn = add ? static_cast<const char*>(k_new) + (int64_t)s0 * rb : nullptr;
+        const char* vn = add ? static_cast<const char*>(v_new) + (int64_t)s0 * rb : nullptr;
+        const char* qs = static_cast<const char*>(q) + (int64_t)s0 * qo_stride;
+        char* os = static_cast<char*>(out) + (int64_t)s0 * qo_stride;
+        LenTable t{};
+        hipError_t e = hipSuccess;
+        if (mfma) {
+            // the kernel reads the new row from k_new/v_new and stores it into the slab itself
+            for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i] + add;
+            e = launch_decode_mfma(*shape, ns, ks, vs_, capacity, t, qs, kn, vn, os, workspace,
+                                   static_cast<char*>(workspace) + ctrl, stream);
+        } else {
+            if (add) {
+                for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i];
+                e = launch_append_rows(ns, ks, vs_, (int64_t)capacity * rb, &t, nullptr, kn, vn, rb, 0,
+                                       (int32_t)rb, stream);
+                if (e != hipSuccess) return VS_ERR_HIP;  // (a row copy that did not start leaves nothing behind)
+            }
+            for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i] + add;
+            e = launch_decode_simple(*shape, ns, ks, vs_, capacity, t, qs, os, stream);
+        }
+        if (e != hipSuccess) return VS_ERR_HIP;
+        // the lengths follow the launches group by group: after a failure in a later group, lens
+        // still says exactly which rows have been written
+        if (add)
+            for (int32_t i = 0; i < ns; ++i) lens[s0 + i] += 1;
+    }
+    return VS_OK;
+}
+
 extern "C" {
 
 const char* vs_status_string(vs_status s) {
@@ -293,66 +360,8 @@ vs_status vs_decode_attn(const vs_shape* shape, int32_t n_streams, void* k_slab,
                          int32_t capacity, int32_t* lens, const void* q, const void* k_new,
                          const void* v_new, void* out, void* workspace, size_t workspace_bytes,
                          void* hip_stream) {
-    forget_stale_hip_error();
-    vs_status st = check_shape(shape);
-    if (st != VS_OK) return st;
-    if (!k_slab || !v_slab || !lens || !q || !out) return VS_ERR_NULL;
-    if ((k_new == nullptr) != (v_new == nullptr)) return VS_ERR_NULL;
-    if (n_streams < 1 || n_streams > kMaxStreams || capacity < 1) return VS_ERR_SHAPE;
-    if (!aligned16(k_slab) || !aligned16(v_slab) || !aligned16(q) || !aligned16(out) ||
-        !aligned16(k_new) || !aligned16(v_new))
-        return VS_ERR_ALIGN;
-    const int add = k_new ? 1 : 0;
-    int32_t max_rows = 0;
-    for (int32_t s = 0; s < n_streams; ++s) {
-        if (lens[s] < 0) return VS_ERR_SHAPE;
-        if (lens[s] > capacity || lens[s] + add > capacity) return VS_ERR_CAPACITY;
-        if (lens[s] + add < 1) return VS_ERR_SHAPE;
-        if (lens[s] + add > max_rows) max_rows = lens[s] + add;
-    }
-    const bool mfma = shape->dtype == VS_BF16;
-    const size_t ctrl = control_block_bytes(*shape);
-    if (mfma) {
-        const int chunk = n_streams < kMaxStreamsPerLaunch ? n_streams : kMaxStreamsPerLaunch;
-        if (!workspace || workspace_bytes < ctrl + decode_mfma_workspace_bytes(*shape, chunk, max_rows))
-            return VS_ERR_WORKSPACE;
-        if (!aligned16(workspace)) return VS_ERR_ALIGN;
-    }
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int64_t rb = row_bytes(shape);
-    const int64_t qo_stride = (int64_t)shape->n_q_heads * shape->head_dim * (int64_t)elem_bytes(shape);
-    for (int32_t s0 = 0; s0 < n_streams; s0 += kMaxStreamsPerLaunch) {
-        const int32_t ns = (n_streams - s0) < kMaxStreamsPerLaunch ? (n_streams - s0) : kMaxStreamsPerLaunch;
-        char* ks = static_cast<char*>(k_slab) + (int64_t)s0 * capacity * rb;
-        char* vs_ = static_cast<char*>(v_slab) + (int64_t)s0 * capacity * rb;
-        const char* kn = add ? static_cast<const char*>(k_new) + (int64_t)s0 * rb : nullptr;
-        const char* vn = add ? static_cast<const char*>(v_new) + (int64_t)s0 * rb : nullptr;
-        const char* qs = static_cast<const char*>(q) + (int64_t)s0 * qo_stride;
-        char* os = static_cast<char*>(out) + (int64_t)s0 * qo_stride;
-        LenTable t{};
-        hipError_t e = hipSuccess;
-        if (mfma) {
-            // the kernel reads the new row from k_new/v_new and stores it into the slab itself
-            for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i] + add;
-            e = launch_decode_mfma(*shape, ns, ks, vs_, capacity, t, qs, kn, vn, os, workspace,
-                                   static_cast<char*>(workspace) + ctrl, stream);
-        } else {
-            if (add) {
-                for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i];
-                e = launch_append_rows(ns, ks, vs_, (int64_t)capacity * rb, &t, nullptr, kn, vn, rb, 0,
-                                       (int32_t)rb, stream);
-                if (e != hipSuccess) return VS_ERR_HIP;  // (a row copy that did not start leaves nothing behind)
-            }
-            for (int32_t i = 0; i < ns; ++i) t.v[i] = lens[s0 + i] + add;
-            e = launch_decode_simple(*shape, ns, ks, vs_, capacity, t, qs, os, stream);
-        }
-        if (e != hipSuccess) return VS_ERR_HIP;
-        // the lengths follow the launches group by group: after a failure in a later group, lens
-        // still says exactly which rows have been written
-        if (add)
-            for (int32_t i = 0; i < ns; ++i) lens[s0 + i] += 1;
-    }
-    return VS_OK;
+    return vs::decode_entry(shape, n_streams, k_slab, v_slab, capacity, lens, q, k_new, v_new, out, workspace,
+                            workspace_bytes, hip_stream);
 }
 
 size_t vs_frames_workspace_bytes(const vs_shape* shape, int32_t n_frames, int32_t n_tokens,

@@ -75,6 +75,11 @@ hipError_t probe_xcd_mapping(void* scratch, hipStream_t st);
 bool prefill_placement_fault(int dev);
 void prefill_guard_test_mode(int on);
 
+// the body of vs_decode_attn (checks, launches, length bookkeeping) over any workspace
+vs_status decode_entry(const vs_shape* shape, int32_t n_streams, void* k_slab, void* v_slab, int32_t capacity,
+                       int32_t* lens, const void* q, const void* k_new, const void* v_new, void* out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
 // row copies
 hipError_t launch_append_rows(int32_t n_caches, void* k_slab, void* v_slab, int64_t cache_stride_bytes,
                               const LenTable* lens_by_value, const int32_t* lens_device,
