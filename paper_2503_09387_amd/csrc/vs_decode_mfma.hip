@@ -8,9 +8,9 @@
 // the KV heads (wavefront w walks the share for head w), so together they stream contiguous
 // memory, which HBM serves measurably faster than one head's 256 bytes out of every 1 KB.
 // (With fewer than 4 KV heads the spare wavefronts take sub-ranges of the share; with more,
-// blockIdx.y selects the group of 4 heads.)  The grid is at most two workgroups per compute
-// unit, so they all run at once and stream for the whole launch.  A wavefront works alone,
-// with no barrier anywhere in the kernel:
+// blockIdx.y selects the group of 4 heads.)  The grid is one workgroup per compute unit, so
+// they all run at once and stream for the whole launch.  A wavefront works alone, with no
+// barrier anywhere in the kernel:
 //   * K rows go straight from global memory into the A operand of
 //     v_mfma_f32_16x16x32_bf16 (S^T = K Q^T; the G query heads of the KV head are the
 //     columns, padded to 16);
@@ -23,10 +23,12 @@
 // The row appended in this step is read from k_new / v_new (never from the slab, which the
 // wavefront that owns the stream's last tile updates on the side).  Every wavefront leaves a
 // normalised partial result (bf16) with its reference and sum; a second small kernel merges
-// them.  (Merging inside the attention kernel, by the last workgroup to arrive, was measured
-// and rejected: partials must then be written through to device-coherent memory or the L2
-// flushed per workgroup, because the 8 XCDs' L2 caches are not coherent with each other
-// inside a kernel, and either costs more than a second launch.)
+// them (a launch that follows another on the same stream starts within about a microsecond of
+// it; what the merge costs is its one round trip to memory).  Merging inside the attention
+// kernel, by the last wavefront of a stream to arrive, would need the partials of workgroups on
+// all 8 XCDs, whose L2 caches are not coherent with each other inside a kernel: they would
+// have to be written through and re-read at device scope, which on the prefill kernel cost
+// more than the second launch does here.
 #include "vs_internal.h"
 
 namespace vs {
@@ -62,6 +64,8 @@ struct DecodeParams {
     float scale_log2e;
     LenTable lens;           // valid rows per stream, the appended row included
     int tile_prefix[kMaxStreamsPerLaunch + 1];  // tiles of the streams before this one
+    int first_wg[kMaxStreamsPerLaunch];  // first workgroup (along x) that holds tiles of the stream, and how many do:
+    int n_wgs[kMaxStreamsPerLaunch];     // what the merge kernel walks
 };
 
 // first flat tile of workgroup w (w = n_wg gives the end)
@@ -125,7 +129,13 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
 
 #define VS_KPTR(row) (((row) == new_row ? knew : kslab + (int64_t)(row) * row_stride) + 8 * kq)
 #define VS_VPTR(row) (((row) == new_row ? vnew : vslab + (int64_t)(row) * row_stride) + 8 * i16)
-#define VS_LD(ptr) (*reinterpret_cast<const uint4*>(ptr))
+// every K/V byte is read once by one wavefront: the loads are marked non-temporal
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_nt(const void* p) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+#define VS_LD(ptr) ld_nt(ptr)
 // loads one tile into the register set named by suffix X: 8 K operands (rows r+i16 and
 // r+16+i16) and 8 V row pieces (individually named registers, so that nothing lands in scratch)
 #define VS_FETCH(tile, X)                                                            \
@@ -285,50 +295,43 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
 #undef VS_TILE
 
 // Merge of a stream's partials (a stream that one wavefront per head covered alone was written
-// directly).  Grid (streams, query heads), 128 threads = 8 groups x 16: a thread owns 8 output
-// dims and the partials group, group + 8, ..., all of them requested at once; the groups are
-// then merged through LDS.
-constexpr int kCombineGroups = 8, kCombineDepth = 8;
-__global__ __launch_bounds__(16 * kCombineGroups) void decode_combine_kernel(DecodeParams p) {
+// directly).  Grid (streams, query heads), one wavefront each = 4 groups of 16 lanes: a lane owns
+// 8 output dims and the partials group, group + 4, ..; up to kCombineDepth of them per lane are
+// requested at once (one round trip to memory for up to 64 partials), merged in the lane in index
+// order, and the four groups are then merged with two lane exchanges.  No LDS, no barrier.
+constexpr int kCombineGroups = 4, kCombineDepth = 16;
+__global__ __launch_bounds__(64) void decode_combine_kernel(DecodeParams p) {
     const int s = blockIdx.x, hq = blockIdx.y;
+    const int w_first = p.first_wg[s], n_wgs = p.n_wgs[s];
+    if (n_wgs == 1 && p.nsub == 1) return;
     const int g = hq / p.G, h = hq - g * p.G;
-    const int tid = threadIdx.x, pg = tid >> 4, t = tid & 15, d8 = t * 8;
-    // largest w with wg_first_tile(w) <= tile
-    auto owner = [&](int tile) {
-        const int big = p.share_r * (p.share_q + 1);  // tiles held by the workgroups with one tile more
-        return tile < big ? tile / (p.share_q + 1) : p.share_r + (tile - big) / max(p.share_q, 1);
-    };
-    const int w_first = owner(p.tile_prefix[s]), w_last = owner(p.tile_prefix[s + 1] - 1);
-    if (w_first == w_last && p.nsub == 1) return;
-    const int n_parts = (w_last - w_first + 1) * p.nsub;
+    const int lane = threadIdx.x, pg = lane >> 4, t = lane & 15, d8 = t * 8;
+    const int n_parts = n_wgs * p.nsub;
     // partial c of the stream: workgroup w_first + c / nsub, sub-range c % nsub
+    const int64_t slot_rows = (int64_t)p.Hkv * p.nsub * p.G;
     auto row_of = [&](int c) {
-        const int w = w_first + c / p.nsub, sub = c - (c / p.nsub) * p.nsub;
-        return ((((int64_t)w + s) * p.Hkv + g) * p.nsub + sub) * p.G + h;
+        const int w = p.nsub == 1 ? c : c / p.nsub, sub = p.nsub == 1 ? 0 : c - w * p.nsub;
+        return ((int64_t)(w_first + w + s) * slot_rows) + ((int64_t)g * p.nsub + sub) * p.G + h;
     };
     float acc[8], den = 0.f, mref = -INFINITY;
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     for (int c0 = pg; c0 < n_parts; c0 += kCombineGroups * kCombineDepth) {
-        float m[kCombineDepth], l[kCombineDepth];
+        float2 ml[kCombineDepth];
         bf16x8 o[kCombineDepth];
 #pragma unroll
         for (int u = 0; u < kCombineDepth; ++u) {
-            const int c = c0 + kCombineGroups * u;
-            m[u] = -INFINITY;
-            l[u] = 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) o[u][j] = (__bf16)0.f;
-            if (c < n_parts) {
-                const int64_t pr = row_of(c);
-                m[u] = p.part_ml[pr * 2];
-                l[u] = p.part_ml[pr * 2 + 1];
-                o[u] = *reinterpret_cast<const bf16x8*>(p.part_o + pr * D + d8);
-            }
+            const int c = min(c0 + kCombineGroups * u, n_parts - 1);  // (past the end: a valid row, ignored below)
+            const int64_t pr = row_of(c);
+            ml[u] = *reinterpret_cast<const float2*>(p.part_ml + pr * 2);
+            o[u] = *reinterpret_cast<const bf16x8*>(p.part_o + pr * D + d8);
         }
+#pragma unroll
+        for (int u = 0; u < kCombineDepth; ++u)
+            if (c0 + kCombineGroups * u >= n_parts) ml[u] = make_float2(-INFINITY, 0.f);
         float mx = mref;
 #pragma unroll
-        for (int u = 0; u < kCombineDepth; ++u) mx = fmaxf(mx, m[u]);
+        for (int u = 0; u < kCombineDepth; ++u) mx = fmaxf(mx, ml[u].x);
         if (mx == -INFINITY) continue;
         const float sc = (mref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mref - mx);
         den *= sc;
@@ -337,36 +340,34 @@ __global__ __launch_bounds__(16 * kCombineGroups) void decode_combine_kernel(Dec
         mref = mx;
 #pragma unroll
         for (int u = 0; u < kCombineDepth; ++u) {
-            const float wt = (m[u] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[u] - mx) * l[u];
+            const float wt = (ml[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[u].x - mx) * ml[u].y;
             den += wt;
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] += wt * (float)o[u][j];
         }
     }
-    __shared__ float sm_acc[kCombineGroups][16][8];
-    __shared__ float sm_md[kCombineGroups][16][2];
-    sm_md[pg][t][0] = mref;
-    sm_md[pg][t][1] = den;
+    // the four groups: (0, 1) and (2, 3) first, then the pairs
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sm_acc[pg][t][j] = acc[j];
-    __syncthreads();
-    if (pg != 0) return;
-    float mstar = -INFINITY;
-    for (int i = 0; i < kCombineGroups; ++i) mstar = fmaxf(mstar, sm_md[i][t][0]);
-    float tot[8], dtot = 0.f;
+    for (int off = 16; off <= 32; off <<= 1) {
+        const float m2 = __shfl_xor(mref, off), d2 = __shfl_xor(den, off);
+        const float mx = fmaxf(mref, m2);
+        const float a0 = (mref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mref - mx);
+        const float a1 = (m2 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m2 - mx);
+        // (both lanes of a pair must add in the same order to end up with the same bits: the lower group first)
+        const bool low = (lane & off) == 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) tot[j] = 0.f;
-    for (int i = 0; i < kCombineGroups; ++i) {
-        const float mi = sm_md[i][t][0];
-        const float wt = (mi == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mi - mstar);
-        dtot += wt * sm_md[i][t][1];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) tot[j] += wt * sm_acc[i][t][j];
+        for (int j = 0; j < 8; ++j) {
+            const float x2 = __shfl_xor(acc[j], off);
+            acc[j] = low ? acc[j] * a0 + x2 * a1 : x2 * a1 + acc[j] * a0;
+        }
+        den = low ? den * a0 + d2 * a1 : d2 * a1 + den * a0;
+        mref = mx;
     }
-    const float inv = 1.0f / dtot;
+    if (pg != 0) return;
+    const float inv = 1.0f / den;
     bf16x8 r;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) r[j] = (__bf16)(tot[j] * inv);
+    for (int j = 0; j < 8; ++j) r[j] = (__bf16)(acc[j] * inv);
     *reinterpret_cast<bf16x8*>(p.out + ((int64_t)s * p.Hq + hq) * D + d8) = r;
 }
 
@@ -413,10 +414,12 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     for (int i = 0; i < n_streams; ++i) p.tile_prefix[i + 1] = p.tile_prefix[i] + (lens.v[i] + TR - 1) / TR;
     for (int i = n_streams; i < kMaxStreamsPerLaunch; ++i) p.tile_prefix[i + 1] = 0x7fffffff;  // never "before" a tile
     p.total_tiles = p.tile_prefix[n_streams];
-    // Shares of equal size in tiles, at most two workgroups per compute unit along x; the tuning
-    // knob gives the rows per share instead.
+    // Shares of equal size in tiles, one workgroup per compute unit (measured on cfg4: 256 workgroups
+    // 30.0 us, 512 30.7 us, and anything in between worse, because some compute units then hold two
+    // workgroups and the others one; fewer shares also mean fewer partial results to merge); the
+    // tuning knob gives the rows per share instead.
     const int groups_y = s.n_kv_heads / p.nh;
-    const int max_x = 512 / groups_y;
+    const int max_x = groups_y < 256 ? 256 / groups_y : 1;
     int64_t tiles_per_wg = g_tune_decode_chunk_rows ? g_tune_decode_chunk_rows / TR : (p.total_tiles + max_x - 1) / max_x;
     if (tiles_per_wg < p.nsub) tiles_per_wg = p.nsub;
     int64_t n_wg = (p.total_tiles + tiles_per_wg - 1) / tiles_per_wg;
@@ -425,6 +428,21 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     p.n_wg = (int)n_wg;
     p.share_q = p.total_tiles / p.n_wg;
     p.share_r = p.total_tiles % p.n_wg;
+    // which workgroups hold a stream: the largest w with first tile <= the stream's first / last tile
+    {
+        const int big = p.share_r * (p.share_q + 1);  // tiles held by the workgroups with one tile more
+        auto owner = [&](int tile) {
+            return tile < big ? tile / (p.share_q + 1) : p.share_r + (tile - big) / (p.share_q > 0 ? p.share_q : 1);
+        };
+        for (int i = 0; i < kMaxStreamsPerLaunch; ++i) {
+            p.first_wg[i] = 0;
+            p.n_wgs[i] = 1;
+            if (i < n_streams && p.tile_prefix[i + 1] > p.tile_prefix[i]) {
+                p.first_wg[i] = owner(p.tile_prefix[i]);
+                p.n_wgs[i] = owner(p.tile_prefix[i + 1] - 1) - p.first_wg[i] + 1;
+            }
+        }
+    }
     // the largest slot a wavefront can name is (n_wg - 1) + (n_streams - 1)
     const int64_t rows = partial_rows(s, n_streams);
     if ((int64_t)(p.n_wg + n_streams - 1) * s.n_kv_heads * p.nsub * p.G > rows) return hipErrorInvalidValue;
@@ -434,7 +452,7 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     decode_mfma_kernel<<<grid, kThreads, 0, st>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_combine_kernel<<<dim3(n_streams, s.n_q_heads), 16 * kCombineGroups, 0, st>>>(p);
+    decode_combine_kernel<<<dim3(n_streams, s.n_q_heads), 64, 0, st>>>(p);
     return hipGetLastError();
 }
 
