@@ -22,7 +22,7 @@
 //     accumulator rescale.
 // The row appended in this step is read from k_new / v_new (never from the slab, which the
 // wavefront that owns the stream's last tile updates on the side).  Every wavefront leaves a
-// normalised partial result (bf16) with its reference and sum; a second small kernel merges
+// normalised partial result (fp16 with a power-of-two scale per row) with its reference and sum; a second small kernel merges
 // them (a launch that follows another on the same stream starts within about a microsecond of
 // it; what the merge costs is its one round trip to memory).  Merging inside the attention
 // kernel, by the last wavefront of a stream to arrive, would need the partials of workgroups on
@@ -36,6 +36,8 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
@@ -53,8 +55,11 @@ struct DecodeParams {
     const __bf16* k_new;  // may be null
     const __bf16* v_new;
     __bf16* out;
-    __bf16* part_o;       // [slot][Hkv][nsub][G][D] normalised, slot = workgroup + stream of the segment
-    float* part_ml;       // [slot][Hkv][nsub][G][2]: reference (log2 units), sum
+    // partial results: [slot][Hkv][nsub][G][D] normalised, slot = workgroup + stream of the segment; stored
+    // as fp16 after multiplying the row by the power of two that brings its largest entry into
+    // [2^14, 2^15) (11 significant bits whatever the size of the values, in the bytes of bf16)
+    _Float16* part_o;
+    float* part_ml;       // [slot][Hkv][nsub][G][4]: reference (log2 units), sum, inverse of the row's scale, unused
     int64_t stream_stride;   // elements between streams in the slabs
     int n_streams, G, Hq, Hkv;
     int nh, nsub;            // KV heads per workgroup (1, 2 or 4) and sub-ranges per share (4 / nh)
@@ -258,28 +263,45 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
     // ---- this wavefront's result: lane (head = i16, kq) holds dims 16*db + 4*kq + e ----
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
-    if (i16 < p.G) {
+    {
         const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
-        __bf16* dst;
+        const int head = min(i16, p.G - 1);  // (lanes beyond the G heads compute along and store nothing)
         if (whole_stream) {
-            dst = p.out + ((int64_t)s * p.Hq + (int64_t)g * p.G + i16) * D + 4 * kq;
-        } else {
-            const int64_t pr = ((((int64_t)blockIdx.x + s) * p.Hkv + g) * p.nsub + sub) * p.G + i16;
-            dst = p.part_o + pr * D + 4 * kq;
-            if (kq == 0) {
-                p.part_ml[pr * 2 + 0] = m_ref;
-                p.part_ml[pr * 2 + 1] = l_run;
-            }
-        }
+            __bf16* dst = p.out + ((int64_t)s * p.Hq + (int64_t)g * p.G + head) * D + 4 * kq;
 #define VS_OUT(ACC, DB)                                                                  \
-        do {                                                                             \
-            bf16x4 r_;                                                                   \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) r_[j] = (__bf16)(ACC[j] * inv); \
-            *reinterpret_cast<bf16x4*>(dst + 16 * (DB)) = r_;                            \
-        } while (0)
-        VS_OUT(o0, 0); VS_OUT(o1, 1); VS_OUT(o2, 2); VS_OUT(o3, 3);
-        VS_OUT(o4, 4); VS_OUT(o5, 5); VS_OUT(o6, 6); VS_OUT(o7, 7);
+            do {                                                                         \
+                bf16x4 r_;                                                               \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j) r_[j] = (__bf16)(ACC[j] * inv); \
+                if (i16 < p.G) *reinterpret_cast<bf16x4*>(dst + 16 * (DB)) = r_;         \
+            } while (0)
+            VS_OUT(o0, 0); VS_OUT(o1, 1); VS_OUT(o2, 2); VS_OUT(o3, 3);
+            VS_OUT(o4, 4); VS_OUT(o5, 5); VS_OUT(o6, 6); VS_OUT(o7, 7);
 #undef VS_OUT
+        } else {
+            // the row's largest entry: this lane holds 32 of its dims, lanes +-16, +-32 the rest
+            float big = 0.f;
+#define VS_BIG(ACC) big = fmaxf(fmaxf(fmaxf(big, fabsf(ACC[0])), fmaxf(fabsf(ACC[1]), fabsf(ACC[2]))), fabsf(ACC[3]))
+            VS_BIG(o0); VS_BIG(o1); VS_BIG(o2); VS_BIG(o3); VS_BIG(o4); VS_BIG(o5); VS_BIG(o6); VS_BIG(o7);
+#undef VS_BIG
+            big *= inv;
+            big = fmaxf(big, __shfl_xor(big, 16));
+            big = fmaxf(big, __shfl_xor(big, 32));
+            const int expo = (int)((__float_as_uint(big) >> 23) & 255u);
+            const int se = min(max(127 + 14 + 127 - expo, 1), 254);  // biased exponent of the scale
+            const float scale = __uint_as_float((unsigned)se << 23), inv_scale = __uint_as_float((unsigned)(254 - se) << 23);
+            const int64_t pr = ((((int64_t)blockIdx.x + s) * p.Hkv + g) * p.nsub + sub) * p.G + head;
+            _Float16* dst = p.part_o + pr * D + 4 * kq;
+            if (kq == 0 && i16 < p.G) *reinterpret_cast<float4*>(p.part_ml + pr * 4) = make_float4(m_ref, l_run, inv_scale, 0.f);
+#define VS_OUT(ACC, DB)                                                                  \
+            do {                                                                         \
+                f16x4 r_;                                                                \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j) r_[j] = (_Float16)((ACC[j] * inv) * scale); \
+                if (i16 < p.G) *reinterpret_cast<f16x4*>(dst + 16 * (DB)) = r_;          \
+            } while (0)
+            VS_OUT(o0, 0); VS_OUT(o1, 1); VS_OUT(o2, 2); VS_OUT(o3, 3);
+            VS_OUT(o4, 4); VS_OUT(o5, 5); VS_OUT(o6, 6); VS_OUT(o7, 7);
+#undef VS_OUT
+        }
     }
     flat = first_of + seg_b;  // next segment: the next stream
   }
@@ -317,18 +339,18 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeParams p) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     for (int c0 = pg; c0 < n_parts; c0 += kCombineGroups * kCombineDepth) {
-        float2 ml[kCombineDepth];
-        bf16x8 o[kCombineDepth];
+        float4 ml[kCombineDepth];  // reference, sum, inverse scale of the stored row
+        f16x8 o[kCombineDepth];
 #pragma unroll
         for (int u = 0; u < kCombineDepth; ++u) {
             const int c = min(c0 + kCombineGroups * u, n_parts - 1);  // (past the end: a valid row, ignored below)
             const int64_t pr = row_of(c);
-            ml[u] = *reinterpret_cast<const float2*>(p.part_ml + pr * 2);
-            o[u] = *reinterpret_cast<const bf16x8*>(p.part_o + pr * D + d8);
+            ml[u] = *reinterpret_cast<const float4*>(p.part_ml + pr * 4);
+            o[u] = *reinterpret_cast<const f16x8*>(p.part_o + pr * D + d8);
         }
 #pragma unroll
         for (int u = 0; u < kCombineDepth; ++u)
-            if (c0 + kCombineGroups * u >= n_parts) ml[u] = make_float2(-INFINITY, 0.f);
+            if (c0 + kCombineGroups * u >= n_parts) ml[u] = make_float4(-INFINITY, 0.f, 0.f, 0.f);
         float mx = mref;
 #pragma unroll
         for (int u = 0; u < kCombineDepth; ++u) mx = fmaxf(mx, ml[u].x);
@@ -342,8 +364,9 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeParams p) {
         for (int u = 0; u < kCombineDepth; ++u) {
             const float wt = (ml[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[u].x - mx) * ml[u].y;
             den += wt;
+            const float wo = wt * ml[u].z;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] += wt * (float)o[u][j];
+            for (int j = 0; j < 8; ++j) acc[j] += wo * (float)o[u][j];
         }
     }
     // the four groups: (0, 1) and (2, 3) first, then the pairs
@@ -387,7 +410,7 @@ int64_t partial_rows(const vs_shape& s, int32_t n_streams) {
 }  // namespace
 
 size_t decode_mfma_workspace_bytes(const vs_shape& s, int32_t n_streams, int32_t /*max_rows*/) {
-    return (size_t)(partial_rows(s, n_streams) * (D * sizeof(__bf16) + 2 * sizeof(float)));
+    return (size_t)(partial_rows(s, n_streams) * (D * sizeof(_Float16) + 4 * sizeof(float)));
 }
 
 hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab, void* v_slab,
@@ -447,7 +470,7 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
     const int64_t rows = partial_rows(s, n_streams);
     if ((int64_t)(p.n_wg + n_streams - 1) * s.n_kv_heads * p.nsub * p.G > rows) return hipErrorInvalidValue;
     p.part_ml = (float*)workspace;
-    p.part_o = (__bf16*)(p.part_ml + rows * 2);
+    p.part_o = (_Float16*)(p.part_ml + rows * 4);
     const dim3 grid(p.n_wg, groups_y);
     decode_mfma_kernel<<<grid, kThreads, 0, st>>>(p);
     hipError_t e = hipGetLastError();

@@ -18,7 +18,7 @@
 //     of the rows).  Tiles are dealt to the (split, key group) lanes in whole tiles, equally
 //     many per lane; the tiles that hold frame rows are spread over the lanes and come first
 //     in their lane.  One wavefront per SIMD: it owns all 512 registers.
-//   * The per-workgroup partials (reference, sum, normalised accumulator in bf16) are merged
+//   * The per-workgroup partials (reference, sum, normalised accumulator as scaled fp16) are merged
 //     inside the launch by the last workgroup of a row tile to arrive (all splits of a row
 //     tile run on one XCD and count themselves in through its L2; nobody waits), or, where
 //     that is not possible, by a second small kernel.  Same sums, same order, same bits.
@@ -49,6 +49,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -72,8 +73,11 @@ struct PrefillParams {
     __bf16* out;
     // partial accumulators, normalised, in register order:
     // [nsplit*Hkv][row tiles][4 row groups of 32][4 dim blocks][2][64 lanes] x 8 bf16
-    __bf16* part_o;
-    float* part_ml;  // [nsplit*Hkv][m_pad][2]: reference (log2 units), row sum
+    // (stored as fp16 after multiplying the row by a power of two that brings its largest entry
+    // into [2^14, 2^15): 11 significant bits whatever the size of the values, in the bytes bf16
+    // would take; the power's inverse travels with the row's reference and sum)
+    _Float16* part_o;
+    float* part_ml;  // [nsplit*Hkv][m_pad][4]: reference (log2 units), row sum, inverse of the row's scale, unused
     __bf16* k_append_dst;    // frame rows append_first .. T-1 are copied here (null: none)
     __bf16* v_append_dst;
     int append_first;        // T - 1: the carrier alone; 0: every row of the run (a question)
@@ -115,6 +119,21 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
 // (dst is the same for the whole wavefront); completion is counted by vmcnt.
 __device__ __forceinline__ void load_to_lds16(const char* src, char* dst) {
     __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)dst, 16, 0, 0);
+}
+
+// Power of two that brings a row whose largest absolute entry is `big` into fp16's top binade
+// [2^14, 2^15), and its inverse; rows of zeros (and entries below 2^-112) take the largest power
+// there is, NaN and infinity pass through as they are.
+struct PartScale {
+    float scale, inv_scale;
+};
+__device__ __forceinline__ PartScale part_scale(float big) {
+    const int expo = (int)((__float_as_uint(big) >> 23) & 255u);           // biased exponent of big
+    const int se = min(max(127 + 14 + 127 - expo, 1), 254);                // biased exponent of the scale
+    PartScale r;
+    r.scale = __uint_as_float((unsigned)se << 23);
+    r.inv_scale = __uint_as_float((unsigned)(254 - se) << 23);
+    return r;
 }
 
 // The matrix instructions are issued from hand-scheduled blocks of inline assembly
@@ -595,21 +614,29 @@ void prefill_mfma_kernel(PrefillParams p) {
         } else {
             // normalised partials in register order: every store instruction writes 1 KB contiguous
             const int64_t unit = (int64_t)c * p.n_row_tiles + rt;
-            bf16x8* po = reinterpret_cast<bf16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane;
+            f16x8* po = reinterpret_cast<f16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane;
+            // the row's largest entry (this lane holds 64 of its 128 dims, lane ^ 32 the rest)
+            float big = 0.f;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) big = fmaxf(big, fabsf(oo[db][e]));
+            big *= inv;
+            big = fmaxf(big, xhalf(big));
+            const PartScale sc = part_scale(big);
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int h2 = 0; h2 < 2; ++h2) {
-                    bf16x8 wv;
+                    f16x8 wv;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) wv[j] = (__bf16)(oo[db][8 * h2 + j] * inv);
+                    for (int j = 0; j < 8; ++j) wv[j] = (_Float16)((oo[db][8 * h2 + j] * inv) * sc.scale);  // (the second product is exact)
                     if (p.arrivals) po[(db * 2 + h2) * 64] = wv;  // read back from L2 by this launch
                     else __builtin_nontemporal_store(wv, &po[(db * 2 + h2) * 64]);
                 }
             if (hi == 0) {
                 const int64_t prow = (int64_t)c * p.m_pad + r_mine[r];
-                p.part_ml[prow * 2 + 0] = m_row;
-                p.part_ml[prow * 2 + 1] = l_row;
+                *reinterpret_cast<float4*>(p.part_ml + prow * 4) = make_float4(m_row, l_row, sc.inv_scale, 0.f);
             }
         }
     };
@@ -687,24 +714,24 @@ void prefill_mfma_kernel(PrefillParams p) {
                 const bool row_ok = r_mine[r] < M;
                 const int t = row_ok ? div_small(r_mine[r], G, inv_G) : 0, hl = r_mine[r] - t * G;
                 __bf16* const orow = out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
-                const float* const ml0 = p.part_ml + ((int64_t)gf * p.m_pad + r_mine[r]) * 2;
-                const int64_t ml_step = (int64_t)HF * p.m_pad * 2;       // floats between splits
-                const bf16x8* const po0 = reinterpret_cast<const bf16x8*>(p.part_o) +
+                const float* const ml0 = p.part_ml + ((int64_t)gf * p.m_pad + r_mine[r]) * 4;
+                const int64_t ml_step = (int64_t)HF * p.m_pad * 4;       // floats between splits
+                const f16x8* const po0 = reinterpret_cast<const f16x8*>(p.part_o) +
                                           (((int64_t)gf * p.n_row_tiles + rt) * 4 + rg) * (8 * 64) + lane;
-                const int64_t po_step = (int64_t)HF * p.n_row_tiles * 4 * (8 * 64);  // bf16x8 between splits
+                const int64_t po_step = (int64_t)HF * p.n_row_tiles * 4 * (8 * 64);  // f16x8 between splits
                 // NS splits, the 8 pieces of a lane in PASSES rounds: everything of a round is
                 // requested before anything is used (a round trip to L2 is what this tail costs)
                 auto tail = [&](auto ns_tag, auto passes_tag) {
                     constexpr int NS = decltype(ns_tag)::value, PASSES = decltype(passes_tag)::value, PIECES = 8 / PASSES;
-                    float2 ml[NS];
-                    bf16x8 v[NS][PIECES];
+                    float4 ml[NS];  // reference, sum, inverse scale of the stored row
+                    f16x8 v[NS][PIECES];
                     // (addresses are worked out here, per case: an opaque copy of the bases keeps the
                     // compiler from preparing those of all cases ahead of the switch)
                     const float* mlb = ml0;
-                    const bf16x8* pob = po0;
+                    const f16x8* pob = po0;
                     asm volatile("" : "+v"(mlb), "+v"(pob));
 #pragma unroll
-                    for (int u = 0; u < NS; ++u) ml[u] = *reinterpret_cast<const float2*>(mlb + u * ml_step);
+                    for (int u = 0; u < NS; ++u) ml[u] = *reinterpret_cast<const float4*>(mlb + u * ml_step);
 #pragma unroll
                     for (int pass = 0; pass < PASSES; ++pass) {
 #pragma unroll
@@ -714,11 +741,12 @@ void prefill_mfma_kernel(PrefillParams p) {
                         float m_star = -INFINITY;
 #pragma unroll
                         for (int u = 0; u < NS; ++u) m_star = fmaxf(m_star, ml[u].x);
-                        float wgt[NS], denom = 0.f;
+                        float wgt[NS], denom = 0.f;  // wgt: what the stored (scaled) row is multiplied by
 #pragma unroll
                         for (int u = 0; u < NS; ++u) {
-                            wgt[u] = (ml[u].x != -INFINITY) ? __builtin_amdgcn_exp2f(ml[u].x - m_star) * ml[u].y : 0.f;
-                            denom += wgt[u];
+                            const float w = (ml[u].x != -INFINITY) ? __builtin_amdgcn_exp2f(ml[u].x - m_star) * ml[u].y : 0.f;
+                            denom += w;
+                            wgt[u] = w * ml[u].z;
                         }
                         const float inv = 1.0f / denom;
 #pragma unroll
@@ -787,22 +815,24 @@ __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
     // softmax, against the running reference m_run.
     float m_run = -INFINITY, denom = 0.f;
     for (int s0 = 0; s0 < p.nsplit; s0 += 8) {
-        float ms[8], ls[8];
-        bf16x8 v[8];
+        float ms[8], ls[8], isc[8];
+        f16x8 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             ms[u] = -INFINITY;
             ls[u] = 0.f;
+            isc[u] = 0.f;
             if (s0 + u < p.nsplit) {
                 const int c = (s0 + u) * HF + gf;
-                const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + ((int64_t)c * p.m_pad + rr) * 2);
+                const float4 ml = *reinterpret_cast<const float4*>(p.part_ml + ((int64_t)c * p.m_pad + rr) * 4);
                 ms[u] = ml.x;
                 ls[u] = ml.y;
+                isc[u] = ml.z;
                 const int64_t unit = (int64_t)c * p.n_row_tiles + rt;
-                v[u] = (reinterpret_cast<const bf16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane)[(db * 2 + h2) * 64];
+                v[u] = (reinterpret_cast<const f16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane)[(db * 2 + h2) * 64];
             } else {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[u][j] = (__bf16)0.f;
+                for (int j = 0; j < 8; ++j) v[u][j] = (_Float16)0.f;
             }
         }
         float m_new = m_run;
@@ -818,8 +848,9 @@ __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
         for (int u = 0; u < 8; ++u) {
             const float w = (ms[u] != -INFINITY) ? __builtin_amdgcn_exp2f(ms[u] - m_new) * ls[u] : 0.f;
             denom += w;
+            const float wo = w * isc[u];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] += w * (float)v[u][j];
+            for (int j = 0; j < 8; ++j) acc[j] += wo * (float)v[u][j];
         }
     }
     if (r >= p.M) return;
@@ -983,7 +1014,7 @@ size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens) {
     const int64_t M = (int64_t)max_q_tokens * G;
     const int64_t m_pad = ((M + BM - 1) / BM) * BM;
     const int64_t slots = (int64_t)kMaxPrefillSplits * s.n_kv_heads * m_pad;
-    return (size_t)(slots * (D * sizeof(__bf16) + 2 * sizeof(float)));
+    return (size_t)(slots * (D * sizeof(_Float16) + 4 * sizeof(float)));
 }
 
 // Bytes the partial results of a run of n_frames frames can take (the plan's own choice of
@@ -993,7 +1024,7 @@ size_t prefill_frames_workspace_bytes(const vs_shape& s, int32_t n_frames, int32
     const int64_t M = (int64_t)n_tokens * G;
     const int64_t m_pad = ((M + BM - 1) / BM) * BM;
     const int64_t slots = (int64_t)nsplit * s.n_kv_heads * n_frames * m_pad;
-    return (size_t)(slots * (D * sizeof(__bf16) + 2 * sizeof(float)));
+    return (size_t)(slots * (D * sizeof(_Float16) + 4 * sizeof(float)));
 }
 
 int prefill_frames_splits(const vs_shape& s, int32_t n_frames, int32_t n_tokens, int32_t len) {
@@ -1068,7 +1099,7 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
     }
     const int64_t slots = (int64_t)pl.nsplit * s.n_kv_heads * n_frames * pl.m_pad;
     p.part_ml = (float*)workspace;
-    p.part_o = (__bf16*)(p.part_ml + slots * 2);
+    p.part_o = (_Float16*)(p.part_ml + slots * 4);
     return pl.kvg == 1 ? launch_kvg<1>(p, pl, s.n_kv_heads, st) : launch_kvg<2>(p, pl, s.n_kv_heads, st);
 }
 

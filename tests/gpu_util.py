@@ -16,23 +16,23 @@ DEV = "cuda:0"
 #   relative to the oracle's own output, because with near-uniform softmax over thousands of
 #   rows the outputs are ~1e-2 in size and the absolute gates alone would pass an all-zero
 #   result:
-#     per element  |err| <= 2^-7 |ref| + 2e-2 rms(ref)
+#     per element  |err| <= 2^-7 |ref| + 1.5e-2 rms(ref)
 #     on average   mean|err| <= 5e-3 rms(ref)
-#   Error model behind them.  Three roundings to bf16 (8 significand bits, uniform in
+#   Error model behind them.  Two roundings to bf16 (8 significand bits, uniform in
 #   +-2^-9 |x|, std 1.13e-3 |x|) touch every output: (1) the output itself; (2) P before
 #   P.V (the prefill kernel sums the rounded P for the denominator, the decode kernel the
 #   unrounded P): as noise ~1.1e-3 rms, and when the probabilities are nearly equal their
 #   roundings line up and, where the denominator does not share them, shift the row by up
-#   to 2^-9 |x|; (3) when the keys are split over workgroups, each normalised partial result
-#   on its way through memory: nsplit independent terms, each weighted ~1/nsplit but
-#   ~sqrt(nsplit) larger than the final output, together again ~1.1e-3 rms.  Sum: a
-#   systematic part <= 2^-8 |x| and noise of std ~2e-3..2.5e-3 rms (measured mean|err| =
-#   1.7e-3..2e-3 rms), whose 5-sigma tail over ~1e6 elements is ~1.25e-2 rms; fp32
-#   accumulation terms are below 1e-6.  The gates are 2x the systematic part, 1.6x the noise
+#   to 2^-9 |x|.  When the keys are split over workgroups, each normalised partial result
+#   passes through memory as fp16 with a power-of-two scale per row (11 significand bits
+#   relative to the row's largest entry: std ~1.4e-4 of that entry, an eighth of a bf16
+#   rounding), which adds ~2e-4 rms in all.  Sum: a systematic part <= 2^-8 |x| and noise of
+#   std ~1.6e-3..2e-3 rms, whose 5-sigma tail over ~1e6 elements is ~1e-2 rms; fp32
+#   accumulation terms are below 1e-6.  The gates are 2x the systematic part, 1.5x the noise
 #   tail and ~2.5x the mean.  An all-zero output fails the element gate on ~98% of elements.
 F32_MAX_ABS = 1e-5
 BF16_MAX_ABS, BF16_MEAN_ABS = 2e-2, 2e-3
-BF16_ELEM_REL, BF16_ELEM_RMS, BF16_MEAN_REL_RMS = 2.0 ** -7, 2e-2, 5e-3
+BF16_ELEM_REL, BF16_ELEM_RMS, BF16_MEAN_REL_RMS = 2.0 ** -7, 1.5e-2, 5e-3
 
 
 def torch_dtype(shape_dtype):
