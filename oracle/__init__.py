@@ -9,6 +9,10 @@ from .vs_oracle import (  # noqa: F401
     bank_victim,
     compact_append,
     decode,
+    decoder_layer,
+    gated_unit,
+    linear,
+    rmsnorm,
     frame_prefill,
     frame_qkv,
     frames_prefill,

@@ -421,3 +421,92 @@ int vs_oracle_frame_qkv(const double *E, int64_t N, int64_t d, const double *W, 
     free(c);
     return rc;
 }
+
+/*
+ * The decoder layer around the attention.  The paper fixes only the attention (Eq. 1) and the
+ * projections Q = X W_Q, K = X W_K, V = X W_V (Section 3.1); for the rest it names the model it is
+ * built on (Section 4.1), whose layer is the usual pre-norm one.  Readings taken (listed in the
+ * design notes): RMS norm y_j = x_j g_j / sqrt(mean_k x_k^2 + eps); projections without bias; no
+ * position encoding; a feed-forward gated by SiLU, silu(a) = a / (1 + exp(-a)); residual sums
+ * around the attention block and around the feed-forward block.
+ */
+
+/* y[t][j] = x[t][j] * g[j] / sqrt((1/d) sum_k x[t][k]^2 + eps) */
+int vs_oracle_rmsnorm(const double *X, int64_t T, int64_t d, const double *g, double eps, double *Y) {
+    if (!X || !g || !Y || T < 1 || d < 1 || !(eps >= 0.0)) return VSO_ERR_ARG;
+    for (int64_t t = 0; t < T; ++t) {
+        double ss = 0.0;
+        for (int64_t k = 0; k < d; ++k) ss += X[(size_t)t * d + k] * X[(size_t)t * d + k];
+        const double r = sqrt(ss / (double)d + eps);
+        for (int64_t j = 0; j < d; ++j) Y[(size_t)t * d + j] = X[(size_t)t * d + j] * g[j] / r;
+    }
+    return VSO_OK;
+}
+
+/* Y[t][n] = sum_k X[t][k] W[n][k]: one row of K weights per output feature, summed in index order */
+int vs_oracle_linear(const double *X, int64_t T, int64_t K, const double *W, int64_t N, double *Y) {
+    if (!X || !W || !Y || T < 1 || K < 1 || N < 1) return VSO_ERR_ARG;
+#ifdef _OPENMP
+#pragma omp parallel for collapse(2) schedule(static)
+#endif
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int64_t k = 0; k < K; ++k) s += X[(size_t)t * K + k] * W[(size_t)n * K + k];
+            Y[(size_t)t * N + n] = s;
+        }
+    }
+    return VSO_OK;
+}
+
+/* Y[t][j] = silu(G[t][j]) * U[t][j] */
+int vs_oracle_gated_unit(const double *G, const double *U, int64_t T, int64_t F, double *Y) {
+    if (!G || !U || !Y || T < 1 || F < 1) return VSO_ERR_ARG;
+    for (int64_t i = 0; i < T * F; ++i) Y[i] = G[i] / (1.0 + exp(-G[i])) * U[i];
+    return VSO_OK;
+}
+
+/*
+ * One layer for one frame run H [T][d] (the frame's N visual tokens, then its carrier):
+ *   X1 = rmsnorm(H, g1);  Q = X1 Wq^T, K = X1 Wk^T, V = X1 Wv^T;
+ *   A  = frame prefill attention of (Q, K, V) over the L retained rows (vs_oracle_frame_prefill);
+ *   H1 = H + A Wo^T;  X2 = rmsnorm(H1, g2);  Hout = H1 + (silu(X2 Wg^T) * (X2 Wu^T)) Wd^T.
+ * Wq [Hq D][d], Wk, Wv [Hkv D][d], Wo [d][Hq D], Wg, Wu [F][d], Wd [d][F].  Kf, Vf [T][Hkv][D]
+ * receive the run's K and V rows (the caller keeps the last one, the carrier's, with
+ * vs_oracle_compact_append).
+ */
+int vs_oracle_decoder_layer(const double *H, int64_t T, int64_t d, int32_t Hq, int32_t Hkv, int32_t D, int64_t F,
+                            const double *g1, const double *Wq, const double *Wk, const double *Wv,
+                            const double *Wo, const double *g2, const double *Wg, const double *Wu,
+                            const double *Wd, double eps, const double *Kc, const double *Vc, int64_t L,
+                            double scale, double *Kf, double *Vf, double *Hout) {
+    if (!H || !g1 || !Wq || !Wk || !Wv || !Wo || !g2 || !Wg || !Wu || !Wd || !Kf || !Vf || !Hout) return VSO_ERR_ARG;
+    if (T < 1 || d < 1 || Hq < 1 || Hkv < 1 || D < 1 || F < 1 || L < 0) return VSO_ERR_ARG;
+    const int64_t nq = (int64_t)Hq * D, nk = (int64_t)Hkv * D;
+    double *x = (double *)malloc((size_t)T * d * sizeof(double));
+    double *q = (double *)malloc((size_t)T * nq * sizeof(double));
+    double *a = (double *)malloc((size_t)T * nq * sizeof(double));
+    double *h1 = (double *)malloc((size_t)T * d * sizeof(double));
+    double *gg = (double *)malloc((size_t)T * F * sizeof(double));
+    double *uu = (double *)malloc((size_t)T * F * sizeof(double));
+    double *o = (double *)malloc((size_t)T * d * sizeof(double));
+    int rc = (x && q && a && h1 && gg && uu && o) ? VSO_OK : VSO_ERR_NOMEM;
+    if (rc == VSO_OK) rc = vs_oracle_rmsnorm(H, T, d, g1, eps, x);
+    if (rc == VSO_OK) rc = vs_oracle_linear(x, T, d, Wq, nq, q);
+    if (rc == VSO_OK) rc = vs_oracle_linear(x, T, d, Wk, nk, Kf);
+    if (rc == VSO_OK) rc = vs_oracle_linear(x, T, d, Wv, nk, Vf);
+    if (rc == VSO_OK) rc = vs_oracle_frame_prefill(q, Kc, Vc, L, Kf, Vf, T, Hq, Hkv, D, scale, a, NULL);
+    if (rc == VSO_OK) rc = vs_oracle_linear(a, T, nq, Wo, d, o);
+    if (rc == VSO_OK) {
+        for (int64_t i = 0; i < T * d; ++i) h1[i] = H[i] + o[i];
+        rc = vs_oracle_rmsnorm(h1, T, d, g2, eps, x);
+    }
+    if (rc == VSO_OK) rc = vs_oracle_linear(x, T, d, Wg, F, gg);
+    if (rc == VSO_OK) rc = vs_oracle_linear(x, T, d, Wu, F, uu);
+    if (rc == VSO_OK) rc = vs_oracle_gated_unit(gg, uu, T, F, gg);
+    if (rc == VSO_OK) rc = vs_oracle_linear(gg, T, F, Wd, d, o);
+    if (rc == VSO_OK)
+        for (int64_t i = 0; i < T * d; ++i) Hout[i] = h1[i] + o[i];
+    free(x); free(q); free(a); free(h1); free(gg); free(uu); free(o);
+    return rc;
+}

@@ -23,6 +23,11 @@ class OracleError(RuntimeError):
 ERR_ARG, ERR_CAPACITY, ERR_NOMEM = 1, 2, 3
 
 
+def _need(ok, what):
+    if not ok:
+        raise OracleError(ERR_ARG, what)
+
+
 def _lib():
     global _LIB
     if _LIB is None:
@@ -43,6 +48,11 @@ def _lib():
         lib.vs_oracle_query_prefill.argtypes = [dp, dp, dp, i64, ip, dp, dp, i64, i32, i32, i32, f64, dp]
         lib.vs_oracle_frame_qkv.argtypes = [dp, i64, i64, dp, i64, dp]
         lib.vs_oracle_bank_victim.argtypes = [dp, i64, i64, dp, i32, dp, ip]
+        lib.vs_oracle_rmsnorm.argtypes = [dp, i64, i64, dp, f64, dp]
+        lib.vs_oracle_linear.argtypes = [dp, i64, i64, dp, i64, dp]
+        lib.vs_oracle_gated_unit.argtypes = [dp, dp, i64, i64, dp]
+        lib.vs_oracle_decoder_layer.argtypes = [dp, i64, i64, i32, i32, i32, i64, dp, dp, dp, dp, dp, dp, dp, dp, dp, f64,
+                                                dp, dp, i64, f64, dp, dp, dp]
         lib.vs_oracle_bank_apply.argtypes = [dp, i64, i64, i64, i64, i64, i64, dp, ip]
         _LIB = lib
     return _LIB
@@ -234,3 +244,64 @@ def frame_qkv(E, W, n_q_heads, n_kv_heads, head_dim):
     return (Y[:, :nq].reshape(N + 1, n_q_heads, head_dim).copy(),
             Y[:, nq:nq + nk].reshape(N + 1, n_kv_heads, head_dim).copy(),
             Y[:, nq + nk:].reshape(N + 1, n_kv_heads, head_dim).copy())
+
+
+def rmsnorm(X, g, eps):
+    """Y[t][j] = X[t][j] g[j] / sqrt(mean_k X[t][k]^2 + eps)  (reading of the backbone's norm)."""
+    X, g = _c(X), _c(g)
+    T, d = X.shape
+    _need(g.shape == (d,), "rmsnorm")
+    Y = np.empty_like(X)
+    rc = _lib().vs_oracle_rmsnorm(_p(X), T, d, _p(g), float(eps), _p(Y))
+    if rc:
+        raise OracleError(rc, "rmsnorm")
+    return Y
+
+
+def linear(X, W):
+    """Y = X W^T: X [T][K], W [N][K] (one row of weights per output feature; Section 3.1)."""
+    X, W = _c(X), _c(W)
+    T, K = X.shape
+    N = W.shape[0]
+    _need(W.shape == (N, K), "linear")
+    Y = np.empty((T, N), dtype=np.float64)
+    rc = _lib().vs_oracle_linear(_p(X), T, K, _p(W), N, _p(Y))
+    if rc:
+        raise OracleError(rc, "linear")
+    return Y
+
+
+def gated_unit(G, U):
+    """silu(G) * U, silu(a) = a / (1 + exp(-a))."""
+    G, U = _c(G), _c(U)
+    _need(G.shape == U.shape and G.ndim == 2, "gated_unit")
+    Y = np.empty_like(G)
+    rc = _lib().vs_oracle_gated_unit(_p(G), _p(U), G.shape[0], G.shape[1], _p(Y))
+    if rc:
+        raise OracleError(rc, "gated_unit")
+    return Y
+
+
+def decoder_layer(H, g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd, eps, Kc, Vc, n_q_heads, n_kv_heads, head_dim, scale):
+    """One pre-norm decoder layer for one frame run H [T][d] over the retained rows Kc, Vc [L][Hkv][D]
+    (None for an empty cache).  Returns (H_out [T][d], K_f, V_f [T][Hkv][D])."""
+    H = _c(H)
+    T, d = H.shape
+    nq, nk = n_q_heads * head_dim, n_kv_heads * head_dim
+    g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd = (_c(a) for a in (g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd))
+    F = Wg.shape[0]
+    _need(Wq.shape == (nq, d) and Wk.shape == (nk, d) and Wv.shape == (nk, d) and Wo.shape == (d, nq), "decoder_layer")
+    _need(Wg.shape == (F, d) and Wu.shape == (F, d) and Wd.shape == (d, F) and g1.shape == (d,) and g2.shape == (d,), "decoder_layer")
+    L = 0 if Kc is None else Kc.shape[0]
+    if L:
+        Kc, Vc = _c(Kc), _c(Vc)
+    Kf = np.empty((T, n_kv_heads, head_dim), dtype=np.float64)
+    Vf = np.empty_like(Kf)
+    Hout = np.empty_like(H)
+    rc = _lib().vs_oracle_decoder_layer(_p(H), T, d, n_q_heads, n_kv_heads, head_dim, F, _p(g1), _p(Wq), _p(Wk), _p(Wv),
+                                        _p(Wo), _p(g2), _p(Wg), _p(Wu), _p(Wd), float(eps),
+                                        _p(Kc) if L else None, _p(Vc) if L else None, L, float(scale), _p(Kf), _p(Vf),
+                                        _p(Hout))
+    if rc:
+        raise OracleError(rc, "decoder_layer")
+    return Hout, Kf, Vf

@@ -591,6 +591,94 @@ def pin_frame_rows_and_their_projections(impl):
     _close(O[N, h], np.array(want), 1e-12, "carrier's attention from E and W")
 
 
+def pin_decoder_layer(impl):
+    """The layer around the attention (Section 4.1 names the backbone; Section 3.1 the projections).
+    Pins of the readings taken: RMS norm, bias-free projections as X W^T, SiLU-gated feed-forward,
+    residual sums around both blocks."""
+    r = _rng(71)
+    # --- RMS norm: closed forms
+    x = np.array([[3.0, -4.0, 0.0, 0.0]])                     # mean of squares 25/4: rms 5/2
+    _close(impl.rmsnorm(x, np.ones(4), 0.0), x / 2.5, 1e-15, "rms of (3, -4, 0, 0) is 5/2")
+    _close(impl.rmsnorm(x, np.array([2.0, 1.0, 7.0, 7.0]), 0.0), np.array([[2.4, -1.6, 0.0, 0.0]]), 1e-15, "gain per feature")
+    _close(impl.rmsnorm(np.array([[1.0, 1.0, 1.0, 1.0]]), np.ones(4), 3.0), np.full((1, 4), 0.5), 1e-15, "eps under the root: 1/sqrt(1+3)")
+    X = r.normal(size=(5, 12))
+    g = r.normal(size=12)
+    Y = impl.rmsnorm(X, g, 0.0)
+    _close(impl.rmsnorm(7.5 * X, g, 0.0), Y, 1e-13, "scale invariance without eps")
+    _close(np.sqrt(np.mean((Y / g) ** 2, axis=1)), np.ones(5), 1e-13, "unit rms before the gain")
+    for t in range(5):                                           # rows are independent, brute force
+        rms = math.sqrt(math.fsum(v * v for v in X[t]) / 12 + 1e-3)
+        _close(impl.rmsnorm(X, g, 1e-3)[t], np.array([X[t, j] * g[j] / rms for j in range(12)]), 1e-14, f"row {t}")
+    # --- linear: brute force, identity, and weights that pick single features (transposition shows)
+    W = r.normal(size=(7, 12))
+    L = impl.linear(X, W)
+    assert L.shape == (5, 7)
+    for t in range(5):
+        for n in range(7):
+            assert abs(L[t, n] - math.fsum(X[t, k] * W[n, k] for k in range(12))) < 1e-13
+    pick = np.zeros((3, 12))
+    pick[0, 11], pick[1, 0], pick[2, 5] = 1.0, 1.0, 1.0
+    _close(impl.linear(X, pick), X[:, [11, 0, 5]], 1e-15, "rows of W pick features 11, 0, 5")
+    # --- gated unit: silu(a) - silu(-a) = a; silu(ln 3) = (3/4) ln 3; silu(0) = 0; the second factor multiplies
+    a = r.normal(size=(2, 6))
+    _close(impl.gated_unit(a, np.ones_like(a)) - impl.gated_unit(-a, np.ones_like(a)), a, 1e-14, "silu is x sigmoid(x)")
+    _close(impl.gated_unit(np.array([[math.log(3.0), 0.0]]), np.array([[2.0, 5.0]])), np.array([[1.5 * math.log(3.0), 0.0]]), 1e-15,
+           "silu(ln 3) = 3/4 ln 3")
+    # --- the layer.  Tiny shape, everything worked out with fsum from the definitions above.
+    T, d, Hq, Hkv, D, F, Lc = 3, 4, 2, 1, 2, 3, 2
+    H = r.normal(size=(T, d))
+    g1, g2 = r.normal(size=d), r.normal(size=d)
+    Wq, Wk, Wv = r.normal(size=(Hq * D, d)), r.normal(size=(Hkv * D, d)), r.normal(size=(Hkv * D, d))
+    Wo, Wg, Wu, Wd = r.normal(size=(d, Hq * D)), r.normal(size=(F, d)), r.normal(size=(F, d)), r.normal(size=(d, F))
+    Kc, Vc = r.normal(size=(Lc, Hkv, D)), r.normal(size=(Lc, Hkv, D))
+    eps, scale = 1e-2, 0.6
+    Hout, Kf, Vf = impl.decoder_layer(H, g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd, eps, Kc, Vc, Hq, Hkv, D, scale)
+
+    def norm(M, gain):
+        return [[M[t][j] * gain[j] / math.sqrt(math.fsum(v * v for v in M[t]) / len(M[t]) + eps) for j in range(len(M[t]))]
+                for t in range(len(M))]
+
+    def mat(M, Wm):
+        return [[math.fsum(M[t][k] * Wm[n][k] for k in range(len(M[t]))) for n in range(len(Wm))] for t in range(len(M))]
+    x1 = norm(H.tolist(), g1)
+    q, k, v = mat(x1, Wq), mat(x1, Wk), mat(x1, Wv)
+    _close(Kf.reshape(T, -1), np.array(k), 1e-13, "the run's K rows")
+    _close(Vf.reshape(T, -1), np.array(v), 1e-13, "the run's V rows")
+    Q3 = [[[q[t][h * D + j] for j in range(D)] for h in range(Hq)] for t in range(T)]
+    Kall = Kc.tolist() + [[[k[t][j] for j in range(D)]] for t in range(T)]
+    Vall = Vc.tolist() + [[[v[t][j] for j in range(D)]] for t in range(T)]
+    att, _ = brute_attention(Q3, Kall, Vall, [Lc + t + 1 for t in range(T)], scale)
+    aflat = [[att[t][h][j] for h in range(Hq) for j in range(D)] for t in range(T)]
+    o = mat(aflat, Wo)
+    h1 = [[H[t][j] + o[t][j] for j in range(d)] for t in range(T)]
+    x2 = norm(h1, g2)
+    gg, uu = mat(x2, Wg), mat(x2, Wu)
+    act = [[gg[t][f] / (1.0 + math.exp(-gg[t][f])) * uu[t][f] for f in range(F)] for t in range(T)]
+    dn = mat(act, Wd)
+    want = [[h1[t][j] + dn[t][j] for j in range(d)] for t in range(T)]
+    _close(Hout, np.array(want), 1e-12, "layer output from the definitions")
+    # with the two output projections at zero both blocks add nothing: the residual path alone
+    Hz, _, _ = impl.decoder_layer(H, g1, Wq, Wk, Wv, 0 * Wo, g2, Wg, Wu, 0 * Wd, eps, Kc, Vc, Hq, Hkv, D, scale)
+    _close(Hz, H, 0.0, "zero output projections leave the hidden state alone")
+    # causality survives the layer: a later token changes no earlier row; the retained rows reach all rows
+    H2 = H.copy()
+    H2[T - 1] += 1.0
+    Hc, _, _ = impl.decoder_layer(H2, g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd, eps, Kc, Vc, Hq, Hkv, D, scale)
+    assert np.array_equal(Hc[:T - 1], Hout[:T - 1]) and not np.allclose(Hc[T - 1], Hout[T - 1])
+    Hk, _, _ = impl.decoder_layer(H, g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd, eps, Kc + 0.5, Vc, Hq, Hkv, D, scale)
+    assert all(not np.allclose(Hk[t], Hout[t]) for t in range(T))
+    # an empty cache is allowed
+    He, _, _ = impl.decoder_layer(H[:1], g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd, eps, None, None, Hq, Hkv, D, scale)
+    x1e = norm(H[:1].tolist(), g1)
+    ve = mat(x1e, Wv)[0]                       # one token, one key: the attention returns its own V row, for both heads
+    oe = mat([[ve[j] for _ in range(Hq) for j in range(D)]], Wo)[0]
+    h1e = [[H[0][j] + oe[j] for j in range(d)]]
+    x2e = norm(h1e, g2)
+    ge, ue = mat(x2e, Wg)[0], mat(x2e, Wu)[0]
+    acte = [[ge[f] / (1.0 + math.exp(-ge[f])) * ue[f] for f in range(F)]]
+    _close(He, np.array([[h1e[0][j] + mat(acte, Wd)[0][j] for j in range(d)]]), 1e-12, "one token, empty cache")
+
+
 ALL_PINS = [
     pin_golden_rational,
     pin_uniform_scores_mean_of_visible,
@@ -612,4 +700,5 @@ ALL_PINS = [
     pin_frames_with_semantic_mask,
     pin_question_after_the_video,
     pin_frame_rows_and_their_projections,
+    pin_decoder_layer,
 ]

@@ -130,6 +130,51 @@ class NumpyImpl:
         return (parts[0].reshape(N + 1, n_q_heads, head_dim).copy(), parts[1].reshape(N + 1, n_kv_heads, head_dim).copy(),
                 parts[2].reshape(N + 1, n_kv_heads, head_dim).copy())
 
+    def rmsnorm(self, X, g, eps):
+        X, g = np.asarray(X, dtype=np.float64), np.asarray(g, dtype=np.float64)
+        ms = (X ** 2).sum(axis=1, keepdims=True) if self.bug == "norm_sum_not_mean" else (X ** 2).mean(axis=1, keepdims=True)
+        if self.bug == "norm_centres":
+            X = X - X.mean(axis=1, keepdims=True)
+        if self.bug == "norm_eps_outside_root":
+            return X * g / (np.sqrt(ms) + eps)
+        if self.bug == "norm_no_gain":
+            return X / np.sqrt(ms + eps)
+        return X * g / np.sqrt(ms + eps)
+
+    def linear(self, X, W):
+        X, W = np.asarray(X, dtype=np.float64), np.asarray(W, dtype=np.float64)
+        if self.bug == "linear_weights_transposed":
+            return X @ W.reshape(W.shape[1], W.shape[0])
+        return X @ W.T
+
+    def gated_unit(self, G, U):
+        G, U = np.asarray(G, dtype=np.float64), np.asarray(U, dtype=np.float64)
+        if self.bug == "gate_is_sigmoid_only":
+            return U / (1.0 + np.exp(-G))
+        if self.bug == "gate_acts_on_value":
+            return G * (U / (1.0 + np.exp(-U)))
+        if self.bug == "gate_relu":
+            return np.maximum(G, 0.0) * U
+        return G / (1.0 + np.exp(-G)) * U
+
+    def decoder_layer(self, H, g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd, eps, Kc, Vc, n_q_heads, n_kv_heads, head_dim, scale):
+        H = np.asarray(H, dtype=np.float64)
+        T = H.shape[0]
+        x1 = H if self.bug == "layer_no_first_norm" else self.rmsnorm(H, g1, eps)
+        q = self.linear(x1, Wq).reshape(T, n_q_heads, head_dim)
+        k = self.linear(x1, Wk).reshape(T, n_kv_heads, head_dim)
+        v = self.linear(x1, Wv).reshape(T, n_kv_heads, head_dim)
+        a = self.frame_prefill(q, Kc, Vc, k, v, scale).reshape(T, -1)
+        o = self.linear(a, Wo)
+        h1 = o if self.bug == "layer_no_attention_residual" else H + o
+        x2 = self.rmsnorm(H if self.bug == "layer_post_norm_of_input" else h1, g1 if self.bug == "layer_same_gain_twice" else g2, eps)
+        act = self.gated_unit(self.linear(x2, Wg), self.linear(x2, Wu))
+        dn = self.linear(act, Wd)
+        out = (H + dn) if self.bug == "layer_second_residual_from_input" else (h1 + dn)
+        if self.bug == "layer_no_mlp_residual":
+            out = dn
+        return out, k, v
+
     def mean_pool(self, E):
         E = np.asarray(E, dtype=np.float64)
         if self.bug == "pool_sum":
@@ -218,7 +263,10 @@ BUGS = ["gqa_interleaved", "scores_from_v", "no_scale", "scale_squared", "no_nor
         "run_sees_later_carriers", "question_rows_off_by_one", "question_keeps_last_token_only",
         "question_not_causal", "question_blind_to_itself", "question_length_plus_one", "question_no_capacity_check",
         "proj_carrier_is_sum", "proj_carrier_is_last_token", "proj_carrier_first", "proj_weights_transposed",
-        "proj_k_and_v_swapped", "proj_heads_interleaved"]
+        "proj_k_and_v_swapped", "proj_heads_interleaved",
+        "norm_sum_not_mean", "norm_centres", "norm_eps_outside_root", "norm_no_gain", "linear_weights_transposed",
+        "gate_is_sigmoid_only", "gate_acts_on_value", "gate_relu", "layer_no_first_norm", "layer_no_attention_residual",
+        "layer_post_norm_of_input", "layer_same_gain_twice", "layer_second_residual_from_input", "layer_no_mlp_residual"]
 
 
 def _failures(impl):
@@ -248,6 +296,33 @@ def test_oracle_matches_numpy_evaluation_midsize():
     a, pa = oracle.attention(Q, K, V, vis, 0.25, return_probs=True)
     b, pb = NumpyImpl().attention(Q, K, V, vis, 0.25, return_probs=True)
     assert np.abs(a - b).max() < 1e-14 and np.abs(pa - pb).max() < 1e-15
+
+
+def test_oracle_layer_matches_numpy_evaluation_midsize():
+    """The layer, two independently written evaluations, at a shape with grouped heads and a ragged cache."""
+    r = np.random.default_rng(6)
+    T, d, Hq, Hkv, D, F, L = 11, 24, 6, 2, 8, 40, 13
+    H, g1, g2 = r.normal(size=(T, d)), r.normal(size=d), r.normal(size=d)
+    Wq, Wk, Wv = (r.normal(size=(n, d)) / 5 for n in (Hq * D, Hkv * D, Hkv * D))
+    Wo, Wg, Wu, Wd = r.normal(size=(d, Hq * D)) / 7, r.normal(size=(F, d)) / 5, r.normal(size=(F, d)) / 5, r.normal(size=(d, F)) / 6
+    Kc, Vc = r.normal(size=(L, Hkv, D)), r.normal(size=(L, Hkv, D))
+    a = oracle.decoder_layer(H, g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd, 1e-6, Kc, Vc, Hq, Hkv, D, 0.3)
+    b = NumpyImpl().decoder_layer(H, g1, Wq, Wk, Wv, Wo, g2, Wg, Wu, Wd, 1e-6, Kc, Vc, Hq, Hkv, D, 0.3)
+    for x, y in zip(a, b):
+        assert x.shape == y.shape and np.abs(x - y).max() < 1e-12
+
+
+def test_oracle_layer_rejects_bad_arguments():
+    H, g = np.zeros((2, 4)), np.ones(4)
+    W = np.zeros((4, 4))
+    with pytest.raises(oracle.OracleError):  # projection width is not heads x head_dim
+        oracle.decoder_layer(H, g, np.zeros((6, 4)), W[:2], W[:2], W, g, W, W, W, 1e-6, None, None, 2, 1, 2, 1.0)
+    with pytest.raises(oracle.OracleError):  # gain of the wrong length
+        oracle.rmsnorm(H, np.ones(3), 1e-6)
+    with pytest.raises(oracle.OracleError):  # inner sizes differ
+        oracle.linear(H, np.zeros((3, 5)))
+    with pytest.raises(oracle.OracleError):  # the two halves of the gated unit differ in shape
+        oracle.gated_unit(np.zeros((2, 3)), np.zeros((2, 4)))
 
 
 def test_oracle_rejects_bad_arguments():
