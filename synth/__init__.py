@@ -15,4 +15,6 @@ from .gen import (  # noqa: F401
     decode_lengths,
     cfg1_inputs,
     to_f64,
+    hidden_rows,
+    layer_weights,
 )

@@ -7,13 +7,23 @@ import numpy as np
 import torch
 
 _KIND = {"cache_k": 1, "cache_v": 2, "q": 3, "k_f": 4, "v_f": 5, "e": 6,
-         "dq": 7, "dk": 8, "dv": 9, "lens": 10}
+         "dq": 7, "dk": 8, "dv": 9, "lens": 10, "h": 11, "w_q": 12, "w_k": 13, "w_v": 14, "w_o": 15,
+         "w_gate": 16, "w_up": 17, "w_down": 18, "norm1": 19, "norm2": 20}
 
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 
 def _seed(base, kind, a=0, b=0):
-    return ((int(base) & 0xFFFF) << 44) | (_KIND[kind] << 40) | ((int(a) & 0xFFFFF) << 16) | (int(b) & 0xFFFF)
+    """One seed per (config seed, tensor kind, frame/step, layer).  The fields are packed and then
+    mixed (the 64-bit finaliser of splitmix64), because torch's host generator keys its stream on
+    the low 32 bits of the seed alone: unmixed, tensors that differ only in the high fields would
+    share their draws."""
+    x = ((int(base) & 0xFFFF) << 45) | (_KIND[kind] << 40) | ((int(a) & 0xFFFFF) << 16) | (int(b) & 0xFFFF)
+    m = (1 << 64) - 1
+    x = (x + 0x9E3779B97F4A7C15) & m
+    x = ((x ^ (x >> 30)) * 0xBF58476D1CE4E5B9) & m
+    x = ((x ^ (x >> 27)) * 0x94D049BB133111EB) & m
+    return (x ^ (x >> 31)) & 0x7FFFFFFFFFFFFFFF
 
 
 def draw(seed, shape, sigma, dtype):
@@ -99,3 +109,22 @@ def carrier_embeddings(seed, n, d, dtype):
         cur = 0.8 * cur + 0.6 * step * torch.randn(d, generator=g)
         e[t] = cur
     return e.to(_TORCH_DTYPE[dtype]).contiguous()
+
+
+def hidden_rows(base_seed, n_tokens, d_model, sigma=1.0, frame=0, layer=0, dtype="bf16"):
+    """Hidden states [T][d] of one frame run entering a decoder layer (synthetic)."""
+    return draw(_seed(base_seed, "h", frame, layer), (n_tokens, d_model), sigma, dtype)
+
+
+def layer_weights(base_seed, shape, d_model, d_ff, layer=0, dtype="bf16"):
+    """Random-init weights of one decoder layer, one row per output feature: w_q [Hq D][d], w_k, w_v
+    [Hkv D][d], w_o [d][Hq D], w_gate, w_up [F][d], w_down [d][F], each N(0, 1/fan_in) so that
+    activations keep the size of their inputs; the two norm gains are 1 + N(0, 0.1^2)."""
+    nq, nk = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    dims = {"w_q": (nq, d_model), "w_k": (nk, d_model), "w_v": (nk, d_model), "w_o": (d_model, nq),
+            "w_gate": (d_ff, d_model), "w_up": (d_ff, d_model), "w_down": (d_model, d_ff)}
+    w = {name: draw(_seed(base_seed, name, 0, layer), dim, dim[1] ** -0.5, dtype) for name, dim in dims.items()}
+    for name in ("norm1", "norm2"):
+        g = torch.Generator(device="cpu").manual_seed(_seed(base_seed, name, 0, layer))
+        w[name] = (1.0 + 0.1 * torch.randn(d_model, generator=g, dtype=torch.float32)).to(_TORCH_DTYPE[dtype]).contiguous()
+    return w

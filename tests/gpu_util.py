@@ -18,8 +18,9 @@ DEV = "cuda:0"
 #   result:
 #     per element  |err| <= 2^-7 |ref| + 1.5e-2 rms(ref)
 #     on average   mean|err| <= 5e-3 rms(ref)
-#   Error model behind them.  Two roundings to bf16 (8 significand bits, uniform in
-#   +-2^-9 |x|, std 1.13e-3 |x|) touch every output: (1) the output itself; (2) P before
+#   Error model behind them.  Two roundings to bf16 (8 significand bits: at most 2^-8 |x|,
+#   std between 1.13e-3 |x| and 2.26e-3 |x| depending on where x lies in its binade) touch every
+#   output: (1) the output itself; (2) P before
 #   P.V (the prefill kernel sums the rounded P for the denominator, the decode kernel the
 #   unrounded P): as noise ~1.1e-3 rms, and when the probabilities are nearly equal their
 #   roundings line up and, where the denominator does not share them, shift the row by up
@@ -52,7 +53,14 @@ def workspace(s, max_tokens, max_rows, n_streams):
     return vs.make_workspace(vs_shape(s), max_tokens, max_rows, n_streams, DEV)
 
 
-def check_close(gpu, ref, dtype, what=""):
+def check_close(gpu, ref, dtype, what="", absolute=True, abs_v_out=None):
+    """absolute=False drops the two absolute bf16 gates, which are stated for the benchmark's value
+    distribution (outputs of size ~1e-2..1e-1), for inputs of another size; the relative ones stay.
+    abs_v_out: the oracle's output for the same inputs with |V| in place of V, i.e. sum_i p_i |v_i|
+    per element.  Rounding every p_i to bf16 moves an output by at most 2^-8 of that sum, whatever
+    the number of keys; with few visible keys (the first tokens over a nearly empty cache) single
+    terms p_i v_i are far larger than the rms of the whole output, the statistical element gate
+    above does not describe them, and this worst-case bound takes its place where it is the larger."""
     got = gpu.detach().to(torch.float64).cpu().numpy()
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, f"{what}: shape {got.shape} vs {ref.shape}"
@@ -63,8 +71,11 @@ def check_close(gpu, ref, dtype, what=""):
         assert mx <= F32_MAX_ABS, f"{what}: max-abs {mx:.3e} > {F32_MAX_ABS}"
     else:
         rms = float(np.sqrt(np.mean(ref * ref)))
-        assert mx <= BF16_MAX_ABS and mean <= BF16_MEAN_ABS, f"{what}: max-abs {mx:.3e}, mean-abs {mean:.3e}"
-        worst = float((err / (BF16_ELEM_REL * np.abs(ref) + BF16_ELEM_RMS * rms)).max())
+        assert not absolute or (mx <= BF16_MAX_ABS and mean <= BF16_MEAN_ABS), f"{what}: max-abs {mx:.3e}, mean-abs {mean:.3e}"
+        floor = BF16_ELEM_RMS * rms
+        if abs_v_out is not None:
+            floor = np.maximum(floor, 1.05 * 2.0 ** -8 * np.asarray(abs_v_out, dtype=np.float64))
+        worst = float((err / (BF16_ELEM_REL * np.abs(ref) + floor)).max())
         assert worst <= 1.0, f"{what}: element error {worst:.2f}x the relative gate (max-abs {mx:.3e}, rms {rms:.3e})"
         assert mean <= BF16_MEAN_REL_RMS * rms, f"{what}: mean-abs {mean:.3e} vs rms {rms:.3e}"
         print(f"[parity] {what}: max-abs {mx:.2e} mean-abs {mean:.2e} rms {rms:.2e} gate-use {worst:.2f} "

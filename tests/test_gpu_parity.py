@@ -950,7 +950,9 @@ def test_prefill_random_shapes_sweep():
         q, kf, vf = frame_inputs(700 + case, s, T, 0.5, q_gain=gain)
         out, cache, row = run_prefill(s, hk, hv, L, q, kf, vf, fused=bool(case & 1))
         ref = oracle_prefill_rows(s, q, hk, hv, L, kf, vf)
-        check_close(out, ref, "bf16", f"case {case}: Hq/Hkv {hq}/{hkv} L={L} T={T} splits={splits} kv_groups={kvg} gain={gain}")
+        bound = oracle_prefill_rows(s, q, hk, hv.abs(), L, kf, vf.abs())
+        check_close(out, ref, "bf16", f"case {case}: Hq/Hkv {hq}/{hkv} L={L} T={T} splits={splits} kv_groups={kvg} gain={gain}",
+                    abs_v_out=bound)
         if case & 1:
             assert row == L and cache.len == L + 1 and same_bits(cache.k[L], kf[T - 1]) and same_bits(cache.v[L], vf[T - 1])
 
@@ -982,7 +984,9 @@ def test_runs_of_frames_random_shapes_sweep():
         out = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
         vs.frames_prefill_attn(vs_shape(s), cache, q.to(DEV), kf.to(DEV), vf.to(DEV), out, ws)
         torch.cuda.synchronize()
-        check_close(out, ref, "bf16", f"case {case}: Hq/Hkv {hq}/{hkv} F={F} T={T} L={L} splits={splits}")
+        bound = oracle.frames_prefill(to_f64(q), to_f64(hk) if L else None, np.abs(to_f64(hv)) if L else None, to_f64(kf),
+                                      np.abs(to_f64(vf)), scale32(s))
+        check_close(out, ref, "bf16", f"case {case}: Hq/Hkv {hq}/{hkv} F={F} T={T} L={L} splits={splits}", abs_v_out=bound)
         assert cache.len == L + F and same_bits(cache.k[L:], kf[:, T - 1]) and same_bits(cache.v[L:], vf[:, T - 1])
 
 
