@@ -347,6 +347,65 @@ vs_status vs_frame_qkv_project(const vs_shape *shape, const void *e, int32_t n_v
                                int32_t d_model, const void *w_qkv, void *q_out, void *k_out,
                                void *v_out, void *c_out, void *hip_stream);
 
+/*
+ * The rest of the decoder layer around the attention (Section 4.1 names the backbone the method is
+ * built on; Section 3.1 writes Q = X W_Q, K = X W_K, V = X W_V).  The paper gives none of the
+ * layer's details; taken here: the pre-norm layer of that backbone family -- RMS norm, projections
+ * without bias, a feed-forward gated by SiLU, residual sums -- and no position encoding (the
+ * attention entry points take Q and K as they come).  bf16 storage, fp32 arithmetic, one rounding
+ * per tensor written.  All for runs of at most 192 rows (one frame: N visual tokens + carrier).
+ */
+
+/* out [n_rows][d] = x * gamma / sqrt(mean_j x_j^2 + eps), row by row.  d a multiple of 8. */
+vs_status vs_rmsnorm(const void *x, const void *gamma, int32_t n_rows, int32_t d, float eps, void *out,
+                     void *hip_stream);
+
+typedef enum {
+    VS_LINEAR_STORE = 0,    /* out [n_rows][n] = x w^T */
+    VS_LINEAR_RESIDUAL = 1, /* out [n_rows][n] = residual + x w^T */
+    VS_LINEAR_GATED = 2     /* out [n_rows][n/2]: out_j = silu(x w_{2j}) * (x w_{2j+1}), silu(g) = g / (1 + exp(-g)):
+                               the rows of w alternate gate and value projections */
+} vs_linear_mode;
+
+/*
+ * out = x w^T for 1 <= n_rows <= 192 rows: x [n_rows][k] (row-major, dense), w [n][k] (one row of k
+ * weights per output feature), k a multiple of 64, n a multiple of 2.  `residual` [n_rows][n] is read in
+ * mode VS_LINEAR_RESIDUAL only (it may be the same memory as out).  workspace: device,
+ * vs_linear_workspace_bytes(n_rows, k, n) bytes (0 for shapes that need none: NULL is accepted then).
+ * Errors: VS_ERR_NULL, VS_ERR_SHAPE, VS_ERR_ALIGN, VS_ERR_WORKSPACE, VS_ERR_HIP.
+ */
+size_t vs_linear_workspace_bytes(int32_t n_rows, int32_t k, int32_t n);
+vs_status vs_linear(const void *x, const void *w, int32_t n_rows, int32_t k, int32_t n, int32_t mode,
+                    const void *residual, void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Weights of one decoder layer (device pointers, bf16). */
+typedef struct {
+    const void *norm1;     /* [d_model]                 RMS norm in front of the attention */
+    const void *w_qkv;     /* [(Hq + 2 Hkv) D][d_model] features of W_Q, then W_K, then W_V */
+    const void *w_o;       /* [d_model][Hq D]           output projection */
+    const void *norm2;     /* [d_model]                 RMS norm in front of the feed-forward */
+    const void *w_gate_up; /* [2 d_ff][d_model]         rows 2j, 2j+1: gate and value projection of unit j */
+    const void *w_down;    /* [d_model][d_ff] */
+    int32_t d_model, d_ff; /* multiples of 64 */
+    float eps;             /* of both norms */
+} vs_layer_weights;
+
+/*
+ * One decoder layer for one frame run (Sections 3.2, 3.3: the frame's visual tokens and its carrier,
+ * last, pass through the layers once; only the carrier's K/V row of every layer is kept):
+ *   x1 = rmsnorm(h_in, norm1);  [q k v] = x1 w_qkv^T;  a = frame prefill attention of (q, k, v) over
+ *   the cache, the carrier's K/V row appended to it (vs_frame_prefill_compact);
+ *   h1 = h_in + a w_o^T;  x2 = rmsnorm(h1, norm2);  h_out = h1 + (silu(x2 w_gate^T) * (x2 w_up^T)) w_down^T.
+ * h_in, h_out [n_tokens][d_model] (may be the same memory), 1 <= n_tokens <= 192, bf16 only.
+ * workspace: vs_layer_workspace_bytes (prepared with vs_workspace_init like every workspace that the
+ * attention uses).  Errors as vs_frame_prefill_compact and vs_linear; cache->len grows by one on VS_OK.
+ * Seven launches on hip_stream.
+ */
+size_t vs_layer_workspace_bytes(const vs_shape *shape, const vs_layer_weights *weights, int32_t n_tokens);
+vs_status vs_frame_decoder_layer(const vs_shape *shape, const vs_layer_weights *weights, vs_cache *cache,
+                                 const void *h_in, int32_t n_tokens, void *h_out, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

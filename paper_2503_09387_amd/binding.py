@@ -12,7 +12,8 @@ EXPORTS = [
     "vs_status_string", "vs_workspace_bytes", "vs_workspace_init", "vs_frame_prefill_attn", "vs_frame_prefill_compact",
     "vs_carrier_compact_append", "vs_carrier_compact_append_batched", "vs_decode_attn",
     "vs_carrier_mean_pool", "vs_set_tuning", "vs_memory_bank_push", "vs_carrier_evict_append",
-    "vs_frames_prefill_attn", "vs_decode_attn_static", "vs_question_prefill_append", "vs_frame_qkv_project", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
+    "vs_frames_prefill_attn", "vs_decode_attn_static", "vs_question_prefill_append", "vs_frame_qkv_project",
+    "vs_rmsnorm", "vs_linear", "vs_frame_decoder_layer", "vs_linear_workspace_bytes", "vs_layer_workspace_bytes", "vs_memory_bank_workspace_bytes", "vs_frames_workspace_bytes",
     "vs_decode_static_scratch_bytes",
 ]
 
@@ -99,6 +100,13 @@ def lib():
         L.vs_carrier_mean_pool.argtypes = [vp, i32, i32, i32, vp, vp]
         L.vs_decode_attn_static.argtypes = [sp, i32, vp, vp, i32, ip, vp, vp, vp, vp, vp]
         L.vs_decode_static_scratch_bytes.argtypes = []
+        L.vs_rmsnorm.argtypes = [vp, vp, i32, i32, ctypes.c_float, vp, vp]
+        L.vs_linear.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.vs_linear_workspace_bytes.argtypes = [i32, i32, i32]
+        L.vs_linear_workspace_bytes.restype = sz
+        L.vs_layer_workspace_bytes.argtypes = [sp, vp, i32]
+        L.vs_layer_workspace_bytes.restype = sz
+        L.vs_frame_decoder_layer.argtypes = [sp, vp, cp, vp, i32, vp, vp, sz, vp]
         L.vs_decode_static_scratch_bytes.restype = sz
         L.vs_set_tuning.argtypes = [i32, i32]
         L.vs_memory_bank_push.argtypes = [vp, vp, i32, vp, vp, sz, vp]
@@ -109,7 +117,7 @@ def lib():
         L.vs_frames_workspace_bytes.argtypes = [sp, i32, i32, i32]
         L.vs_frames_workspace_bytes.restype = sz
         L.vs_frame_qkv_project.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
-        for name in EXPORTS[2:-3]:
+        for name in EXPORTS[2:-5]:
             getattr(L, name).restype = ctypes.c_int
         _LIB = L
     return _LIB
@@ -254,6 +262,53 @@ def decode_attn_static(shape, k_slab, v_slab, lens, q, k_new, v_new, out, stream
 
 def decode_static_scratch_bytes():
     return int(lib().vs_decode_static_scratch_bytes())
+
+
+LINEAR_STORE, LINEAR_RESIDUAL, LINEAR_GATED = 0, 1, 2
+
+
+def rmsnorm(x, gamma, out, eps=1e-6, stream=None):
+    """out [rows][d] = x * gamma / sqrt(mean(x^2) + eps)."""
+    _check(lib().vs_rmsnorm(_ptr(x), _ptr(gamma), x.shape[0], x.shape[1], float(eps), _ptr(out), _stream(stream)),
+           "vs_rmsnorm")
+
+
+def linear_workspace_bytes(n_rows, k, n):
+    return int(lib().vs_linear_workspace_bytes(n_rows, k, n))
+
+
+def linear(x, w, out, mode=LINEAR_STORE, residual=None, workspace=None, stream=None):
+    """out = x w^T (x [rows][k], w [n][k]); see vs_linear for the modes."""
+    wp, wb = _ws(workspace)
+    _check(lib().vs_linear(_ptr(x), _ptr(w), x.shape[0], x.shape[1], w.shape[0], int(mode), _ptr(residual), _ptr(out), wp, wb,
+                           _stream(stream)), "vs_linear")
+
+
+class _CLayerWeights(ctypes.Structure):
+    _fields_ = [("norm1", ctypes.c_void_p), ("w_qkv", ctypes.c_void_p), ("w_o", ctypes.c_void_p),
+                ("norm2", ctypes.c_void_p), ("w_gate_up", ctypes.c_void_p), ("w_down", ctypes.c_void_p),
+                ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("eps", ctypes.c_float)]
+
+
+class LayerWeights:
+    """Device tensors of one decoder layer: norm1, norm2 [d]; w_qkv [(Hq+2Hkv)D][d]; w_o [d][Hq D];
+    w_gate_up [2 d_ff][d] (rows alternate gate and value projections); w_down [d][d_ff]."""
+
+    def __init__(self, norm1, w_qkv, w_o, norm2, w_gate_up, w_down, eps=1e-6):
+        self.tensors = (norm1, w_qkv, w_o, norm2, w_gate_up, w_down)
+        self.c = _CLayerWeights(norm1.data_ptr(), w_qkv.data_ptr(), w_o.data_ptr(), norm2.data_ptr(),
+                                w_gate_up.data_ptr(), w_down.data_ptr(), norm1.shape[0], w_down.shape[1], float(eps))
+
+
+def layer_workspace_bytes(shape, weights, n_tokens):
+    return int(lib().vs_layer_workspace_bytes(ctypes.byref(shape), ctypes.byref(weights.c), n_tokens))
+
+
+def frame_decoder_layer(shape, weights, cache, h_in, h_out, workspace, stream=None):
+    """One decoder layer for one frame run h_in [T][d] -> h_out [T][d]; the carrier's K/V row is appended."""
+    wp, wb = _ws(workspace)
+    _check(lib().vs_frame_decoder_layer(ctypes.byref(shape), ctypes.byref(weights.c), ctypes.byref(cache.c), _ptr(h_in),
+                                        h_in.shape[0], _ptr(h_out), wp, wb, _stream(stream)), "vs_frame_decoder_layer")
 
 
 def frames_workspace_bytes(shape, n_frames, n_tokens, max_cache_rows):

@@ -101,4 +101,14 @@ hipError_t launch_mean_pool(const void* e, int32_t n, int32_t d, int32_t dtype, 
 hipError_t launch_frame_qkv(const vs_shape& s, const void* e, int32_t n_visual, int32_t d, const void* w,
                             void* q, void* k, void* v, void* c_out, hipStream_t st);
 
+// dense layers around the attention (Sections 3.1, 4.1): out = X W^T with fp32 sums and a choice of what
+// happens to them (vs_linear_mode); store mode may cut the output features into three tensors
+// (out: features < seg0, out1: < seg1, out2: the rest).  workspace: linear_workspace_bytes.
+size_t linear_workspace_bytes(int32_t n_rows, int32_t K, int32_t N);
+hipError_t launch_linear(const void* x, int32_t ldx, const void* w, int32_t n_rows, int32_t K, int32_t N, int32_t mode,
+                         const void* residual, void* out, void* workspace, hipStream_t st, void* out1 = nullptr,
+                         void* out2 = nullptr, int32_t seg0 = 0, int32_t seg1 = 0);
+hipError_t launch_rmsnorm(const void* x, const void* gamma, int32_t n_rows, int32_t d, float eps, void* out,
+                          hipStream_t st);
+
 }  // namespace vs

@@ -191,6 +191,61 @@ def test_frame_projection_argument_errors():
     assert call(e=ODD) == 6 and call(c=ODD) == 6 and call(k=ODD) == 6
 
 
+def test_dense_layer_argument_errors():
+    L = vs.lib()
+    assert L.vs_rmsnorm(None, FAKE, 4, 64, ctypes.c_float(1e-6), FAKE, None) == 1
+    assert L.vs_rmsnorm(FAKE, FAKE, 0, 64, ctypes.c_float(1e-6), FAKE, None) == 2
+    assert L.vs_rmsnorm(FAKE, FAKE, 4, 60, ctypes.c_float(1e-6), FAKE, None) == 2          # d % 8
+    assert L.vs_rmsnorm(FAKE, FAKE, 4, 64, ctypes.c_float(-1.0), FAKE, None) == 2
+    assert L.vs_rmsnorm(FAKE, FAKE, 4, 64, ctypes.c_float(float("nan")), FAKE, None) == 2
+    assert L.vs_rmsnorm(FAKE, ODD, 4, 64, ctypes.c_float(1e-6), FAKE, None) == 6
+
+    def lin(x=FAKE, w=FAKE, t=170, k=3584, n=3584, mode=0, res=None, out=FAKE, ws=FAKE, wsb=1 << 30):
+        return L.vs_linear(x, w, t, k, n, mode, res, out, ws, wsb, None)
+
+    assert lin(x=None) == 1 and lin(w=None) == 1 and lin(out=None) == 1
+    assert lin(mode=1) == 1 and lin(mode=1, res=FAKE) != 1            # the residual is required in its mode only
+    assert lin(mode=3) == 2 and lin(mode=-1) == 2
+    assert lin(t=0) == 2 and lin(t=193) == 2
+    assert lin(k=0) == 2 and lin(k=100) == 2 and lin(n=0) == 2 and lin(n=7) == 2
+    assert lin(x=ODD) == 6 and lin(out=ODD) == 6 and lin(mode=1, res=ODD) == 6 and lin(ws=ODD) == 6
+    need = L.vs_linear_workspace_bytes(170, 3584, 3584)
+    assert need > 0 and lin(ws=None) == 5 and lin(wsb=need - 1) == 5    # this shape splits K
+    assert L.vs_linear_workspace_bytes(170, 3584, 37888) == 0           # this one does not
+    assert L.vs_linear_workspace_bytes(0, 3584, 3584) == 0 and L.vs_linear_workspace_bytes(170, 100, 3584) == 0
+
+
+def test_decoder_layer_argument_errors():
+    L = vs.lib()
+    s = _shape()
+
+    def weights(d=3584, f=18944, eps=1e-6, **kw):
+        p = dict(norm1=FAKE, w_qkv=FAKE, w_o=FAKE, norm2=FAKE, w_gate_up=FAKE, w_down=FAKE)
+        p.update(kw)
+        return binding._CLayerWeights(p["norm1"], p["w_qkv"], p["w_o"], p["norm2"], p["w_gate_up"], p["w_down"], d, f, eps)
+
+    def cache(cap=100, ln=10):
+        return binding._CCache(FAKE, FAKE, cap, ln)
+
+    def layer(w=None, c=None, h=FAKE, t=170, out=FAKE, ws=FAKE, wsb=1 << 40, shape=s):
+        w = w or weights()
+        c = c or cache()
+        return L.vs_frame_decoder_layer(ctypes.byref(shape), ctypes.byref(w), ctypes.byref(c), h, t, out, ws, wsb, None)
+
+    need = L.vs_layer_workspace_bytes(ctypes.byref(s), ctypes.byref(weights()), 170)
+    assert need > 170 * 18944 * 2
+    assert L.vs_layer_workspace_bytes(ctypes.byref(s), ctypes.byref(weights(d=100)), 170) == 0
+    assert L.vs_layer_workspace_bytes(ctypes.byref(s), ctypes.byref(weights()), 193) == 0
+    assert layer(h=None) == 1 and layer(out=None) == 1 and layer(w=weights(w_o=None)) == 1
+    assert layer(t=0) == 2 and layer(t=193) == 2
+    assert layer(w=weights(d=3600)) == 2 and layer(w=weights(f=1000)) == 2 and layer(w=weights(eps=-1.0)) == 2
+    assert layer(shape=_shape(hq=4, hkv=2, d=64, dt=vs.VS_F32)) == 3
+    full = cache(cap=10, ln=10)
+    assert layer(c=full) == 4 and full.len == 10                        # reported before anything is launched
+    assert layer(ws=None) == 5 and layer(wsb=need - 1) == 5
+    assert layer(h=ODD) == 6 and layer(w=weights(w_down=ODD)) == 6 and layer(ws=ODD) == 6
+
+
 def test_memory_bank_argument_errors():
     L = vs.lib()
     assert L.vs_memory_bank_workspace_bytes(0) == 0 and L.vs_memory_bank_workspace_bytes(1025) == 0
