@@ -6,7 +6,8 @@ configuration (cfg3: 28 layers, 4296 rows already retained, 169 visual tokens + 
 carrier mean pool, then per layer the frame prefill attention with the carrier compaction
 fused into the same launch.  Decode (cfg4: 16 ragged streams, 28 layers) is timed in a
 second region and reported in the same JSON line, as are the single-layer stream (cfg2),
-the dense-vs-compact contrast (cfg5) and a batched compaction micro-benchmark.
+the dense-vs-compact contrast (cfg5), a batched compaction micro-benchmark and the whole
+decoder layers around the attention at the 7B backbone's sizes ("28-layer frames/s").
 
   python bench.py [--gpus 1] [--steps 256] [--warmup 16] [--decode-steps 64] [--repeats 5] [--parts all]
 
@@ -96,7 +97,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
-    parts = set("stream,decode,cfg2,cfg5,compaction,bank,frames,question,projection,cpu".split(",")) if args.parts == "all" \
+    parts = set("stream,decode,cfg2,cfg5,compaction,bank,frames,question,projection,layers,cpu".split(",")) if args.parts == "all" \
         else set(args.parts.split(","))
 
     import numpy as np
@@ -640,6 +641,80 @@ def main():
                  "to back; bytes = weights + embeddings + outputs once")
         log(f"[bench] frame projection (170 x 3584 -> 4608): {tpj * 1e6:.1f} us per launch = {bytes_pj / tpj / 1e9:.0f} GB/s "
             f"({100 * bytes_pj / tpj / 1e9 / PEAK_HBM_GBS:.1f}% of HBM peak), {flops_pj / tpj / 1e12:.0f} TFLOP/s")
+
+    if "layers" in parts:
+        # The whole decoder layers around the attention (Section 4.1: the 7B backbone; d = 3584,
+        # d_ff = 18944): a frame's 169 token rows and the mean of them as carrier row enter as hidden
+        # states, every layer does RMS norm, Q/K/V, attention over the retained rows with the carrier
+        # appended, output projection, gated feed-forward.  Weights are random-init; the 28 layers hold
+        # 28 separate copies (13 GB), so none is served from a cache.
+        from synth import hidden_rows, layer_weights
+        d_model, d_ff = 3584, 18944
+        t0 = time.time()
+        drawn = []
+        for l in range(2):
+            w = layer_weights(c3["seed"], s, d_model, d_ff, layer=l)
+            w_qkv = torch.cat([w["w_q"], w["w_k"], w["w_v"]], dim=0)
+            w_gu = torch.stack([w["w_gate"], w["w_up"]], dim=1).reshape(2 * d_ff, d_model)
+            drawn.append([t.contiguous().to(dev) for t in (w["norm1"], w_qkv, w["w_o"], w["norm2"], w_gu, w["w_down"])])
+        lws = [vs.LayerWeights(*[t.clone() for t in drawn[l % 2]], eps=1e-6) for l in range(NL)]
+        del drawn
+        LF = min(K, 64)
+        lcap = P0 + LF + 1
+        lcaches = []
+        for l in range(NL):
+            hk, hv = cache_rows(c3["seed"], s, P0, c3["sigma"], layer=l)
+            kc = torch.zeros((lcap, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+            vc = torch.zeros_like(kc)
+            kc[:P0].copy_(hk)
+            vc[:P0].copy_(hv)
+            lcaches.append(vs.Cache(kc, vc, P0))
+        emb_l = [hidden_rows(c3["seed"], T, d_model, frame=f).to(dev) for f in range(4)]
+        hbuf = [torch.empty((T, d_model), dtype=torch.bfloat16, device=dev) for _ in range(2)]
+        lws_bytes = vs.layer_workspace_bytes(sh, lws[0], T)
+        wsl = torch.empty(lws_bytes, dtype=torch.uint8, device=dev)
+        vs.workspace_init(sh, wsl)
+        stl = vs.current_stream_handle()
+        log(f"[bench] decoder layers: weights and caches staged in {time.time() - t0:.1f}s")
+
+        def layer_frames(n):
+            for f in range(n):
+                e = emb_l[f % 4]
+                vs.carrier_mean_pool(e[:T - 1], e[T - 1], "bf16", stream=stl)  # the carrier's row: mean of the token rows
+                src = e
+                for l in range(NL):
+                    dst = hbuf[l & 1]
+                    vs.frame_decoder_layer(sh, lws[l], lcaches[l], src, dst, wsl, stream=stl)
+                    src = dst
+
+        def lreset():
+            for cch in lcaches:
+                cch.len = P0
+
+        layer_frames(2)
+        torch.cuda.synchronize()
+        lwalls, lgpus = timed(lambda: layer_frames(LF), before=lreset)
+        lwall, lwall_min, lwall_max = spread(lwalls)
+        lgpu = spread(lgpus)[0]
+        assert all(cch.len == P0 + LF for cch in lcaches) and bool(torch.isfinite(hbuf[(NL - 1) & 1].float()).all())
+        w_bytes = 2 * (2 * d_model + (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim * d_model
+                       + d_model * s.n_q_heads * s.head_dim + 3 * d_ff * d_model)
+        fl_layer = 2 * T * (w_bytes // 2 - 2 * d_model) + float(np.mean([prefill_flops(s, P0 + f, T) for f in range(LF)]))
+        per_layer = lgpu / (LF * NL)
+        extras["decoder_layers"] = dict(
+            frames_per_s=LF / lwall, frames_per_s_min=LF / lwall_max, frames_per_s_max=LF / lwall_min,
+            ms_per_frame=lwall * 1e3 / LF, us_per_layer=per_layer * 1e6, frames_timed=LF, repeats=R,
+            weight_mbytes_per_layer=w_bytes / 1e6, weights_gbs=w_bytes / per_layer / 1e9,
+            frac_hbm=w_bytes / per_layer / 1e9 / PEAK_HBM_GBS, tflops=fl_layer / per_layer / 1e12,
+            frac_mfma=fl_layer / per_layer / 1e12 / PEAK_BF16_TFLOPS, launches_per_layer=10,
+            note="vs_frame_decoder_layer x 28 per frame at the 7B backbone's sizes (d 3584, d_ff 18944, GQA 28/4), "
+                 "random-init weights, one separate copy per layer; per layer: RMS norm, Q/K/V GEMM, attention + "
+                 "carrier append, output GEMM + residual, RMS norm, gate/up GEMM with the SiLU gate, down GEMM + "
+                 "residual; bytes = the layer's weights once")
+        log(f"[bench] 28 decoder layers per frame: {LF / lwall:.1f} frames/s ({lwall * 1e3 / LF:.2f} ms per frame, "
+            f"{per_layer * 1e6:.1f} us per layer = {w_bytes / per_layer / 1e9:.0f} GB/s of weights, "
+            f"{100 * w_bytes / per_layer / 1e9 / PEAK_HBM_GBS:.1f}% of HBM peak; {fl_layer / per_layer / 1e12:.0f} TFLOP/s)")
+        del lws, lcaches, wsl
 
     if "bank" in parts:
         # memory bank at capacity (Section 3.3, memory mechanism; the paper evaluates M = 64 and 128):
