@@ -34,14 +34,16 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # kernels (profiles/*.md), scaled by what the same counters read for a plain 1 GiB copy
 # (FETCH_SIZE x2.0, WRITE_SIZE x1.0).  Static because counters cannot be read inside a timed run.
 TRAFFIC = {
-    "prefill_mfma_kernel": {"fetch_bytes": 28.14e6, "write_bytes": 9.34e6,
-                            "note": "cfg3 launch shape; algorithmic 11.85e6 bytes; on top of that the bf16 partial "
-                                    "results of the 6 key splits are written (7.9e6) and read back by the merging "
-                                    "workgroups (7.9e6), and each head's K/V is fetched by the two XCDs that "
-                                    "hold its row tiles (+9e6)"},
-    "decode_mfma_kernel": {"fetch_bytes": 159.5e6, "write_bytes": 3.72e6,
-                           "note": "cfg4 launch shape; algorithmic 159.4e6 bytes; the writes are the bf16 "
-                                   "partial results of the wavefronts and the appended rows"},
+    "prefill_mfma_kernel": {"fetch_bytes": 28.58e6, "write_bytes": 9.58e6,
+                            "note": "cfg3 launch shape; algorithmic 11.85e6 bytes; on top of that the partial "
+                                    "results of the 6 key splits (fp16 with a scale per row) are written (7.9e6) and "
+                                    "read back by the merging workgroups (7.9e6), and each head's K/V is fetched by "
+                                    "the two XCDs that hold its row tiles (+9e6)"},
+    "decode_layer_call": {"fetch_bytes": 161.5e6, "write_bytes": 2.09e6,
+                          "note": "cfg4 launch shape, both kernels of a layer call; algorithmic 159.5e6 bytes; "
+                                  "decode_mfma_kernel reads 159.4e6 (K and V once) and writes 1.97e6 (the fp16 partial "
+                                  "results of the 256 row shares and the appended rows), decode_combine_kernel "
+                                  "reads those partials back (2.08e6) and writes the outputs (0.11e6)"},
 }
 
 
@@ -316,7 +318,7 @@ def main():
             config={"workload": "cfg4: 16 streams, retained rows U[512,8192]+128, 28 layers, bf16 GQA 28/4, D=128; "
                                 "4 distinct layer slabs drawn on the host, copied to the 28 layers"},
             roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS,
-                          traffic=TRAFFIC.get("decode_mfma_kernel"),
+                          traffic=TRAFFIC.get("decode_layer_call"),
                           kernel="one layer call: decode_mfma_kernel (attention + fused append of the new row) and "
                                  "decode_combine_kernel (merge of the row shares)",
                           avg_launch_us=float(launch_s4 * 1e6), launches_timed=n_launch4,

@@ -62,7 +62,9 @@ def frame_inputs(base_seed, shape, n_tokens, sigma, frame=0, layer=0, q_gain=1.0
 
 def decode_lengths(base_seed, streams, lo, hi, extra):
     """Ragged retained lengths: uniform integer in [lo, hi] per stream, plus `extra` text rows."""
-    rng = np.random.default_rng(_seed(base_seed, "lens"))
+    # (numpy's generator uses all 64 bits of its seed: the plain packing of (seed, kind) is kept here, and with it
+    # the lengths that earlier measurements of this configuration were taken on)
+    rng = np.random.default_rng(((int(base_seed) & 0xFFFF) << 44) | (_KIND["lens"] << 40))
     return (rng.integers(lo, hi + 1, size=streams).astype(np.int64) + int(extra)).tolist()
 
 
