@@ -50,15 +50,16 @@ size_t prefill_frames_workspace_bytes(const vs_shape& s, int32_t n_frames, int32
 int prefill_frames_splits(const vs_shape& s, int32_t n_frames, int32_t n_tokens, int32_t len);
 
 // bf16 split-row decode over ragged streams; appends (k_new, v_new) on the side when given.
-// `counters` points at the decode counters of an initialised workspace control block.
+// `counters` points at the front of an initialised workspace's control block: reserved for the decode
+// kernels, which at present keep no state between or within launches there.
 size_t decode_mfma_workspace_bytes(const vs_shape& s, int32_t n_streams, int32_t max_rows);
 hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab, void* v_slab,
                               int32_t capacity, const LenTable& lens, const void* q,
                               const void* k_new, const void* v_new, void* out, void* counters,
                               void* workspace, hipStream_t st);
 
-// Control block at the start of every workspace: arrival counters that are zero between
-// launches (decode: [kMaxStreamsPerLaunch][Hkv]; prefill: [kMaxRowTiles][Hkv]).
+// Control block at the start of every workspace: [kMaxStreamsPerLaunch][Hkv] words reserved for decode
+// (unused), then the prefill's arrival counters [kMaxRowTiles][Hkv], which are zero between launches.
 constexpr int kMaxRowTiles = 256;
 size_t control_block_bytes(const vs_shape& s);
 inline size_t prefill_counter_offset(const vs_shape& s) {
