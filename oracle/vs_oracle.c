@@ -482,6 +482,7 @@ int vs_oracle_decoder_layer(const double *H, int64_t T, int64_t d, int32_t Hq, i
                             double scale, double *Kf, double *Vf, double *Hout) {
     if (!H || !g1 || !Wq || !Wk || !Wv || !Wo || !g2 || !Wg || !Wu || !Wd || !Kf || !Vf || !Hout) return VSO_ERR_ARG;
     if (T < 1 || d < 1 || Hq < 1 || Hkv < 1 || D < 1 || F < 1 || L < 0) return VSO_ERR_ARG;
+    if (Hq % Hkv != 0 || (L > 0 && (!Kc || !Vc))) return VSO_ERR_ARG;  /* (before any weight is read) */
     const int64_t nq = (int64_t)Hq * D, nk = (int64_t)Hkv * D;
     double *x = (double *)malloc((size_t)T * d * sizeof(double));
     double *q = (double *)malloc((size_t)T * nq * sizeof(double));

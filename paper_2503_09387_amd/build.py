@@ -30,21 +30,17 @@ def generate() -> None:
     mod.main(os.path.join(CSRC, "vs_prefill_asm.inc"))
 
 
-def check_prefill_listing() -> None:
+def check_prefill_listing(listing: str) -> None:
     """The prefill kernel keeps state in fixed registers that the compiler does not know about
     (accumulators and query fragments in a0..a191 for the whole kernel; scores, fragments and
-    temporaries and packed probabilities in v128..v247 while the pipeline runs).  Compile it to a listing and make sure
-    that no compiler-generated instruction touches a0..a191, or writes v128..v247 between the
-    first matrix block and the marker that ends the pipeline."""
+    temporaries and packed probabilities in v128..v247 while the pipeline runs).  `listing` is the
+    device assembly of vs_prefill_mfma.hip as written by the very compile that produced the library:
+    make sure that no compiler-generated instruction touches a0..a191, or writes v128..v247 between the
+    first matrix block and the marker that ends the pipeline, and that the kernels and the marker
+    are there to be checked at all."""
     import re
-    import tempfile
-    src = os.path.join(CSRC, "vs_prefill_mfma.hip")
-    with tempfile.TemporaryDirectory() as tmp:
-        lst = os.path.join(tmp, "prefill.s")
-        flags = [f for f in FLAGS if f not in ("-shared", "-fPIC")]
-        subprocess.run([HIPCC] + flags + ["-S", "--cuda-device-only", "-o", lst, src], check=True,
-                       stderr=subprocess.DEVNULL)
-        lines = open(lst).read().split("\n")
+    lines = listing.split("\n")
+    kernels_seen, markers_seen = 0, 0
     kern, in_asm, live, body, bad, label_line = None, False, False, [], [], 0
     stores = ("global_store", "ds_write", "scratch_store", "buffer_store", "s_", "v_cmp", "v_readlane",
               "v_readfirstlane")
@@ -53,6 +49,7 @@ def check_prefill_listing() -> None:
         m = re.match(r"^(_Z\w*prefill_mfma_kernel\w*):", t)
         if m:
             kern, live = m.group(1), False
+            kernels_seen += 1
         if t.startswith(";;#ASMSTART"):
             in_asm, body = True, []
             continue
@@ -61,6 +58,7 @@ def check_prefill_listing() -> None:
             if any("v_mfma" in x for x in body):
                 live = True
             if any("pipeline registers free" in x for x in body):
+                markers_seen += 1
                 live = False  # the marker's own basic block already belongs to the epilogue
                 bad = [x for x in bad if x[0] < label_line or x[2]]
             continue
@@ -88,18 +86,34 @@ def check_prefill_listing() -> None:
                 rebuild = lo >= 216 and parts[0] == "v_cvt_pk_bf16_f32"
                 if hi >= 128 and lo <= 247 and not rebuild:
                     bad.append((ln, t, False))
+    if kernels_seen < 2 or markers_seen < kernels_seen:
+        raise RuntimeError(f"prefill kernel: the listing shows {kernels_seen} kernels and {markers_seen} end-of-pipeline "
+                           "markers; nothing was checked")
     if bad:
         raise RuntimeError("prefill kernel: the compiler touches registers reserved for the hand-scheduled "
                            "blocks:\n" + "\n".join(f"  line {ln}: {t}" for ln, t, _ in bad[:20]))
 
 
 def build(verbose: bool = False) -> str:
+    """Compiles the library and checks the prefill kernel's listing from that same compile (the
+    compiler keeps its intermediate files, in a scratch directory); the library is put in place only
+    if the check passes."""
+    import glob as _glob
+    import shutil
+    import tempfile
     generate()
-    check_prefill_listing()
-    cmd = [HIPCC] + FLAGS + ["-o", LIB] + sources()
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.run(cmd, check=True)
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "libvideoscan.so")
+        cmd = [HIPCC] + FLAGS + ["-save-temps=cwd", "-o", out] + sources()
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.run(cmd, check=True, cwd=tmp)
+        found = _glob.glob(os.path.join(tmp, "vs_prefill_mfma*gfx950*.s"))
+        if len(found) != 1:
+            raise RuntimeError(f"prefill kernel: expected one device listing of vs_prefill_mfma.hip, found {found}")
+        check_prefill_listing(open(found[0]).read())
+        shutil.copyfile(out, LIB)
+        os.chmod(LIB, 0o755)
     return LIB
 
 
