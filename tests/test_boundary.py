@@ -3,6 +3,7 @@ and refuses bad arguments before launching anything."""
 import ctypes
 import os
 import re
+import sys
 
 import pytest
 
@@ -334,3 +335,11 @@ def test_prefill_workgroup_placement_map(tmp_path):
                     os.path.join(root, "tests", "prefill_map_check.cpp"), "-o", exe], check=True)
     r = subprocess.run([exe], capture_output=True, text=True)
     assert r.returncode == 0 and r.stdout.startswith("ok"), r.stdout + r.stderr
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N above 1 exits with a message that says so (nothing here uses a second GPU)."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout) and r.stdout.strip() == ""
