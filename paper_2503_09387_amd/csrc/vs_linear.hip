@@ -183,10 +183,19 @@ __global__ __launch_bounds__(kThreads) void linear_kernel(LinParams p) {
         for (int u = 0; u < kMaxMine; ++u) {
             const int grp = min(w + 8 * u, w + 8 * (my_groups - 1));
             const unsigned dst = base + (unsigned)grp * 1024;
-            asm volatile("s_mov_b32 m0, %[dst]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[a], off"
-                         :
-                         : [dst] "s"(dst), [a] "v"(src[min(u, my_groups - 1)] + off)
-                         : "memory");
+            const char* const from = src[min(u, my_groups - 1)] + off;
+            // groups from 24 on (u >= 3 for every wavefront) are rows of W: each byte of W is needed
+            // once by one workgroup, so it is asked for as non-temporal and leaves the L2 to X
+            if (u >= kRows / 64)
+                asm volatile("s_mov_b32 m0, %[dst]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[a], off nt"
+                             :
+                             : [dst] "s"(dst), [a] "v"(from)
+                             : "memory");
+            else
+                asm volatile("s_mov_b32 m0, %[dst]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[a], off"
+                             :
+                             : [dst] "s"(dst), [a] "v"(from)
+                             : "memory");
         }
     };
 
