@@ -95,16 +95,27 @@ __global__ __launch_bounds__(kThreads) void frame_qkv_kernel(QkvParams p) {
                                // the number of loads in flight stays what the waits below assume)
         const int64_t off = (int64_t)min(t, n_tiles - 1) * 128;
         const unsigned dst = ring_lds + (unsigned)(t % kRing) * kTileBytes + (unsigned)w * 1024;
+        // the groups of W rows (those from kRows / 8 on) are asked for as non-temporal: every byte of W
+        // is needed once, by one workgroup
         asm volatile(
             "s_mov_b32 m0, %[dst]\n\ts_nop 0\n\t"
             "global_load_lds_dwordx4 %[a0], off\n\ts_add_u32 m0, m0, 0x2000\n\ts_nop 0\n\t"
-            "global_load_lds_dwordx4 %[a1], off\n\ts_add_u32 m0, m0, 0x2000\n\ts_nop 0\n\t"
-            "global_load_lds_dwordx4 %[a2], off"
+            "global_load_lds_dwordx4 %[a1], off"
             :
-            : [dst] "s"(dst), [a0] "v"(src[0] + off), [a1] "v"(src[1] + off), [a2] "v"(src[2] + off)
+            : [dst] "s"(dst), [a0] "v"(src[0] + off), [a1] "v"(src[1] + off)
             : "memory");
+        if (w + 16 >= kRows / 8)
+            asm volatile("s_mov_b32 m0, %[dst]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[a2], off nt"
+                         :
+                         : [dst] "s"(dst + 2 * 0x2000), [a2] "v"(src[2] + off)
+                         : "memory");
+        else
+            asm volatile("s_mov_b32 m0, %[dst]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[a2], off"
+                         :
+                         : [dst] "s"(dst + 2 * 0x2000), [a2] "v"(src[2] + off)
+                         : "memory");
         if (my_groups == 4)
-            asm volatile("s_mov_b32 m0, %[dst]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[a3], off"
+            asm volatile("s_mov_b32 m0, %[dst]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[a3], off nt"
                          :
                          : [dst] "s"(dst + 3 * 0x2000), [a3] "v"(src[3] + off)
                          : "memory");
