@@ -90,9 +90,10 @@ size_t vs_workspace_bytes(const vs_shape *shape, int32_t max_q_tokens, int32_t m
                           int32_t n_streams);
 
 /*
- * Prepares a freshly allocated (or overwritten) workspace: clears the small control
+ * Prepares a freshly allocated (or overwritten) workspace: clears the control
  * block at its start, which holds arrival counters that the kernels leave at zero
- * after every launch.  The first call on a device also runs a one-off probe of how the
+ * after every launch and, per row tile, the number of the launch that last completed it
+ * (launches are numbered from 1, process-wide).  The first call on a device also runs a one-off probe of how the
  * device distributes workgroups and waits for it (hip_stream is synchronised once).
  * Must have completed on the device (same stream, or
  * synchronised) before the first call that uses the workspace; needed once, not per
@@ -101,12 +102,16 @@ size_t vs_workspace_bytes(const vs_shape *shape, int32_t max_q_tokens, int32_t m
  * is also printed on stderr as text.
  *
  * What the probe is for.  When a bf16 prefill call splits the keys of a row tile over several
- * workgroups, the last of them to finish merges their partial results inside the same launch,
+ * workgroups, they merge their partial results inside the same launch once the last of them has
+ * finished (each its share of the rows; the others wait for the last one, looking at a word in
+ * memory a bounded number of times, a few milliseconds at most),
  * through the L2 cache that the compute units of one XCD (accelerator die) share; the library
  * therefore gives all those workgroups ids that the device deals to one XCD, which it learns
  * from the probe (ids go to the XCDs in turn).  Every workgroup of every such launch checks that
  * it really runs on the XCD the probe saw for its id.  If one does not (another partition mode,
- * masked compute units), it sets a word of pinned host memory (64 bytes per device, allocated by
+ * masked compute units), or if one waits for the last of its row tile in vain (the workgroups of
+ * the launch are not all running at once: the device is shared with other work), it sets a word
+ * of pinned host memory (64 bytes per device, allocated by
  * the first vs_workspace_init on the device and kept until the process ends).  The next bf16
  * prefill call on that device (vs_frame_prefill_attn, vs_frame_prefill_compact,
  * vs_question_prefill_append, vs_frames_prefill_attn) then launches nothing and returns
@@ -313,11 +318,17 @@ vs_status vs_carrier_evict_append(const vs_shape *shape, int32_t n_layers, vs_ca
  *   VS_TUNE_PREFILL_SPLITS    workgroups sharing one row tile's keys, 1..32
  *   VS_TUNE_PREFILL_KV_GROUPS  key groups (sets of 4 wavefronts) per prefill workgroup, 1 or 2
  *   VS_TUNE_DECODE_CHUNK_ROWS rows of a stream per decode workgroup share, a multiple of 32
- *   VS_TUNE_PREFILL_MERGE     2 = prefill always merges split results with the second kernel,
- *                             never inside the attention kernel; 3 = for tests of the placement
- *                             guard (see vs_workspace_init): the kernels are told the probed XCD
- *                             order rotated by one, so every workgroup reports itself misplaced
- *                             while the results stay correct
+ *   VS_TUNE_PREFILL_MERGE     1 = split results are merged inside the attention kernel by the last
+ *                             workgroup of a row tile to arrive alone (not shared by the tile's
+ *                             workgroups); 2 = always by the second kernel, never inside the
+ *                             attention kernel; 3 = for tests of the placement guard (see
+ *                             vs_workspace_init): the kernels are told the probed XCD order
+ *                             rotated by one, so every workgroup reports itself misplaced while
+ *                             the results stay correct; 4 = for tests of the bounded wait of the
+ *                             shared merge: the last workgroup to arrive does not say so and the
+ *                             others give up after four looks and report, as if the workgroups
+ *                             of a tile were not running at the same time (that call's output
+ *                             is incomplete; the next call returns VS_ERR_PLACEMENT)
  */
 typedef enum {
     VS_TUNE_PREFILL_SPLITS = 0,

@@ -500,9 +500,9 @@ vs_status vs_set_tuning(int32_t knob, int32_t value) {
             g_tune_decode_chunk_rows = value;
             return VS_OK;
         case VS_TUNE_PREFILL_MERGE:
-            if (value != 0 && value != 2 && value != 3) return VS_ERR_SHAPE;
-            g_tune_prefill_merge = value == 2 ? 2 : 0;
-            prefill_guard_test_mode(value == 3);
+            if (value > 4) return VS_ERR_SHAPE;
+            g_tune_prefill_merge = value <= 2 ? value : 0;
+            prefill_guard_test_mode(value >= 3 ? value : 0);
             return VS_OK;
         default: break;
     }

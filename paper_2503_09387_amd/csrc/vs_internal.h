@@ -15,7 +15,7 @@ constexpr int kMaxGroup = 8;              // query heads per KV head
 extern int g_tune_prefill_splits;
 extern int g_tune_prefill_kv_groups;
 extern int g_tune_decode_chunk_rows;
-extern int g_tune_prefill_merge;  // 0 automatic, 2 always by the second kernel
+extern int g_tune_prefill_merge;  // 0 automatic, 1 inside the kernel by the last workgroup alone, 2 always by the second kernel
 
 struct LenTable {
     int32_t v[kMaxStreamsPerLaunch];
@@ -59,11 +59,19 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
                               void* workspace, hipStream_t st);
 
 // Control block at the start of every workspace: [kMaxStreamsPerLaunch][Hkv] words reserved for decode
-// (unused), then the prefill's arrival counters [kMaxRowTiles][Hkv], which are zero between launches.
+// (unused), then the prefill's arrival counters [kMaxRowTiles][Hkv], which are zero between launches,
+// then the prefill's "all arrived" words, one per unit = (KV head, frame, row tile), each alone in
+// 128 bytes: the number of the launch whose partial results of that unit are complete (zero after
+// vs_workspace_init; launch numbers start at 1 and are never reused).
 constexpr int kMaxRowTiles = 256;
+constexpr int kGoStrideBytes = 128;
 size_t control_block_bytes(const vs_shape& s);
 inline size_t prefill_counter_offset(const vs_shape& s) {
     return (size_t)kMaxStreamsPerLaunch * s.n_kv_heads * sizeof(unsigned int);
+}
+inline size_t prefill_go_offset(const vs_shape& s) {  // from the start of the control block; a multiple of 128
+    const size_t n = (size_t)(kMaxStreamsPerLaunch + kMaxRowTiles) * s.n_kv_heads * sizeof(unsigned int);
+    return (n + 127) & ~size_t(127);
 }
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t st);
 // log2 of the number of XCDs workgroup ids are dealt to in turn on this device, -1 if unknown

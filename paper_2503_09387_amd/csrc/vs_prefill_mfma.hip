@@ -40,6 +40,8 @@
 //     chosen so that the workgroups of one KV head sit on as few XCDs as possible.
 #include <type_traits>
 
+#include <atomic>
+
 #include "vs_internal.h"
 #include "vs_prefill_map.h"
 
@@ -96,6 +98,13 @@ struct PrefillParams {
     // on another XCD sets (the host looks at it before every launch)
     unsigned long long xcc_of_residue;
     unsigned* misplaced;
+    // merge shared by a unit's workgroups: the unit's "all arrived" word (128 bytes apart), this
+    // launch's number, how often a waiting workgroup looks before it gives up, and (tests only) whether
+    // the last workgroup to arrive says so at all
+    unsigned long long* go;
+    unsigned long long launch_no;
+    int max_looks;
+    int announce;
     float inv_row_tiles;
     // A run of F frames (semantic-aware mask, Section 3.4): frame a has its own T rows of q, kf,
     // vf and out, and sees L + a retained rows (the carriers of the frames before it have been
@@ -704,6 +713,113 @@ void prefill_mfma_kernel(PrefillParams p) {
             *box = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         __syncthreads();
         const unsigned before = *box;
+        if (NKG == 2 && p.go) {
+            // ---- The merge shared by the workgroups of the unit.  The last one to arrive writes this
+            // launch's number into the unit's word (a read-modify-write, executed at the L2 like the
+            // count); the others look at the word with read-modify-writes of their own (adding a zero
+            // the compiler cannot see, so that no look is served by the compute unit's cache), a
+            // bounded number of times.  Whoever has seen the number knows that every partial result of
+            // the unit is complete in this L2, and merges its own pieces: of the unit's 4 row groups
+            // x 8 pieces of 16 features per lane, wavefront w of split j takes those from
+            // (4 j + w) * ppw on, ppw = 1, 2 or 4, so that one round trip brings in all it needs.
+            // The sums are those of the single-workgroup merge below and of prefill_combine_kernel,
+            // in the same order.  A workgroup that has looked max_looks times in vain (its unit's
+            // workgroups are not all running at once: the device is shared, or part of it is masked)
+            // reports through the same host word as a misplaced one and leaves its pieces
+            // unmerged: the next call returns VS_ERR_PLACEMENT and the library merges with the
+            // second kernel from then on. ----
+            unsigned long long* const go = p.go + (int64_t)(gf * p.n_row_tiles + rt) * (kGoStrideBytes / 8);
+            if (before + 1 == (unsigned)nsplit) {
+                if (tid == 0) {
+                    *counter = 0;  // zero again for the next launch
+                    if (p.announce) __hip_atomic_exchange(go, p.launch_no, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            } else {
+                unsigned long long zero = 0;
+                asm volatile("" : "+s"(zero));
+                unsigned* const seen_box = box + 1;
+                if (tid == 0) {
+                    unsigned ok = 0;
+                    for (int n = 0; n < p.max_looks && !ok; ++n) {
+                        ok = __hip_atomic_fetch_add(go, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == p.launch_no;
+                        if (!ok) __builtin_amdgcn_s_sleep(2);
+                    }
+                    *seen_box = ok;
+                    if (!ok) __hip_atomic_store(p.misplaced, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                }
+                __syncthreads();
+                if (!*seen_box) return;
+            }
+            const int n_waves = 4 * nsplit;
+            const int ppw = n_waves >= 32 ? 1 : n_waves >= 16 ? 2 : 4;  // pieces per wavefront
+            const int first = (split * 4 + w) * ppw;                     // of the unit's 4 x 8 pieces
+            if (first >= 32) return;
+            const int rg = first >> 3, piece0 = first & 7;
+            const int m = rt * BM + rg * 32 + l32;  // the lane's row of the packed rows
+            const bool row_ok = m < M;
+            const int t = row_ok ? div_small(m, G, inv_G) : 0, hl = m - t * G;
+            __bf16* const orow = out + ((int64_t)t * p.Hq + (int64_t)g * G + hl) * D;
+            const float* const ml0 = p.part_ml + ((int64_t)gf * p.m_pad + m) * 4;
+            const int64_t ml_step = (int64_t)HF * p.m_pad * 4;  // floats between splits
+            const f16x8* const po0 = reinterpret_cast<const f16x8*>(p.part_o) +
+                                      (((int64_t)gf * p.n_row_tiles + rt) * 4 + rg) * (8 * 64) + piece0 * 64 + lane;
+            const int64_t po_step = (int64_t)HF * p.n_row_tiles * 4 * (8 * 64);  // f16x8 between splits
+            auto share = [&](auto ns_tag, auto pieces_tag) {
+                constexpr int NS = decltype(ns_tag)::value, PIECES = decltype(pieces_tag)::value;
+                float4 ml[NS];  // reference, sum, inverse scale of the stored row
+                f16x8 v[NS][PIECES];
+#pragma unroll
+                for (int u = 0; u < NS; ++u) ml[u] = *reinterpret_cast<const float4*>(ml0 + u * ml_step);
+#pragma unroll
+                for (int u = 0; u < NS; ++u)
+#pragma unroll
+                    for (int k = 0; k < PIECES; ++k) v[u][k] = po0[u * po_step + k * 64];
+                float m_star = -INFINITY;
+#pragma unroll
+                for (int u = 0; u < NS; ++u) m_star = fmaxf(m_star, ml[u].x);
+                float wgt[NS], denom = 0.f;  // wgt: what the stored (scaled) row is multiplied by
+#pragma unroll
+                for (int u = 0; u < NS; ++u) {
+                    const float ww = (ml[u].x != -INFINITY) ? __builtin_amdgcn_exp2f(ml[u].x - m_star) * ml[u].y : 0.f;
+                    denom += ww;
+                    wgt[u] = ww * ml[u].z;
+                }
+                const float inv = 1.0f / denom;
+#pragma unroll
+                for (int k = 0; k < PIECES; ++k) {
+                    float acc[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+#pragma unroll
+                    for (int u = 0; u < NS; ++u)
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) acc[j] += wgt[u] * (float)v[u][k][j];
+                    if (row_ok) {
+                        // piece (db, h2) = (piece >> 1, piece & 1): dims 32 db + 16 h2 + 4 hi + 0..3, + 8
+                        bf16x4 w0, w1;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            w0[j] = (__bf16)(acc[j] * inv);
+                            w1[j] = (__bf16)(acc[4 + j] * inv);
+                        }
+                        __bf16* dst = orow + 16 * (piece0 + k) + 4 * hi;
+                        *reinterpret_cast<bf16x4*>(dst) = w0;
+                        *reinterpret_cast<bf16x4*>(dst + 8) = w1;
+                    }
+                }
+            };
+            using std::integral_constant;
+            switch (nsplit) {
+                case 2: share(integral_constant<int, 2>{}, integral_constant<int, 4>{}); break;
+                case 3: share(integral_constant<int, 3>{}, integral_constant<int, 4>{}); break;
+                case 4: share(integral_constant<int, 4>{}, integral_constant<int, 2>{}); break;
+                case 5: share(integral_constant<int, 5>{}, integral_constant<int, 2>{}); break;
+                case 6: share(integral_constant<int, 6>{}, integral_constant<int, 2>{}); break;
+                case 7: share(integral_constant<int, 7>{}, integral_constant<int, 2>{}); break;
+                default: share(integral_constant<int, 8>{}, integral_constant<int, 1>{}); break;
+            }
+            return;
+        }
         if (before + 1 == (unsigned)nsplit) {
             if (tid == 0) *counter = 0;  // zero again for the next launch
             // the rows this wavefront has closed: row group kg of its 64 rows, or both
@@ -884,7 +1000,12 @@ unsigned long long g_xcc_of_residue[16] = {};  // XCC_ID read for ids of residue
 // than the probed one.
 unsigned* g_misplaced[16] = {};      // as the host addresses it
 unsigned* g_misplaced_dev[16] = {};  // as the kernels address it
-int g_tune_guard_test = 0;  // tests: the next probe-derived table is handed to the kernels rotated by one XCD
+// tests: 3 = the probe-derived table is handed to the kernels rotated by one XCD; 4 = the last workgroup
+// of a unit to arrive does not say so and the others look only four times
+int g_tune_guard_test = 0;
+// Launches that merge inside the kernel are numbered, process-wide, from 1: a unit's "all arrived"
+// word holds the number of the launch that completed it, so it never has to be cleared.
+std::atomic<unsigned long long> g_launch_no{0};
 
 __global__ void xcd_probe_kernel(unsigned* out) {
     unsigned x;
@@ -1073,6 +1194,10 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
     p.xcd_shift = p.units_per_xcd = 0;
     p.xcc_of_residue = 0;
     p.misplaced = nullptr;
+    p.go = nullptr;
+    p.launch_no = 0;
+    p.max_looks = 0;
+    p.announce = 1;
     p.inv_row_tiles = 1.0f / (float)pl.n_row_tiles;
     p.F = n_frames;
     p.inv_frame_tiles = 1.0f / (float)(pl.n_row_tiles * n_frames);
@@ -1093,9 +1218,18 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
         p.xcd_shift = g_xcd_shift[dev];
         p.units_per_xcd = prefill_units_per_xcd(pl.n_row_tiles * s.n_kv_heads * n_frames, p.xcd_shift);
         p.xcc_of_residue = g_xcc_of_residue[dev];
-        if (g_tune_guard_test && p.xcd_shift > 0)  // entry r names the XCD of residue r + 1: every workgroup is "misplaced"
+        if (g_tune_guard_test == 3 && p.xcd_shift > 0)  // entry r names the XCD of residue r + 1: every workgroup is "misplaced"
             p.xcc_of_residue = (p.xcc_of_residue >> 4) | ((p.xcc_of_residue & 15ull) << (4 * ((1 << p.xcd_shift) - 1)));
         p.misplaced = g_misplaced_dev[dev];
+        if (g_tune_prefill_merge != 1 && pl.kvg == 2) {
+            // (counters points at the arrival counters, prefill_counter_offset into the control block)
+            p.go = reinterpret_cast<unsigned long long*>(static_cast<char*>(counters) - prefill_counter_offset(s) +
+                                                         prefill_go_offset(s));
+            p.launch_no = g_launch_no.fetch_add(1, std::memory_order_relaxed) + 1;
+            // ~0.3 us a look: a workgroup waits some milliseconds at most
+            p.max_looks = g_tune_guard_test == 4 ? 4 : 8192;
+            p.announce = g_tune_guard_test != 4;
+        }
     }
     const int64_t slots = (int64_t)pl.nsplit * s.n_kv_heads * n_frames * pl.m_pad;
     p.part_ml = (float*)workspace;

@@ -175,7 +175,7 @@ def test_mean_pool_and_tuning_argument_errors():
     assert L.vs_set_tuning(2, 100) == 2 and L.vs_set_tuning(9, 1) == 2
     assert L.vs_set_tuning(3, 1) == 2 and L.vs_set_tuning(3, 0) == 2      # no such knob
     assert L.vs_set_tuning(0, 4) == 0 and L.vs_set_tuning(0, 0) == 0
-    assert L.vs_set_tuning(4, 1) == 2 and L.vs_set_tuning(4, 2) == 0 and L.vs_set_tuning(4, 0) == 0
+    assert L.vs_set_tuning(4, 5) == 2 and L.vs_set_tuning(4, 1) == 0 and L.vs_set_tuning(4, 2) == 0 and L.vs_set_tuning(4, 0) == 0
     assert L.vs_set_tuning(99, 7) == 2 and L.vs_set_tuning(99, 0) == 2    # no such knob
 
 

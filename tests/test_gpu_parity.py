@@ -329,9 +329,11 @@ def test_prefill_result_does_not_depend_on_the_split(kv_groups):
 @pytest.mark.parametrize("L,T,splits", [(4424, 170, 0), (1500, 170, 0), (1500, 170, 3), (3000, 300, 8), (700, 40, 2),
                                           (200, 170, 0), (264, 170, 3), (100, 20, 2)])
 def test_prefill_merge_inside_the_kernel_equals_the_second_kernel(L, T, splits):
-    """Split results are merged either by the last workgroup of a row tile to arrive, inside the
-    attention kernel, or by a second kernel: the same sums in the same order, so the same bits;
-    also on repeated calls through one workspace (the arrival counters return to zero)."""
+    """Split results are merged inside the attention kernel, by the workgroups of a row tile together
+    once the last of them has arrived (the library's choice) or by that last one alone, or by a
+    second kernel: the same sums in the same order, so the same bits; also on repeated calls
+    through one workspace (the arrival counters return to zero, launch numbers move on) and with
+    the three ways taking turns."""
     s = QW
     hk, hv = cache_rows(31, s, L, 0.5)
     q, kf, vf = frame_inputs(31, s, T, 0.5, q_gain=4)
@@ -341,10 +343,11 @@ def test_prefill_merge_inside_the_kernel_equals_the_second_kernel(L, T, splits):
     vs.set_tuning(vs.TUNE_PREFILL_MERGE, 2)
     two_kernels, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
     check_close(two_kernels, ref, "bf16", f"second-kernel merge L={L} T={T} splits={splits}")
-    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
-    for rep in range(3):
+    for mode in (0, 0, 0, 1, 0, 1, 2, 0):
+        vs.set_tuning(vs.TUNE_PREFILL_MERGE, mode)
         inside, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
-        assert same_bits(inside, two_kernels.cpu()), f"merge inside the kernel differs (call {rep})"
+        assert same_bits(inside, two_kernels.cpu()), f"merge mode {mode} differs from the second kernel's"
+    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
 
 
 @pytest.mark.parametrize("F,T,L,splits", [(2, 170, 4296, 0), (2, 170, 4296, 5), (3, 170, 2000, 4), (4, 60, 900, 2),
@@ -375,9 +378,10 @@ def test_runs_of_frames_merge_inside_the_kernel_equals_the_second_kernel(F, T, L
     vs.set_tuning(vs.TUNE_PREFILL_MERGE, 2)
     two_kernels = run()
     assert bool(torch.isfinite(two_kernels.float()).all())
+    for mode in (0, 0, 1, 0):
+        vs.set_tuning(vs.TUNE_PREFILL_MERGE, mode)
+        assert torch.equal(run().view(torch.int16), two_kernels.view(torch.int16)), f"merge mode {mode}"
     vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
-    for rep in range(3):
-        assert torch.equal(run().view(torch.int16), two_kernels.view(torch.int16)), f"call {rep}"
 
 
 def test_prefill_placement_guard_reports_and_falls_back():
@@ -406,6 +410,33 @@ def test_prefill_placement_guard_reports_and_falls_back():
     again, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws2)
     assert same_bits(again, good.cpu())
     run_prefill(s, hk, hv, L, q, kf, vf, ws=ws2)                      # and nothing is reported this time
+
+
+def test_prefill_shared_merge_gives_up_waiting_and_reports():
+    """In the shared merge the workgroups of a row tile wait for the last of them, looking at a word
+    in memory a bounded number of times.  With tuning value 4 the last one never says that it has
+    arrived and the others look four times only: every kernel still ends, the waiting workgroups
+    report through the host word, the next call launches nothing and returns VS_ERR_PLACEMENT, the
+    calls after it merge with the second kernel and are right, and a new vs_workspace_init brings
+    the in-kernel merge back."""
+    s, L, T = QW, 1500, 170
+    hk, hv = cache_rows(76, s, L, 0.5)
+    q, kf, vf = frame_inputs(76, s, T, 0.5, q_gain=4)
+    ws = workspace(s, T, L, 0)
+    good, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
+    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 4)
+    run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)                       # ends; its output is incomplete
+    vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
+    with pytest.raises(vs.VSError) as err:
+        run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
+    assert err.value.code == 8
+    for _ in range(2):                                                # second-kernel merge from now on
+        after, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws)
+        assert same_bits(after, good.cpu())
+    ws2 = workspace(s, T, L, 0)                                       # probes the device again
+    for _ in range(2):
+        again, _, _ = run_prefill(s, hk, hv, L, q, kf, vf, ws=ws2)
+        assert same_bits(again, good.cpu())
 
 
 @pytest.mark.parametrize("L", [130, 1500])
