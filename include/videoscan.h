@@ -92,8 +92,7 @@ size_t vs_workspace_bytes(const vs_shape *shape, int32_t max_q_tokens, int32_t m
 /*
  * Prepares a freshly allocated (or overwritten) workspace: clears the control
  * block at its start, which holds arrival counters that the kernels leave at zero
- * after every launch and, per row tile, the number of the launch that last completed it
- * (launches are numbered from 1, process-wide).  The first call on a device also runs a one-off probe of how the
+ * after every launch.  The first call on a device also runs a one-off probe of how the
  * device distributes workgroups and waits for it (hip_stream is synchronised once).
  * Must have completed on the device (same stream, or
  * synchronised) before the first call that uses the workspace; needed once, not per
@@ -325,10 +324,10 @@ vs_status vs_carrier_evict_append(const vs_shape *shape, int32_t n_layers, vs_ca
  *                             vs_workspace_init): the kernels are told the probed XCD order
  *                             rotated by one, so every workgroup reports itself misplaced while
  *                             the results stay correct; 4 = for tests of the bounded wait of the
- *                             shared merge: the last workgroup to arrive does not say so and the
- *                             others give up after four looks and report, as if the workgroups
- *                             of a tile were not running at the same time (that call's output
- *                             is incomplete; the next call returns VS_ERR_PLACEMENT)
+ *                             shared merge: the workgroups that would wait for the last of their
+ *                             tile give up at once and report, as if the workgroups of a tile
+ *                             were not running at the same time (that call's output is
+ *                             incomplete; the next call returns VS_ERR_PLACEMENT)
  */
 typedef enum {
     VS_TUNE_PREFILL_SPLITS = 0,

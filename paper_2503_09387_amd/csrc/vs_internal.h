@@ -59,18 +59,15 @@ hipError_t launch_decode_mfma(const vs_shape& s, int32_t n_streams, void* k_slab
                               void* workspace, hipStream_t st);
 
 // Control block at the start of every workspace: [kMaxStreamsPerLaunch][Hkv] words reserved for decode
-// (unused), then the prefill's arrival counters [kMaxRowTiles][Hkv], which are zero between launches,
-// then the prefill's "all arrived" words, one per unit = (KV head, frame, row tile), each alone in
-// 128 bytes: the number of the launch whose partial results of that unit are complete (zero after
-// vs_workspace_init; launch numbers start at 1 and are never reused).
+// (unused), then the prefill's arrival counters, one per unit = (KV head, frame, row tile), each alone
+// in 128 bytes (the workgroups of a unit look at theirs while they wait for one another: counters of
+// other units in the same line would queue behind those looks).  A counter wraps to zero with the last
+// arrival, so all of them are zero between launches.
 constexpr int kMaxRowTiles = 256;
-constexpr int kGoStrideBytes = 128;
+constexpr int kCounterStrideBytes = 128;
 size_t control_block_bytes(const vs_shape& s);
-inline size_t prefill_counter_offset(const vs_shape& s) {
-    return (size_t)kMaxStreamsPerLaunch * s.n_kv_heads * sizeof(unsigned int);
-}
-inline size_t prefill_go_offset(const vs_shape& s) {  // from the start of the control block; a multiple of 128
-    const size_t n = (size_t)(kMaxStreamsPerLaunch + kMaxRowTiles) * s.n_kv_heads * sizeof(unsigned int);
+inline size_t prefill_counter_offset(const vs_shape& s) {  // from the start of the control block; a multiple of 128
+    const size_t n = (size_t)kMaxStreamsPerLaunch * s.n_kv_heads * sizeof(unsigned int);
     return (n + 127) & ~size_t(127);
 }
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t st);

@@ -19,9 +19,11 @@
 //     many per lane; the tiles that hold frame rows are spread over the lanes and come first
 //     in their lane.  One wavefront per SIMD: it owns all 512 registers.
 //   * The per-workgroup partials (reference, sum, normalised accumulator as scaled fp16) are merged
-//     inside the launch by the last workgroup of a row tile to arrive (all splits of a row
-//     tile run on one XCD and count themselves in through its L2; nobody waits), or, where
-//     that is not possible, by a second small kernel.  Same sums, same order, same bits.
+//     inside the launch (all splits of a row tile run on one XCD and count themselves in
+//     through its L2): by the tile's workgroups together, each its share of the rows, once
+//     the last of them has arrived (the others wait for it, a bounded number of looks at the
+//     counter), or by that last one alone, or, where neither is possible, by a second small
+//     kernel.  Same sums, same order, same bits.
 //   * Scores are computed transposed, S^T = K Q^T (v_mfma_f32_32x32x16_bf16), so that a
 //     lane owns one query column: softmax statistics stay in the lane, and the
 //     probabilities are already laid out as the B operand of O^T += V^T P^T.  V^T comes
@@ -39,8 +41,6 @@
 //   * Workgroup ids are dealt to the 8 XCDs in turn, and each XCD has its own L2: ids are
 //     chosen so that the workgroups of one KV head sit on as few XCDs as possible.
 #include <type_traits>
-
-#include <atomic>
 
 #include "vs_internal.h"
 #include "vs_prefill_map.h"
@@ -90,7 +90,7 @@ struct PrefillParams {
     // Merging inside this kernel (see the end of the kernel): the workgroups of one (row tile,
     // KV head) unit are placed on one XCD and count their arrivals in `arrivals`; null = the
     // partial results are merged by prefill_combine_kernel.
-    unsigned* arrivals;       // [Hkv][row tiles], zero between launches
+    unsigned* arrivals;       // [Hkv][frames][row tiles], kCounterStrideBytes apart, zero between launches
     int xcd_shift;            // log2 of the number of XCDs workgroup ids are dealt to in turn
     int units_per_xcd;
     // the guard of that placement: the XCC_ID the probe read for every residue of the id (4 bits
@@ -98,13 +98,10 @@ struct PrefillParams {
     // on another XCD sets (the host looks at it before every launch)
     unsigned long long xcc_of_residue;
     unsigned* misplaced;
-    // merge shared by a unit's workgroups: the unit's "all arrived" word (128 bytes apart), this
-    // launch's number, how often a waiting workgroup looks before it gives up, and (tests only) whether
-    // the last workgroup to arrive says so at all
-    unsigned long long* go;
-    unsigned long long launch_no;
+    // merge shared by a unit's workgroups (0: the last one to arrive merges alone), and how often a
+    // waiting workgroup looks at the counter before it gives up
+    int share_merge;
     int max_looks;
-    int announce;
     float inv_row_tiles;
     // A run of F frames (semantic-aware mask, Section 3.4): frame a has its own T rows of q, kf,
     // vf and out, and sees L + a retained rows (the carriers of the frames before it have been
@@ -700,48 +697,43 @@ void prefill_mfma_kernel(PrefillParams p) {
         // ---- merge of the splits inside this launch.  Every workgroup has stored its
         // partial result above (ordinary stores: they stay in the XCD's L2, and all splits
         // of the unit run on this XCD).  Once the stores of all its wavefronts have been
-        // acknowledged the workgroup counts itself in; the one that finds all others
-        // counted reads their partials back from L2 and writes the unit's output rows.
-        // Nobody waits for anybody.  The sums run over the splits in index order and take
-        // this workgroup's own part rounded as stored, so the result does not depend on
-        // which workgroup comes last, and equals what prefill_combine_kernel computes. ----
+        // acknowledged the workgroup counts itself in.  Then either the workgroups of the unit
+        // share the merge (below), or the one that finds all others counted reads their partials
+        // back from L2 and writes the unit's output rows alone, and nobody waits for anybody.
+        // Either way the sums run over the splits in index order and take a workgroup's own part
+        // rounded as stored, so the result does not depend on which workgroup comes last, and
+        // equals what prefill_combine_kernel computes. ----
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         __syncthreads();                     // also: the exchange area is free again
         unsigned* const box = reinterpret_cast<unsigned*>(dyn_smem);
-        unsigned* const counter = p.arrivals + gf * p.n_row_tiles + rt;
-        if (tid == 0)
-            *box = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        unsigned* const counter = p.arrivals + (int64_t)(gf * p.n_row_tiles + rt) * (kCounterStrideBytes / 4);
+        // (an increment that wraps: 0, 1, .., nsplit - 1, 0: the counter is back at zero with the last
+        // arrival, for the next launch and as the sign that all have arrived)
+        if (tid == 0) *box = __builtin_amdgcn_atomic_inc32(counter, (unsigned)(nsplit - 1), __ATOMIC_RELAXED, "workgroup");
         __syncthreads();
         const unsigned before = *box;
-        if (NKG == 2 && p.go) {
-            // ---- The merge shared by the workgroups of the unit.  The last one to arrive writes this
-            // launch's number into the unit's word (a read-modify-write, executed at the L2 like the
-            // count); the others look at the word with read-modify-writes of their own (adding a zero
-            // the compiler cannot see, so that no look is served by the compute unit's cache), a
-            // bounded number of times.  Whoever has seen the number knows that every partial result of
-            // the unit is complete in this L2, and merges its own pieces: of the unit's 4 row groups
-            // x 8 pieces of 16 features per lane, wavefront w of split j takes those from
-            // (4 j + w) * ppw on, ppw = 1, 2 or 4, so that one round trip brings in all it needs.
-            // The sums are those of the single-workgroup merge below and of prefill_combine_kernel,
-            // in the same order.  A workgroup that has looked max_looks times in vain (its unit's
-            // workgroups are not all running at once: the device is shared, or part of it is masked)
-            // reports through the same host word as a misplaced one and leaves its pieces
-            // unmerged: the next call returns VS_ERR_PLACEMENT and the library merges with the
-            // second kernel from then on. ----
-            unsigned long long* const go = p.go + (int64_t)(gf * p.n_row_tiles + rt) * (kGoStrideBytes / 8);
-            if (before + 1 == (unsigned)nsplit) {
-                if (tid == 0) {
-                    *counter = 0;  // zero again for the next launch
-                    if (p.announce) __hip_atomic_exchange(go, p.launch_no, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                }
-            } else {
-                unsigned long long zero = 0;
+        if (NKG == 2 && p.share_merge) {
+            // ---- The merge shared by the workgroups of the unit.  Those that are not the last to
+            // arrive look at the counter again, with read-modify-writes (adding a zero the compiler
+            // cannot see), which are executed at the L2 like the count itself and never served by the
+            // compute unit's cache, a bounded number of times: a zero says that the last one has
+            // arrived.  Whoever knows that, knows that every partial result of the unit is complete
+            // in this L2, and merges its own pieces: of the unit's 4 row groups x 8 pieces of 16
+            // features per lane, wavefront w of split j takes those from (4 j + w) * ppw on, ppw = 1,
+            // 2 or 4, so that one round trip brings in all it needs.  The sums are those of the
+            // single-workgroup merge below and of prefill_combine_kernel, in the same order.  A
+            // workgroup that has looked max_looks times in vain (its unit's workgroups are not all
+            // running at once: the device is shared, or part of it is masked) reports through the
+            // same host word as a misplaced one and leaves its pieces unmerged: the next call
+            // returns VS_ERR_PLACEMENT and the library merges with the second kernel from then on. ----
+            if (before + 1 != (unsigned)nsplit) {
+                unsigned zero = 0;
                 asm volatile("" : "+s"(zero));
                 unsigned* const seen_box = box + 1;
                 if (tid == 0) {
                     unsigned ok = 0;
                     for (int n = 0; n < p.max_looks && !ok; ++n) {
-                        ok = __hip_atomic_fetch_add(go, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == p.launch_no;
+                        ok = __hip_atomic_fetch_add(counter, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0u;
                         if (!ok) __builtin_amdgcn_s_sleep(2);
                     }
                     *seen_box = ok;
@@ -821,7 +813,6 @@ void prefill_mfma_kernel(PrefillParams p) {
             return;
         }
         if (before + 1 == (unsigned)nsplit) {
-            if (tid == 0) *counter = 0;  // zero again for the next launch
             // the rows this wavefront has closed: row group kg of its 64 rows, or both
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
@@ -1000,12 +991,9 @@ unsigned long long g_xcc_of_residue[16] = {};  // XCC_ID read for ids of residue
 // than the probed one.
 unsigned* g_misplaced[16] = {};      // as the host addresses it
 unsigned* g_misplaced_dev[16] = {};  // as the kernels address it
-// tests: 3 = the probe-derived table is handed to the kernels rotated by one XCD; 4 = the last workgroup
-// of a unit to arrive does not say so and the others look only four times
+// tests: 3 = the probe-derived table is handed to the kernels rotated by one XCD; 4 = workgroups that
+// wait for the last of their unit do not look at all and give up
 int g_tune_guard_test = 0;
-// Launches that merge inside the kernel are numbered, process-wide, from 1: a unit's "all arrived"
-// word holds the number of the launch that completed it, so it never has to be cleared.
-std::atomic<unsigned long long> g_launch_no{0};
 
 __global__ void xcd_probe_kernel(unsigned* out) {
     unsigned x;
@@ -1194,10 +1182,8 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
     p.xcd_shift = p.units_per_xcd = 0;
     p.xcc_of_residue = 0;
     p.misplaced = nullptr;
-    p.go = nullptr;
-    p.launch_no = 0;
+    p.share_merge = 0;
     p.max_looks = 0;
-    p.announce = 1;
     p.inv_row_tiles = 1.0f / (float)pl.n_row_tiles;
     p.F = n_frames;
     p.inv_frame_tiles = 1.0f / (float)(pl.n_row_tiles * n_frames);
@@ -1222,13 +1208,8 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
             p.xcc_of_residue = (p.xcc_of_residue >> 4) | ((p.xcc_of_residue & 15ull) << (4 * ((1 << p.xcd_shift) - 1)));
         p.misplaced = g_misplaced_dev[dev];
         if (g_tune_prefill_merge != 1 && pl.kvg == 2) {
-            // (counters points at the arrival counters, prefill_counter_offset into the control block)
-            p.go = reinterpret_cast<unsigned long long*>(static_cast<char*>(counters) - prefill_counter_offset(s) +
-                                                         prefill_go_offset(s));
-            p.launch_no = g_launch_no.fetch_add(1, std::memory_order_relaxed) + 1;
-            // ~0.3 us a look: a workgroup waits some milliseconds at most
-            p.max_looks = g_tune_guard_test == 4 ? 4 : 8192;
-            p.announce = g_tune_guard_test != 4;
+            p.share_merge = 1;
+            p.max_looks = g_tune_guard_test == 4 ? 0 : 8192;  // ~0.3 us a look: some milliseconds at most
         }
     }
     const int64_t slots = (int64_t)pl.nsplit * s.n_kv_heads * n_frames * pl.m_pad;

@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(uint32_t* p, size_t n) {
 }  // namespace
 
 size_t control_block_bytes(const vs_shape& s) {
-    const size_t n = prefill_go_offset(s) + (size_t)kMaxRowTiles * s.n_kv_heads * kGoStrideBytes;
+    const size_t n = prefill_counter_offset(s) + (size_t)kMaxRowTiles * s.n_kv_heads * kCounterStrideBytes;
     return (n + 255) & ~size_t(255);
 }
 

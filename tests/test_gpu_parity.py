@@ -414,9 +414,9 @@ def test_prefill_placement_guard_reports_and_falls_back():
 
 def test_prefill_shared_merge_gives_up_waiting_and_reports():
     """In the shared merge the workgroups of a row tile wait for the last of them, looking at a word
-    in memory a bounded number of times.  With tuning value 4 the last one never says that it has
-    arrived and the others look four times only: every kernel still ends, the waiting workgroups
-    report through the host word, the next call launches nothing and returns VS_ERR_PLACEMENT, the
+    in memory a bounded number of times.  With tuning value 4 that number is zero: every kernel
+    still ends, the workgroups that would have waited report through the host word (and leave their
+    share unmerged), the next call launches nothing and returns VS_ERR_PLACEMENT, the
     calls after it merge with the second kernel and are right, and a new vs_workspace_init brings
     the in-kernel merge back."""
     s, L, T = QW, 1500, 170
