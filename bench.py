@@ -34,7 +34,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # kernels (profiles/*.md), scaled by what the same counters read for a plain 1 GiB copy
 # (FETCH_SIZE x2.0, WRITE_SIZE x1.0).  Static because counters cannot be read inside a timed run.
 TRAFFIC = {
-    "prefill_mfma_kernel": {"fetch_bytes": 28.58e6, "write_bytes": 9.58e6,
+    "prefill_mfma_kernel": {"fetch_bytes": 27.94e6, "write_bytes": 9.59e6,
                             "note": "cfg3 launch shape; algorithmic 11.85e6 bytes; on top of that the partial "
                                     "results of the 6 key splits (fp16 with a scale per row) are written (7.9e6) and "
                                     "read back by the merging workgroups (7.9e6), and each head's K/V is fetched by "
