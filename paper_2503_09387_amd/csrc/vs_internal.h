@@ -80,6 +80,18 @@ hipError_t probe_xcd_mapping(void* scratch, hipStream_t st);
 // on another XCD than probed; in-kernel merging is then off for the device until it is probed again.
 bool prefill_placement_fault(int dev);
 void prefill_guard_test_mode(int on);
+// What a kernel that merges inside the launch needs to know about the device: how many XCDs ids are
+// dealt to in turn (log2), which XCD ids of residue r were seen on (4 bits each), the host word (as
+// the kernels address it) through which a workgroup reports, and how often a waiting workgroup looks
+// before it gives up.  False: not probed, a fault has been reported since, or merging inside kernels is
+// switched off (VS_TUNE_PREFILL_MERGE = 2): merge with a second kernel.
+struct XcdPlacement {
+    int xcd_shift;
+    unsigned long long xcc_of_residue;
+    unsigned* misplaced;
+    int max_looks;
+};
+bool xcd_placement_of_device(int dev, XcdPlacement* out);
 
 // the body of vs_decode_attn (checks, launches, length bookkeeping) over any workspace
 vs_status decode_entry(const vs_shape* shape, int32_t n_streams, void* k_slab, void* v_slab, int32_t capacity,
@@ -111,9 +123,12 @@ hipError_t launch_frame_qkv(const vs_shape& s, const void* e, int32_t n_visual, 
 // happens to them (vs_linear_mode); store mode may cut the output features into three tensors
 // (out: features < seg0, out1: < seg1, out2: the rest).  workspace: linear_workspace_bytes.
 size_t linear_workspace_bytes(int32_t n_rows, int32_t K, int32_t N);
+// arrival_counters: the prefill's counters in an initialised control block (null: none).  With them, and
+// at most kMaxRowTiles * Hkv blocks, the split-K shares are added inside the multiplying launch.
 hipError_t launch_linear(const void* x, int32_t ldx, const void* w, int32_t n_rows, int32_t K, int32_t N, int32_t mode,
                          const void* residual, void* out, void* workspace, hipStream_t st, void* out1 = nullptr,
-                         void* out2 = nullptr, int32_t seg0 = 0, int32_t seg1 = 0);
+                         void* out2 = nullptr, int32_t seg0 = 0, int32_t seg1 = 0, void* arrival_counters = nullptr,
+                         int32_t n_counters = 0);
 hipError_t launch_rmsnorm(const void* x, const void* gamma, int32_t n_rows, int32_t d, float eps, void* out,
                           hipStream_t st);
 

@@ -122,25 +122,30 @@ vs_status vs_frame_decoder_layer(const vs_shape* shape, const vs_layer_weights* 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
     const int32_t T = n_tokens, d = wt->d_model;
+    // the arrival counters of the attention's control block also serve the split-K launches (every
+    // kernel leaves them at zero)
+    void* const counters = ws + l.attn + prefill_counter_offset(*shape);
+    const int32_t n_counters = kMaxRowTiles * shape->n_kv_heads;
     const int32_t nq = shape->n_q_heads * shape->head_dim, nk = shape->n_kv_heads * shape->head_dim;
     // x1 = rmsnorm(h_in); [q k v] = x1 w_qkv^T
     if (launch_rmsnorm(h_in, wt->norm1, T, d, wt->eps, ws + l.x, stream) != hipSuccess) return VS_ERR_HIP;
     if (launch_linear(ws + l.x, d, wt->w_qkv, T, d, nq + 2 * nk, VS_LINEAR_STORE, nullptr, ws + l.q, ws + l.lin, stream,
-                      ws + l.k, ws + l.v, nq, nq + nk) != hipSuccess)
+                      ws + l.k, ws + l.v, nq, nq + nk, counters, n_counters) != hipSuccess)
         return VS_ERR_HIP;
     // the attention of the frame over what has been kept; the carrier's K/V row stays
     st = vs_frame_prefill_compact(shape, cache, ws + l.q, ws + l.k, ws + l.v, T, ws + l.a, nullptr, ws + l.attn,
                                   l.x - l.attn, hip_stream);
     if (st != VS_OK) return st;
     // h1 = h_in + a w_o^T; x2 = rmsnorm(h1); act = silu(x2 w_gate^T) * (x2 w_up^T); h_out = h1 + act w_down^T
-    if (launch_linear(ws + l.a, nq, wt->w_o, T, nq, d, VS_LINEAR_RESIDUAL, h_in, ws + l.h1, ws + l.lin, stream) != hipSuccess)
+    if (launch_linear(ws + l.a, nq, wt->w_o, T, nq, d, VS_LINEAR_RESIDUAL, h_in, ws + l.h1, ws + l.lin, stream, nullptr,
+                      nullptr, 0, 0, counters, n_counters) != hipSuccess)
         return VS_ERR_HIP;
     if (launch_rmsnorm(ws + l.h1, wt->norm2, T, d, wt->eps, ws + l.x, stream) != hipSuccess) return VS_ERR_HIP;
     if (launch_linear(ws + l.x, d, wt->w_gate_up, T, d, 2 * wt->d_ff, VS_LINEAR_GATED, nullptr, ws + l.act, ws + l.lin,
                       stream) != hipSuccess)
         return VS_ERR_HIP;
     if (launch_linear(ws + l.act, wt->d_ff, wt->w_down, T, wt->d_ff, d, VS_LINEAR_RESIDUAL, ws + l.h1, h_out, ws + l.lin,
-                      stream) != hipSuccess)
+                      stream, nullptr, nullptr, 0, 0, counters, n_counters) != hipSuccess)
         return VS_ERR_HIP;
     return VS_OK;
 }

@@ -22,11 +22,14 @@
 //   gated      out [T][N/2]: feature 2j is the gate g, 2j+1 the value u of output j:
 //              out_j = bf16(g / (1 + exp(-g)) * u)         (SiLU gate, as in the backbone)
 // With split-K the workgroups leave their fp32 sums in the workspace, in register order (a store
-// instruction writes 1 KB), and a second small kernel adds the shares in index order and does the
-// above; without, the multiplying kernel does it itself.
+// instruction writes 1 KB); the shares are added in index order, and the above done, either by a
+// second small kernel or, when the caller provides arrival counters (the decoder layer does), inside
+// the launch by the workgroups of a block together, each its rows, once the last of them has
+// finished: the same sums in the same order.  Without split-K the multiplying kernel does it itself.
 #include <hip/hip_runtime.h>
 
 #include "vs_internal.h"
+#include "vs_prefill_map.h"
 
 namespace vs {
 namespace {
@@ -53,6 +56,14 @@ struct LinParams {
     int T, N, K, ldx;
     int mode;           // vs_linear_mode
     int ksplit, tiles_per_split;
+    // split-K shares added inside the launch (null: by linear_reduce_kernel).  All shares of a block
+    // then run on one XCD and meet in its L2, exactly as the key splits of the prefill kernel do
+    // (vs_prefill_map.h: unit = block, split = share), counted in and waited for in the same way.
+    unsigned* arrivals;          // one counter per block, kCounterStrideBytes apart, zero between launches
+    unsigned* misplaced;         // pinned host word through which a workgroup reports
+    unsigned long long xcc_of_residue;
+    int xcd_shift, units_per_xcd, n_blocks, max_looks;
+    float inv_ksplit;
 };
 
 // s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14; expcnt, lgkmcnt left at "no wait")
@@ -152,9 +163,22 @@ __global__ __launch_bounds__(kThreads) void linear_kernel(LinParams p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i16 = lane & 15, kq = lane >> 4;
-    const int n0 = blockIdx.x * kTileN;
+    int blk = blockIdx.x, share = blockIdx.y;
+    if (p.arrivals) {
+        // 1-D grid: ids of one residue modulo the number of XCDs go to one XCD, and block b's shares
+        // take consecutive slots of one residue
+        const PrefillSlot at = prefill_slot_of_id(blockIdx.x, p.n_blocks, p.units_per_xcd, p.ksplit, p.inv_ksplit, p.xcd_shift);
+        if (at.unit < 0) return;  // spare ids
+        unsigned xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        if ((xcc & 15u) != (unsigned)((p.xcc_of_residue >> (4 * at.xcd)) & 15u) && threadIdx.x == 0)
+            __hip_atomic_store(p.misplaced, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // (see vs_workspace_init)
+        blk = at.unit;
+        share = at.split;
+    }
+    const int n0 = blk * kTileN;
     const int n_tiles_all = p.K / 64;
-    const int t_begin = blockIdx.y * p.tiles_per_split;
+    const int t_begin = share * p.tiles_per_split;
     const int n_tiles = max(0, min(p.tiles_per_split, n_tiles_all - t_begin));
 
     // ---- global -> LDS.  A load instruction of a wavefront fills 8 rows: lane l -> row l >> 3, 16-byte
@@ -258,12 +282,92 @@ __global__ __launch_bounds__(kThreads) void linear_kernel(LinParams p) {
     }
     // lane (i16, kq) of accumulator (i, ni): rows (mg + 4 i)*16 + 4 kq + 0..3, feature n0 + 16 ni + i16
     if (p.ws) {
-        if (kh != 0) return;
-        // this share's sums, in register order: [split][block][mg][accumulator][lane] x 4 floats
-        f32x4* dst = reinterpret_cast<f32x4*>(p.ws) +
-                     ((((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 4 + mg) * kAccs) * 64 + lane;
+        if (kh != 0 && !p.arrivals) return;
+        if (kh == 0) {
+            // this share's sums, in register order: [split][block][mg][accumulator][lane] x 4 floats
+            f32x4* dst = reinterpret_cast<f32x4*>(p.ws) + ((((int64_t)share * p.n_blocks + blk) * 4 + mg) * kAccs) * 64 + lane;
+            if (p.arrivals) {  // (written through while the kernel runs, not left for the write-back at its end)
 #pragma unroll
-        for (int a = 0; a < kAccs; ++a) dst[a * 64] = acc[a];
+                for (int a = 0; a < kAccs; ++a) __builtin_nontemporal_store(acc[a], &dst[a * 64]);
+            } else {
+#pragma unroll
+                for (int a = 0; a < kAccs; ++a) dst[a * 64] = acc[a];
+            }
+        }
+        if (!p.arrivals) return;
+        // ---- The shares are added inside this launch, by the workgroups of the block together.
+        // Every workgroup's stores above are complete in its XCD's L2 before it counts itself in
+        // (all wavefronts wait for their stores, then the barrier, then the atomic, executed at that
+        // L2: an increment that wraps, so the counter is zero again with the last arrival).  Those
+        // that are not last look at the counter again with read-modify-writes (adding a zero the
+        // compiler cannot see), never served by the compute unit's cache, a bounded number of times,
+        // until it reads zero; then every share of the block is complete in this L2 (these lines are
+        // read nowhere else in the launch, so the loads miss in the compute unit's cache).
+        // Workgroup j of the block then finishes the 16-row sub-tiles j, j + ksplit, ..: its wavefronts
+        // add the shares of their (sub-tile, feature sub-tile) pairs in index order, as
+        // linear_reduce_kernel does, and the rows leave through LDS as below.  A workgroup that has looked max_looks
+        // times in vain reports through the host word of the placement guard and returns. ----
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        __syncthreads();                     // (also: the exchange area has been read)
+        unsigned* const box = reinterpret_cast<unsigned*>(ring);
+        unsigned* const counter = p.arrivals + (int64_t)blk * (kCounterStrideBytes / 4);
+        if (tid == 0) *box = __builtin_amdgcn_atomic_inc32(counter, (unsigned)(p.ksplit - 1), __ATOMIC_RELAXED, "workgroup");
+        __syncthreads();
+        if (*box + 1 != (unsigned)p.ksplit) {
+            unsigned zero = 0;
+            asm volatile("" : "+s"(zero));
+            if (tid == 0) {
+                unsigned ok = 0;
+                for (int n = 0; n < p.max_looks && !ok; ++n) {
+                    ok = __hip_atomic_fetch_add(counter, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0u;
+                    if (!ok) __builtin_amdgcn_s_sleep(2);
+                }
+                box[1] = ok;
+                if (!ok) __hip_atomic_store(p.misplaced, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
+            __syncthreads();
+            if (!box[1]) return;
+        }
+        // this workgroup's sub-tiles: rs = share, share + ksplit, .. below 12 and below T rows
+        const int n_rs = min(kRows / 16, (p.T + 15) >> 4);
+        const int n_mine = share < n_rs ? (n_rs - share + p.ksplit - 1) / p.ksplit : 0;
+        float* const mine = reinterpret_cast<float*>(ring + 1024);  // [n_mine * 16][kTileN + 4]
+        const int64_t step = (int64_t)p.n_blocks * 4 * kAccs * 64;    // f32x4 between shares
+        const int items = n_mine * NSUB;                              // (sub-tile, feature sub-tile) pairs
+        // two items per wavefront and pass, all their shares requested before any is used: with the
+        // plans in use one pass, so one round trip to L2
+        for (int it0 = w; it0 < items; it0 += 16) {
+            const f32x4* src[2];
+            int k_of[2], ni_of[2];
+#pragma unroll
+            for (int b2 = 0; b2 < 2; ++b2) {
+                const int it = min(it0 + 8 * b2, items - 1);
+                k_of[b2] = it / NSUB;
+                ni_of[b2] = it - k_of[b2] * NSUB;
+                const int rs = share + k_of[b2] * p.ksplit, mg_r = rs & 3, i_r = rs >> 2;  // accumulator row i_r of row group mg_r
+                src[b2] = reinterpret_cast<const f32x4*>(p.ws) + (((int64_t)blk * 4 + mg_r) * kAccs + i_r * NSUB + ni_of[b2]) * 64 + lane;
+            }
+            f32x4 sum[2] = {src[0][0], src[1][0]};
+            for (int s0 = 1; s0 < p.ksplit; s0 += 8) {
+                f32x4 v[2][8];
+#pragma unroll
+                for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[b2][u] = src[b2][(int64_t)min(s0 + u, p.ksplit - 1) * step];
+#pragma unroll
+                for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (s0 + u < p.ksplit) sum[b2] += v[b2][u];
+            }
+#pragma unroll
+            for (int b2 = 0; b2 < 2; ++b2)
+                if (it0 + 8 * b2 < items) put_acc<kTileN>(mine, sum[b2], 16 * k_of[b2], 16 * ni_of[b2], lane);
+        }
+        __syncthreads();
+        const int ks = p.ksplit;
+        write_tile<kTileN>(p, mine, 16 * n_mine, n0, tid, kThreads,
+                           [share, ks](int r) { return (share + (r >> 4) * ks) * 16 + (r & 15); });
         return;
     }
     __syncthreads();  // the exchange area has been read: the tile of sums may overwrite it
@@ -342,18 +446,26 @@ struct LinPlan {
     int nsub, ksplit, n_blocks, tiles_per_split;
 };
 
+// The chip the plan is made for: workgroup ids are dealt to 8 XCDs of 32 compute units in turn.  A
+// split plan keeps all shares of a block on one XCD at once (ceil(blocks / 8) blocks x ksplit shares
+// <= 32 workgroups per XCD), so that the shares can be added inside the launch; the plan does not
+// depend on whether they will be, so both ways of adding them see the same shares.
+constexpr int kPlanXcds = 8, kPlanCusPerXcd = 32;
+
 // Block width and split of K: estimated time = rounds through the chip x (tiles of a workgroup x
 // bytes a tile brings into its compute unit) at ~60 GB/s per compute unit, plus, with split-K,
-// the second kernel and the trip of the shares through memory.
+// the trip of the shares through memory and their addition.
 LinPlan make_lin_plan(int T, int N, int K) {
     (void)T;
     const int ktiles = K / 64;
     LinPlan best{4, 1, (N + 63) / 64, ktiles};
     double best_cost = 1e30;
-    for (int nsub : {4, 8, 10}) {
+    for (int nsub : {4, 7, 8, 10}) {
         const int blocks = (N + 16 * nsub - 1) / (16 * nsub);
         for (int ks = 1; ks <= 16 && ks <= ktiles; ++ks) {
-            if (ks > 1 && blocks * ks > 256) break;
+            if (ks > 1 && (blocks * ks > kPlanXcds * kPlanCusPerXcd ||
+                           ((blocks + kPlanXcds - 1) / kPlanXcds) * ks > kPlanCusPerXcd))
+                break;
             const int tps = (ktiles + ks - 1) / ks;
             const int rounds = (blocks * ks + 255) / 256;
             double cost = rounds * (2.0 + tps * (kRows + 16.0 * nsub) * 128.0 / 60e3);  // us
@@ -377,6 +489,10 @@ hipError_t launch_lin(const LinParams& p, const LinPlan& pl, int dev, hipStream_
         if (err != hipSuccess) return err;
         attr_set_on[dev] = true;
     }
+    if (p.arrivals) {  // 1-D grid, the shares of a block on one XCD; they are added inside the launch
+        linear_kernel<NSUB, RING><<<prefill_grid_ids(pl.n_blocks, pl.ksplit, p.xcd_shift), kThreads, kLds, st>>>(p);
+        return hipGetLastError();
+    }
     linear_kernel<NSUB, RING><<<dim3(pl.n_blocks, pl.ksplit), kThreads, kLds, st>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.ksplit == 1) return e;
@@ -394,7 +510,7 @@ size_t linear_workspace_bytes(int32_t n_rows, int32_t K, int32_t N) {
 
 hipError_t launch_linear(const void* x, int32_t ldx, const void* w, int32_t n_rows, int32_t K, int32_t N, int32_t mode,
                          const void* residual, void* out, void* workspace, hipStream_t st, void* out1, void* out2,
-                         int32_t seg0, int32_t seg1) {
+                         int32_t seg0, int32_t seg1, void* arrival_counters, int32_t n_counters) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return hipErrorInvalidDevice;
     const LinPlan pl = make_lin_plan(n_rows, N, K);
@@ -415,8 +531,25 @@ hipError_t launch_linear(const void* x, int32_t ldx, const void* w, int32_t n_ro
     p.mode = mode;
     p.ksplit = pl.ksplit;
     p.tiles_per_split = pl.tiles_per_split;
+    p.n_blocks = pl.n_blocks;
+    p.arrivals = nullptr;
+    p.misplaced = nullptr;
+    p.xcc_of_residue = 0;
+    p.xcd_shift = p.units_per_xcd = p.max_looks = 0;
+    p.inv_ksplit = 1.0f / (float)pl.ksplit;
+    XcdPlacement where;
+    if (arrival_counters && pl.ksplit > 1 && pl.n_blocks <= n_counters && xcd_placement_of_device(dev, &where) &&
+        (1 << where.xcd_shift) == kPlanXcds) {
+        p.arrivals = (unsigned*)arrival_counters;
+        p.misplaced = where.misplaced;
+        p.xcc_of_residue = where.xcc_of_residue;
+        p.xcd_shift = where.xcd_shift;
+        p.units_per_xcd = prefill_units_per_xcd(pl.n_blocks, where.xcd_shift);
+        p.max_looks = where.max_looks;
+    }
     switch (pl.nsub) {
         case 4: return launch_lin<4, 4>(p, pl, dev, st);
+        case 7: return launch_lin<7, 4>(p, pl, dev, st);
         case 8: return launch_lin<8, 3>(p, pl, dev, st);
         default: return launch_lin<10, 3>(p, pl, dev, st);
     }

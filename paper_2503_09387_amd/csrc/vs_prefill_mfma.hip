@@ -1120,6 +1120,17 @@ bool prefill_placement_fault(int dev) {
 
 void prefill_guard_test_mode(int on) { g_tune_guard_test = on; }
 
+bool xcd_placement_of_device(int dev, XcdPlacement* out) {
+    if (dev < 0 || dev >= 16 || g_xcd_shift[dev] < 0 || !g_misplaced_dev[dev] || g_tune_prefill_merge == 2) return false;
+    out->xcd_shift = g_xcd_shift[dev];
+    out->xcc_of_residue = g_xcc_of_residue[dev];
+    if (g_tune_guard_test == 3 && out->xcd_shift > 0)  // (as for the prefill: the table rotated by one XCD)
+        out->xcc_of_residue = (out->xcc_of_residue >> 4) | ((out->xcc_of_residue & 15ull) << (4 * ((1 << out->xcd_shift) - 1)));
+    out->misplaced = g_misplaced_dev[dev];
+    out->max_looks = g_tune_guard_test == 4 ? 0 : 8192;
+    return true;
+}
+
 size_t prefill_mfma_workspace_bytes(const vs_shape& s, int32_t max_q_tokens) {
     const int G = s.n_q_heads / s.n_kv_heads;
     const int64_t M = (int64_t)max_q_tokens * G;

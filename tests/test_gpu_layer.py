@@ -357,3 +357,46 @@ def test_decoder_layer_reports_a_full_cache_before_any_launch():
         vs.frame_decoder_layer(sh, weights, cache, _dev(hidden_rows(63, T, d)), out, ws)
     torch.cuda.synchronize()
     assert "capacity" in str(e.value).lower() and cache.len == 4 and torch.all(out == 7.0)
+
+
+def test_decoder_layer_adds_the_split_k_shares_inside_the_launch_or_not_same_bits():
+    """Inside the layer the split-K shares of a product are added by the workgroups of a block
+    together, in the multiplying launch (they wait for the last of them a bounded number of looks);
+    with tuning value 2 a second kernel adds them, with value 4 the waiting workgroups give up at
+    once: the first two give the same bits, the third reports (VS_ERR_PLACEMENT on the next call)
+    and the calls after it, which use the second kernel, give the same bits again."""
+    s, d, F, T, L = QW, 3584, 2048, 170, 300
+    pk = _pack(layer_weights(71, s, d, F))
+    weights = vs.LayerWeights(pk["norm1"], pk["w_qkv"], pk["w_o"], pk["norm2"], pk["w_gate_up"], pk["w_down"])
+    sh = vs_shape(s)
+    hk, hv = cache_rows(72, s, L, 0.5)
+    hd = _dev(hidden_rows(73, T, d))
+    ws = torch.empty(vs.layer_workspace_bytes(sh, weights, T), dtype=torch.uint8, device=DEV)
+    vs.workspace_init(sh, ws)
+
+    def run():
+        cache = _cache(s, hk, hv, L, L + 1)
+        out = torch.full((T, d), float("nan"), dtype=BF, device=DEV)
+        vs.frame_decoder_layer(sh, weights, cache, hd, out, ws)
+        torch.cuda.synchronize()
+        return out
+
+    inside = run()
+    assert bool(torch.isfinite(inside.float()).all())
+    try:
+        vs.set_tuning(vs.TUNE_PREFILL_MERGE, 2)
+        assert torch.equal(run(), inside), "second-kernel addition differs"
+        vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
+        assert torch.equal(run(), inside)
+        vs.set_tuning(vs.TUNE_PREFILL_MERGE, 4)
+        run()                                   # ends; its output is incomplete
+        vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
+        with pytest.raises(vs.VSError) as err:
+            run()
+        assert err.value.code == 8
+        for _ in range(2):                      # second kernels from now on
+            assert torch.equal(run(), inside)
+    finally:
+        vs.set_tuning(vs.TUNE_PREFILL_MERGE, 0)
+        vs.workspace_init(sh, ws)               # probes the device again: merging inside is back
+    assert torch.equal(run(), inside)
