@@ -409,7 +409,10 @@ typedef struct {
  * h_in, h_out [n_tokens][d_model] (may be the same memory), 1 <= n_tokens <= 192, bf16 only.
  * workspace: vs_layer_workspace_bytes (prepared with vs_workspace_init like every workspace that the
  * attention uses).  Errors as vs_frame_prefill_compact and vs_linear; cache->len grows by one on VS_OK.
- * Seven launches on hip_stream.
+ * Seven launches on hip_stream.  Where a product's input features are shared out over several
+ * workgroups, these add their sums inside the multiplying launch, placed, counted and waited for
+ * exactly as the key splits of the attention are (vs_workspace_init); what they report comes back
+ * the same way, as VS_ERR_PLACEMENT from the next call, after which second kernels add the sums.
  */
 size_t vs_layer_workspace_bytes(const vs_shape *shape, const vs_layer_weights *weights, int32_t n_tokens);
 vs_status vs_frame_decoder_layer(const vs_shape *shape, const vs_layer_weights *weights, vs_cache *cache,
