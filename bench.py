@@ -217,8 +217,8 @@ def main():
             roofline=dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                           frac=achieved / PEAK_BF16_TFLOPS,
                           traffic=TRAFFIC.get("prefill_mfma_kernel"),
-                          kernel="prefill_mfma_kernel<2> (attention + merge of the key splits by the last workgroup "
-                                 "of a row tile + fused carrier compaction)",
+                          kernel="prefill_mfma_kernel<2> (attention + merge of the key splits by the workgroups of a "
+                                 "row tile together + fused carrier compaction)",
                           avg_launch_us=float(launch_s * 1e6), min_launch_us=float(launch_min * 1e6),
                           max_launch_us=float(launch_max * 1e6), launches_timed=n_launch, repeats=R,
                           timing="HIP events on the launch stream around K x 28 attention launches back to back "
@@ -708,11 +708,11 @@ def main():
             ms_per_frame=lwall * 1e3 / LF, us_per_layer=per_layer * 1e6, frames_timed=LF, repeats=R,
             weight_mbytes_per_layer=w_bytes / 1e6, weights_gbs=w_bytes / per_layer / 1e9,
             frac_hbm=w_bytes / per_layer / 1e9 / PEAK_HBM_GBS, tflops=fl_layer / per_layer / 1e12,
-            frac_mfma=fl_layer / per_layer / 1e12 / PEAK_BF16_TFLOPS, launches_per_layer=10,
+            frac_mfma=fl_layer / per_layer / 1e12 / PEAK_BF16_TFLOPS, launches_per_layer=7,
             note="vs_frame_decoder_layer x 28 per frame at the 7B backbone's sizes (d 3584, d_ff 18944, GQA 28/4), "
                  "random-init weights, one separate copy per layer; per layer: RMS norm, Q/K/V GEMM, attention + "
                  "carrier append, output GEMM + residual, RMS norm, gate/up GEMM with the SiLU gate, down GEMM + "
-                 "residual; bytes = the layer's weights once")
+                 "residual (split-K shares added inside the GEMM launches); bytes = the layer's weights once")
         log(f"[bench] 28 decoder layers per frame: {LF / lwall:.1f} frames/s ({lwall * 1e3 / LF:.2f} ms per frame, "
             f"{per_layer * 1e6:.1f} us per layer = {w_bytes / per_layer / 1e9:.0f} GB/s of weights, "
             f"{100 * w_bytes / per_layer / 1e9 / PEAK_HBM_GBS:.1f}% of HBM peak; {fl_layer / per_layer / 1e12:.0f} TFLOP/s)")
