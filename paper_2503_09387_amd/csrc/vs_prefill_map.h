@@ -1,5 +1,7 @@
 // Where the workgroups of a bf16 prefill launch go when the key splits are merged inside the
-// kernel.  Shared by the kernel, the launcher and a host-side test (plain C++, no HIP types).
+// kernel; the dense layers' split-K launches place their workgroups the same way (unit = block of
+// output features, split = share of the input features).  Shared by the kernels, the launchers
+// and a host-side test (plain C++, no HIP types).
 //
 // The merge goes through the L2 cache that the compute units of one XCD share, so all splits
 // of a unit = (KV head, frame, row tile) must run on one XCD.  The hardware deals workgroup ids

@@ -1,5 +1,6 @@
-// Host-side check of the workgroup id -> (unit, split, XCD) mapping of the bf16 prefill launch
-// (vs_prefill_map.h), for every (units, splits, number of XCDs) the launch planner can emit:
+// Host-side check of the workgroup id -> (unit, split, XCD) mapping of the bf16 prefill launch and of
+// the dense layers' split-K launches (vs_prefill_map.h; there unit = block of output features, split =
+// share of the input features), for every (units, splits, number of XCDs) the launch planners can emit:
 // every (unit, split) pair is named by exactly one id of the grid, all splits of a unit carry
 // ids of one residue modulo the number of XCDs, spare ids name no unit, and units that follow
 // one another share a residue as long as that XCD has room.
@@ -11,7 +12,7 @@
 int main() {
     long checked = 0;
     for (int shift = 0; shift <= 4; ++shift) {
-        for (int nsplit = 1; nsplit <= 8; ++nsplit) {
+        for (int nsplit = 1; nsplit <= 16; ++nsplit) {
             const float inv_nsplit = 1.0f / (float)nsplit;
             for (int units = 1; units <= 1100; units += (units < 300 ? 1 : 37)) {
                 const int upx = vs::prefill_units_per_xcd(units, shift);
