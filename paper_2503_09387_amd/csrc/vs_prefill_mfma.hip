@@ -148,6 +148,57 @@ __device__ __forceinline__ PartScale part_scale(float big) {
 // values the compiler sees; every block names those registers as clobbered.
 #include "vs_prefill_asm.inc"
 
+// The merge of any number of per-split partials of one row, eight of its features at a time: splits
+// are taken in chunks of 8 in index order; everything of a chunk is requested before anything is used,
+// and chunks are merged like sub-blocks of the online softmax, against a running reference (for up to
+// 8 splits: one pass against their largest reference).  ml_of(u) -> (reference, sum, inverse scale, -)
+// and v_of(u) -> the 8 stored features of split u.  One piece of code for the second kernel and for the
+// in-kernel merge of more than 8 splits, so that both give the same bits.
+template <typename MlOf, typename VOf>
+__device__ __forceinline__ void merge_splits_chunked(int nsplit, MlOf ml_of, VOf v_of, float (&acc)[8], float& denom) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    float m_run = -INFINITY;
+    denom = 0.f;
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+        float ms[8], ls[8], isc[8];
+        f16x8 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            ms[u] = -INFINITY;
+            ls[u] = 0.f;
+            isc[u] = 0.f;
+            if (s0 + u < nsplit) {
+                const float4 ml = ml_of(s0 + u);
+                ms[u] = ml.x;
+                ls[u] = ml.y;
+                isc[u] = ml.z;
+                v[u] = v_of(s0 + u);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[u][j] = (_Float16)0.f;
+            }
+        }
+        float m_new = m_run;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) m_new = fmaxf(m_new, ms[u]);
+        if (m_new == -INFINITY) continue;  // nothing in these splits (and nothing before)
+        const float keep = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 for the first chunk with content
+        denom *= keep;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] *= keep;
+        m_run = m_new;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float w = (ms[u] != -INFINITY) ? __builtin_amdgcn_exp2f(ms[u] - m_new) * ls[u] : 0.f;
+            denom += w;
+            const float wo = w * isc[u];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += wo * (float)v[u][j];
+        }
+    }
+}
+
 template <int NKG>
 __global__ __launch_bounds__(kGroupThreads * NKG) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void prefill_mfma_kernel(PrefillParams p) {
@@ -721,8 +772,9 @@ void prefill_mfma_kernel(PrefillParams p) {
             // compute unit's cache, a bounded number of times: a zero says that the last one has
             // arrived.  Whoever knows that, knows that every partial result of the unit is complete
             // in this L2, and merges its own pieces: of the unit's 4 row groups x 8 pieces of 16
-            // features per lane, wavefront w of split j takes those from (4 j + w) * ppw on, ppw = 1,
-            // 2 or 4, so that one round trip brings in all it needs.  The sums are those of the
+            // features per lane, wavefront w of split j takes those from (w nsplit + j) * ppw on, ppw = 1,
+            // 2 or 4, so that the work is spread over the unit's compute units and (up to 8 splits) one
+            // round trip brings in all a wavefront needs.  The sums are those of the
             // single-workgroup merge below and of prefill_combine_kernel, in the same order.  A
             // workgroup that has looked max_looks times in vain (its unit's workgroups are not all
             // running at once: the device is shared, or part of it is masked) reports through the
@@ -744,9 +796,8 @@ void prefill_mfma_kernel(PrefillParams p) {
                 __syncthreads();
                 if (!*seen_box) return;
             }
-            const int n_waves = 4 * nsplit;
-            const int ppw = n_waves >= 32 ? 1 : n_waves >= 16 ? 2 : 4;  // pieces per wavefront
-            const int first = (split * 4 + w) * ppw;                     // of the unit's 4 x 8 pieces
+            const int ppw = nsplit >= 8 ? 1 : nsplit >= 4 ? 2 : 4;  // pieces per wavefront
+            const int first = (w * nsplit + split) * ppw;            // of the unit's 4 x 8 pieces: dealt to the workgroups in turn
             if (first >= 32) return;
             const int rg = first >> 3, piece0 = first & 7;
             const int m = rt * BM + rg * 32 + l32;  // the lane's row of the packed rows
@@ -803,6 +854,25 @@ void prefill_mfma_kernel(PrefillParams p) {
                 }
             };
             using std::integral_constant;
+            if (nsplit > 8) {  // one piece, splits in chunks of 8, exactly as prefill_combine_kernel does it
+                float acc[8], denom;
+                merge_splits_chunked(
+                    nsplit, [&](int u) { return *reinterpret_cast<const float4*>(ml0 + u * ml_step); },
+                    [&](int u) { return po0[u * po_step]; }, acc, denom);
+                if (row_ok) {
+                    const float inv = 1.0f / denom;
+                    bf16x4 w0, w1;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        w0[j] = (__bf16)(acc[j] * inv);
+                        w1[j] = (__bf16)(acc[4 + j] * inv);
+                    }
+                    __bf16* dst = orow + 16 * piece0 + 4 * hi;
+                    *reinterpret_cast<bf16x4*>(dst) = w0;
+                    *reinterpret_cast<bf16x4*>(dst + 8) = w1;
+                }
+                return;
+            }
             switch (nsplit) {
                 case 2: share(integral_constant<int, 2>{}, integral_constant<int, 4>{}); break;
                 case 3: share(integral_constant<int, 3>{}, integral_constant<int, 4>{}); break;
@@ -916,52 +986,15 @@ __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
     if (rt * BM + rg * 32 >= p.M) return;  // whole block beyond the rows
     const int r = rt * BM + rg * 32 + l32;
     const int rr = min(r, p.M - 1);
-    float acc[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-    // Up to 8 splits at a time: everything of a chunk is requested before anything is used (one
-    // memory round trip for the usual case), and chunks are merged like sub-blocks of the online
-    // softmax, against the running reference m_run.
-    float m_run = -INFINITY, denom = 0.f;
-    for (int s0 = 0; s0 < p.nsplit; s0 += 8) {
-        float ms[8], ls[8], isc[8];
-        f16x8 v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            ms[u] = -INFINITY;
-            ls[u] = 0.f;
-            isc[u] = 0.f;
-            if (s0 + u < p.nsplit) {
-                const int c = (s0 + u) * HF + gf;
-                const float4 ml = *reinterpret_cast<const float4*>(p.part_ml + ((int64_t)c * p.m_pad + rr) * 4);
-                ms[u] = ml.x;
-                ls[u] = ml.y;
-                isc[u] = ml.z;
-                const int64_t unit = (int64_t)c * p.n_row_tiles + rt;
-                v[u] = (reinterpret_cast<const f16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane)[(db * 2 + h2) * 64];
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) v[u][j] = (_Float16)0.f;
-            }
-        }
-        float m_new = m_run;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) m_new = fmaxf(m_new, ms[u]);
-        if (m_new == -INFINITY) continue;  // nothing in these splits (and nothing before)
-        const float keep = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 for the first chunk with content
-        denom *= keep;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] *= keep;
-        m_run = m_new;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float w = (ms[u] != -INFINITY) ? __builtin_amdgcn_exp2f(ms[u] - m_new) * ls[u] : 0.f;
-            denom += w;
-            const float wo = w * isc[u];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] += wo * (float)v[u][j];
-        }
-    }
+    float acc[8], denom;
+    merge_splits_chunked(
+        p.nsplit,
+        [&](int u) { return *reinterpret_cast<const float4*>(p.part_ml + ((int64_t)(u * HF + gf) * p.m_pad + rr) * 4); },
+        [&](int u) {
+            const int64_t unit = (int64_t)(u * HF + gf) * p.n_row_tiles + rt;
+            return (reinterpret_cast<const f16x8*>(p.part_o) + (unit * 4 + rg) * (8 * 64) + lane)[(db * 2 + h2) * 64];
+        },
+        acc, denom);
     if (r >= p.M) return;
     const float inv = 1.0f / denom;
     const int t = r / p.G, hl = r - t * p.G;
@@ -1042,7 +1075,9 @@ Plan make_plan(const vs_shape& s, int n_tokens, int len, int n_frames) {
     if (g_tune_prefill_splits) ns = g_tune_prefill_splits < max_tiles ? g_tune_prefill_splits : (max_tiles > 0 ? max_tiles : 1);
     pl.nsplit = ns;
     int dev = 0;
-    pl.merge_inside = g_tune_prefill_merge != 2 && ns > 1 && ns <= 8 && pl.n_row_tiles * n_frames <= kMaxRowTiles &&
+    // (more than 8 splits: only the shared merge knows how)
+    pl.merge_inside = g_tune_prefill_merge != 2 && ns > 1 && (ns <= 8 || (pl.kvg == 2 && g_tune_prefill_merge != 1)) &&
+                      ns <= kMaxPrefillSplits && pl.n_row_tiles * n_frames <= kMaxRowTiles &&
                       hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && g_xcd_shift[dev] >= 0 && g_misplaced[dev];
     return pl;
 }

@@ -327,7 +327,9 @@ def test_prefill_result_does_not_depend_on_the_split(kv_groups):
 
 
 @pytest.mark.parametrize("L,T,splits", [(4424, 170, 0), (1500, 170, 0), (1500, 170, 3), (3000, 300, 8), (700, 40, 2),
-                                          (200, 170, 0), (264, 170, 3), (100, 20, 2)])
+                                          (200, 170, 0), (264, 170, 3), (100, 20, 2),
+                                          # more than 8 splits (questions of a few tokens; several rounds of workgroups)
+                                          (4552, 16, 0), (4552, 64, 0), (1500, 170, 12), (3000, 170, 32), (2100, 30, 9)])
 def test_prefill_merge_inside_the_kernel_equals_the_second_kernel(L, T, splits):
     """Split results are merged inside the attention kernel, by the workgroups of a row tile together
     once the last of them has arrived (the library's choice) or by that last one alone, or by a
