@@ -154,35 +154,21 @@ __device__ __forceinline__ PartScale part_scale(float big) {
 // 8 splits: one pass against their largest reference).  ml_of(u) -> (reference, sum, inverse scale, -)
 // and v_of(u) -> the 8 stored features of split u.  One piece of code for the second kernel and for the
 // in-kernel merge of more than 8 splits, so that both give the same bits.
-template <typename MlOf, typename VOf>
+// NC > 0: the loads of NC chunks at a time are requested before the first of them is used (one round
+// trip for up to 8 NC splits); NC = 0: a chunk's loads at the start of its turn.  The arithmetic
+// is the same either way.
+template <int NC, typename MlOf, typename VOf>
 __device__ __forceinline__ void merge_splits_chunked(int nsplit, MlOf ml_of, VOf v_of, float (&acc)[8], float& denom) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     float m_run = -INFINITY;
     denom = 0.f;
-    for (int s0 = 0; s0 < nsplit; s0 += 8) {
-        float ms[8], ls[8], isc[8];
-        f16x8 v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            ms[u] = -INFINITY;
-            ls[u] = 0.f;
-            isc[u] = 0.f;
-            if (s0 + u < nsplit) {
-                const float4 ml = ml_of(s0 + u);
-                ms[u] = ml.x;
-                ls[u] = ml.y;
-                isc[u] = ml.z;
-                v[u] = v_of(s0 + u);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) v[u][j] = (_Float16)0.f;
-            }
-        }
+    // one chunk: references, sums, inverse scales and stored features of 8 splits (absent ones: -inf, 0, 0, 0)
+    auto chunk = [&](const float (&ms)[8], const float (&ls)[8], const float (&isc)[8], const f16x8 (&v)[8]) {
         float m_new = m_run;
 #pragma unroll
         for (int u = 0; u < 8; ++u) m_new = fmaxf(m_new, ms[u]);
-        if (m_new == -INFINITY) continue;  // nothing in these splits (and nothing before)
+        if (m_new == -INFINITY) return;  // nothing in these splits (and nothing before)
         const float keep = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 for the first chunk with content
         denom *= keep;
 #pragma unroll
@@ -195,6 +181,42 @@ __device__ __forceinline__ void merge_splits_chunked(int nsplit, MlOf ml_of, VOf
             const float wo = w * isc[u];
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] += wo * (float)v[u][j];
+        }
+    };
+    constexpr int kChunks = NC > 0 ? NC : 1;
+    float ms[kChunks][8], ls[kChunks][8], isc[kChunks][8];
+    f16x8 v[kChunks][8];
+    auto fetch = [&](int c, int s0) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            ms[c][u] = -INFINITY;
+            ls[c][u] = 0.f;
+            isc[c][u] = 0.f;
+            if (s0 + u < nsplit) {
+                const float4 ml = ml_of(s0 + u);
+                ms[c][u] = ml.x;
+                ls[c][u] = ml.y;
+                isc[c][u] = ml.z;
+                v[c][u] = v_of(s0 + u);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[c][u][j] = (_Float16)0.f;
+            }
+        }
+    };
+    if constexpr (NC > 0) {
+        for (int g0 = 0; g0 < nsplit; g0 += 8 * NC) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                if (g0 + 8 * c < nsplit) fetch(c, g0 + 8 * c);
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                if (g0 + 8 * c < nsplit) chunk(ms[c], ls[c], isc[c], v[c]);
+        }
+    } else {
+        for (int s0 = 0; s0 < nsplit; s0 += 8) {
+            fetch(0, s0);
+            chunk(ms[0], ls[0], isc[0], v[0]);
         }
     }
 }
@@ -856,9 +878,9 @@ void prefill_mfma_kernel(PrefillParams p) {
             using std::integral_constant;
             if (nsplit > 8) {  // one piece, splits in chunks of 8, exactly as prefill_combine_kernel does it
                 float acc[8], denom;
-                merge_splits_chunked(
-                    nsplit, [&](int u) { return *reinterpret_cast<const float4*>(ml0 + u * ml_step); },
-                    [&](int u) { return po0[u * po_step]; }, acc, denom);
+                auto ml_of = [&](int u) { return *reinterpret_cast<const float4*>(ml0 + u * ml_step); };
+                auto v_of = [&](int u) { return po0[u * po_step]; };
+                merge_splits_chunked<2>(nsplit, ml_of, v_of, acc, denom);
                 if (row_ok) {
                     const float inv = 1.0f / denom;
                     bf16x4 w0, w1;
@@ -987,7 +1009,7 @@ __global__ __launch_bounds__(64) void prefill_combine_kernel(PrefillParams p) {
     const int r = rt * BM + rg * 32 + l32;
     const int rr = min(r, p.M - 1);
     float acc[8], denom;
-    merge_splits_chunked(
+    merge_splits_chunked<0>(
         p.nsplit,
         [&](int u) { return *reinterpret_cast<const float4*>(p.part_ml + ((int64_t)(u * HF + gf) * p.m_pad + rr) * 4); },
         [&](int u) {
