@@ -787,7 +787,7 @@ void prefill_mfma_kernel(PrefillParams p) {
         if (tid == 0) *box = __builtin_amdgcn_atomic_inc32(counter, (unsigned)(nsplit - 1), __ATOMIC_RELAXED, "workgroup");
         __syncthreads();
         const unsigned before = *box;
-        if (NKG == 2 && p.share_merge) {
+        if (p.share_merge) {
             // ---- The merge shared by the workgroups of the unit.  Those that are not the last to
             // arrive look at the counter again, with read-modify-writes (adding a zero the compiler
             // cannot see), which are executed at the L2 like the count itself and never served by the
@@ -818,7 +818,8 @@ void prefill_mfma_kernel(PrefillParams p) {
                 __syncthreads();
                 if (!*seen_box) return;
             }
-            const int ppw = nsplit >= 8 ? 1 : nsplit >= 4 ? 2 : 4;  // pieces per wavefront
+            // pieces per wavefront: the fewest that cover the 32 pieces with the unit's 2 NKG nsplit wavefronts
+            const int ppw = NKG == 2 ? (nsplit >= 8 ? 1 : nsplit >= 4 ? 2 : 4) : (nsplit >= 16 ? 1 : nsplit >= 8 ? 2 : nsplit >= 4 ? 4 : 8);
             const int first = (w * nsplit + split) * ppw;            // of the unit's 4 x 8 pieces: dealt to the workgroups in turn
             if (first >= 32) return;
             const int rg = first >> 3, piece0 = first & 7;
@@ -876,33 +877,47 @@ void prefill_mfma_kernel(PrefillParams p) {
                 }
             };
             using std::integral_constant;
-            if (nsplit > 8) {  // one piece, splits in chunks of 8, exactly as prefill_combine_kernel does it
-                float acc[8], denom;
+            if (nsplit > 8) {  // piece by piece, splits in chunks of 8, exactly as prefill_combine_kernel does it
                 auto ml_of = [&](int u) { return *reinterpret_cast<const float4*>(ml0 + u * ml_step); };
-                auto v_of = [&](int u) { return po0[u * po_step]; };
-                merge_splits_chunked<2>(nsplit, ml_of, v_of, acc, denom);
-                if (row_ok) {
-                    const float inv = 1.0f / denom;
-                    bf16x4 w0, w1;
+                for (int k = 0; k < ppw; ++k) {
+                    float acc[8], denom;
+                    auto v_of = [&](int u) { return po0[u * po_step + k * 64]; };
+                    merge_splits_chunked<2>(nsplit, ml_of, v_of, acc, denom);
+                    if (row_ok) {
+                        const float inv = 1.0f / denom;
+                        bf16x4 w0, w1;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        w0[j] = (__bf16)(acc[j] * inv);
-                        w1[j] = (__bf16)(acc[4 + j] * inv);
+                        for (int j = 0; j < 4; ++j) {
+                            w0[j] = (__bf16)(acc[j] * inv);
+                            w1[j] = (__bf16)(acc[4 + j] * inv);
+                        }
+                        __bf16* dst = orow + 16 * (piece0 + k) + 4 * hi;
+                        *reinterpret_cast<bf16x4*>(dst) = w0;
+                        *reinterpret_cast<bf16x4*>(dst + 8) = w1;
                     }
-                    __bf16* dst = orow + 16 * piece0 + 4 * hi;
-                    *reinterpret_cast<bf16x4*>(dst) = w0;
-                    *reinterpret_cast<bf16x4*>(dst + 8) = w1;
                 }
                 return;
             }
-            switch (nsplit) {
-                case 2: share(integral_constant<int, 2>{}, integral_constant<int, 4>{}); break;
-                case 3: share(integral_constant<int, 3>{}, integral_constant<int, 4>{}); break;
-                case 4: share(integral_constant<int, 4>{}, integral_constant<int, 2>{}); break;
-                case 5: share(integral_constant<int, 5>{}, integral_constant<int, 2>{}); break;
-                case 6: share(integral_constant<int, 6>{}, integral_constant<int, 2>{}); break;
-                case 7: share(integral_constant<int, 7>{}, integral_constant<int, 2>{}); break;
-                default: share(integral_constant<int, 8>{}, integral_constant<int, 1>{}); break;
+            if constexpr (NKG == 2) {
+                switch (nsplit) {
+                    case 2: share(integral_constant<int, 2>{}, integral_constant<int, 4>{}); break;
+                    case 3: share(integral_constant<int, 3>{}, integral_constant<int, 4>{}); break;
+                    case 4: share(integral_constant<int, 4>{}, integral_constant<int, 2>{}); break;
+                    case 5: share(integral_constant<int, 5>{}, integral_constant<int, 2>{}); break;
+                    case 6: share(integral_constant<int, 6>{}, integral_constant<int, 2>{}); break;
+                    case 7: share(integral_constant<int, 7>{}, integral_constant<int, 2>{}); break;
+                    default: share(integral_constant<int, 8>{}, integral_constant<int, 1>{}); break;
+                }
+            } else {
+                switch (nsplit) {
+                    case 2: share(integral_constant<int, 2>{}, integral_constant<int, 8>{}); break;
+                    case 3: share(integral_constant<int, 3>{}, integral_constant<int, 8>{}); break;
+                    case 4: share(integral_constant<int, 4>{}, integral_constant<int, 4>{}); break;
+                    case 5: share(integral_constant<int, 5>{}, integral_constant<int, 4>{}); break;
+                    case 6: share(integral_constant<int, 6>{}, integral_constant<int, 4>{}); break;
+                    case 7: share(integral_constant<int, 7>{}, integral_constant<int, 4>{}); break;
+                    default: share(integral_constant<int, 8>{}, integral_constant<int, 2>{}); break;
+                }
             }
             return;
         }
@@ -1098,7 +1113,7 @@ Plan make_plan(const vs_shape& s, int n_tokens, int len, int n_frames) {
     pl.nsplit = ns;
     int dev = 0;
     // (more than 8 splits: only the shared merge knows how)
-    pl.merge_inside = g_tune_prefill_merge != 2 && ns > 1 && (ns <= 8 || (pl.kvg == 2 && g_tune_prefill_merge != 1)) &&
+    pl.merge_inside = g_tune_prefill_merge != 2 && ns > 1 && (ns <= 8 || g_tune_prefill_merge != 1) &&
                       ns <= kMaxPrefillSplits && pl.n_row_tiles * n_frames <= kMaxRowTiles &&
                       hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && g_xcd_shift[dev] >= 0 && g_misplaced[dev];
     return pl;
@@ -1277,7 +1292,7 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
         if (g_tune_guard_test == 3 && p.xcd_shift > 0)  // entry r names the XCD of residue r + 1: every workgroup is "misplaced"
             p.xcc_of_residue = (p.xcc_of_residue >> 4) | ((p.xcc_of_residue & 15ull) << (4 * ((1 << p.xcd_shift) - 1)));
         p.misplaced = g_misplaced_dev[dev];
-        if (g_tune_prefill_merge != 1 && pl.kvg == 2) {
+        if (g_tune_prefill_merge != 1) {
             p.share_merge = 1;
             p.max_looks = g_tune_guard_test == 4 ? 0 : 8192;  // ~0.3 us a look: some milliseconds at most
         }
