@@ -563,8 +563,8 @@ def main():
                 f"{flf / tf / 1e12:.0f} TFLOP/s ({100 * flf / tf / 1e12 / PEAK_BF16_TFLOPS:.1f}% of bf16 peak)")
             del fcaches, wsf
         extras["runs_of_frames"] = dict(**fr, note="vs_frames_prefill_attn over 28 layers, same inputs every call (warm), "
-                                                  "HIP events around 6 x 28 calls; includes the carrier gather launch and "
-                                                  "the merge; catch-up mode, not the streamed metric")
+                                                  "HIP events around 6 x 28 calls; one launch per call (carriers appended and "
+                                                  "splits merged inside it); catch-up mode, not the streamed metric")
 
     if "question" in parts:
         # the question after the video (Section 3.3, decoding phase): Tq text tokens over the rows that

@@ -104,8 +104,9 @@ struct PrefillParams {
     int max_looks;
     float inv_row_tiles;
     // A run of F frames (semantic-aware mask, Section 3.4): frame a has its own T rows of q, kf,
-    // vf and out, and sees L + a retained rows (the carriers of the frames before it have been
-    // appended to the cache ahead of this launch).  F = 1: the single frame.
+    // vf and out, and sees L + a retained rows: the L rows of the cache and the carriers (last rows)
+    // of the frames before it, which it reads from kf / vf; the launch also copies all F carriers
+    // behind the cache's rows.  F = 1: the single frame.
     int F;
     float inv_frame_tiles;    // 1 / (F * row tiles)
 };
@@ -275,7 +276,11 @@ void prefill_mfma_kernel(PrefillParams p) {
         frame = div_small(blockIdx.z, p.n_row_tiles, p.inv_row_tiles);
         rt = blockIdx.z - frame * p.n_row_tiles;
     }
-    // the frame's own tensors and retained rows
+    // the frame's own tensors and retained rows: Lc rows in the cache, then the carriers of the
+    // run's earlier frames (keys Lc .. L-1, read from the run's own K/V: row T-1 of frame j - Lc)
+    const int Lc = L;
+    const char* const kf0 = kf;
+    const char* const vf0 = vf;
     L += frame;
     qbase += (int64_t)frame * T * p.Hq * (D * 2);
     kf += (int64_t)frame * T * Hkv * kRowBytes;
@@ -304,7 +309,7 @@ void prefill_mfma_kernel(PrefillParams p) {
     // state of the pipeline sees plain tiles only.)
     const int n_lanes = nsplit * NKG;
     const float inv_lanes = NKG == 1 ? inv_nsplit : 0.5f * inv_nsplit;
-    const int n_plain = L / BN;             // tiles of cache rows only (<= n_tiles)
+    const int n_plain = Lc / BN;            // tiles of cache rows only (<= n_tiles)
     const int n_frame = n_tiles - n_plain;
     const bool small = n_tiles < (1 << 22);
     const int q_all = small ? div_small(n_tiles, n_lanes, inv_lanes) : n_tiles / n_lanes;
@@ -347,7 +352,7 @@ void prefill_mfma_kernel(PrefillParams p) {
         const int tile = tile_of(s);
         char* dst = (is_v ? v_ring : k_ring) + (s & 1) * kTileBytes + rb * (8 * 1024);
         const int j0 = tile * BN + rb * 32;  // first row this wave loads
-        if (tile * BN + BN <= L) {
+        if (tile * BN + BN <= Lc) {
             const char* src = (is_v ? vc : kc) + ((int64_t)j0 * Hkv + g) * kRowBytes;
 #pragma unroll
             for (int u = 0; u < 8; ++u)
@@ -358,8 +363,9 @@ void prefill_mfma_kernel(PrefillParams p) {
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int j = min(j0 + 4 * u + lr, L + T - 1);
-                const char* row = (j < L) ? (is_v ? vc : kc) + ((int64_t)j * Hkv + g) * kRowBytes
-                                          : (is_v ? vf : kf) + ((int64_t)(j - L) * Hkv + g) * kRowBytes;
+                const char* row = (j < Lc) ? (is_v ? vc : kc) + ((int64_t)j * Hkv + g) * kRowBytes
+                                  : (j < L) ? (is_v ? vf0 : kf0) + (((int64_t)(j - Lc) * T + (T - 1)) * Hkv + g) * kRowBytes
+                                            : (is_v ? vf : kf) + ((int64_t)(j - L) * Hkv + g) * kRowBytes;
                 const int piece = is_v ? (ls ^ (lr << 1)) : (ls ^ lr ^ ((u & 3) << 2));
                 load_to_lds16(row + (piece << 4), dst + u * 1024);
             }
@@ -549,7 +555,7 @@ void prefill_mfma_kernel(PrefillParams p) {
         // K of the group's second tile and V of its first are requested on the way: from inside
         // the first two blocks, between their matrix instructions, when they are plain cache tiles.
         // sub-block 0: raw scores
-        if (n_my > 1 && tile_of(1) * BN + BN <= L) {
+        if (n_my > 1 && tile_of(1) * BN + BN <= Lc) {
             const unsigned long long ksrc = (unsigned long long)(kc + ((int64_t)(tile_of(1) * BN + rb * 32) * Hkv + g) * kRowBytes);
             asm volatile(VS_ASM_QK0_LOADS
                          :
@@ -562,7 +568,7 @@ void prefill_mfma_kernel(PrefillParams p) {
         // step 0 = QK(1) | SM(0) against the reference 0 (fine whenever the scaled scores are
         // moderate; otherwise commit() redoes it exactly)
         m_ref[0] = m_ref[1] = 0.f;
-        if (tile_of(0) * BN + BN <= L) {
+        if (tile_of(0) * BN + BN <= Lc) {
             const unsigned long long vsrc = (unsigned long long)(vc + ((int64_t)(tile_of(0) * BN + rb * 32) * Hkv + g) * kRowBytes);
             float sum0_, sum1_;
             unsigned long long flag_;
@@ -588,8 +594,8 @@ void prefill_mfma_kernel(PrefillParams p) {
         // tiles to stage now: K of tile s+2, V of tile s+1.  When both lie inside the cache rows
         // the first block issues the loads itself, between its matrix instructions.
         // (the block that can do that is the unmasked one: tile s must be a plain tile too)
-        const bool loads_inside = s + 2 < n_my && tile_of(s + 2) * BN + BN <= L && tile_of(s + 1) * BN + BN <= L &&
-                                  tile_of(s) * BN + BN <= L;
+        const bool loads_inside = s + 2 < n_my && tile_of(s + 2) * BN + BN <= Lc && tile_of(s + 1) * BN + BN <= Lc &&
+                                  tile_of(s) * BN + BN <= Lc;
         if (!loads_inside) {
             issue(s + 2, false);
             issue(s + 1, true);
@@ -649,7 +655,17 @@ void prefill_mfma_kernel(PrefillParams p) {
     // copied into the cache, 16 bytes per thread, the workgroups of the launch taking turns (the
     // carrier's 1 KB is done by the first one alone; no workgroup of this launch reads the
     // cache rows written here)
-    if (p.k_append_dst) {
+    if (p.k_append_dst && p.F > 1) {
+        // a run: row T-1 of every frame goes behind the cache's rows, frame f to row Lc + f
+        const int c16 = kv_row_bytes / 16, n16 = p.F * c16;
+        const int n_thr = kGroupThreads * NKG, n_wgs = p.n_row_tiles * nsplit * HF;
+        for (int ch = wg_id * n_thr + tid; ch < n16; ch += n_wgs * n_thr) {
+            const int f = ch / c16;
+            const int64_t from = ((int64_t)f * T + (T - 1)) * c16 + (ch - f * c16);
+            reinterpret_cast<uint4*>(p.k_append_dst)[ch] = reinterpret_cast<const uint4*>(kf0)[from];
+            reinterpret_cast<uint4*>(p.v_append_dst)[ch] = reinterpret_cast<const uint4*>(vf0)[from];
+        }
+    } else if (p.k_append_dst) {
         const int n16 = (T - p.append_first) * (kv_row_bytes / 16);
         const uint4* ksrc = reinterpret_cast<const uint4*>(kf + (int64_t)p.append_first * kv_row_bytes);
         const uint4* vsrc = reinterpret_cast<const uint4*>(vf + (int64_t)p.append_first * kv_row_bytes);
@@ -1225,17 +1241,6 @@ int prefill_frames_splits(const vs_shape& s, int32_t n_frames, int32_t n_tokens,
     return make_plan(s, n_tokens, len, n_frames).nsplit;
 }
 
-__global__ __launch_bounds__(64) void gather_carriers_kernel(const uint4* __restrict__ kf, const uint4* __restrict__ vf,
-                                                             uint4* __restrict__ kdst, uint4* __restrict__ vdst,
-                                                             int T, int row16) {
-    // frame blockIdx.x: its last row (the carrier) becomes retained row blockIdx.x behind the old ones
-    const int64_t src = ((int64_t)blockIdx.x * T + (T - 1)) * row16, dst = (int64_t)blockIdx.x * row16;
-    for (int i = threadIdx.x; i < row16; i += 64) {
-        kdst[dst + i] = kf[src + i];
-        vdst[dst + i] = vf[src + i];
-    }
-}
-
 hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc, int32_t len,
                                const void* q, const void* kf, const void* vf, int32_t n_tokens,
                                void* out, void* k_append_dst, void* v_append_dst, void* counters,
@@ -1272,16 +1277,6 @@ hipError_t launch_prefill_mfma(const vs_shape& s, const void* kc, const void* vc
     p.inv_row_tiles = 1.0f / (float)pl.n_row_tiles;
     p.F = n_frames;
     p.inv_frame_tiles = 1.0f / (float)(pl.n_row_tiles * n_frames);
-    if (n_frames > 1) {
-        // the carriers of the run's frames go behind the retained rows first: frame a then reads
-        // len + a rows, exactly what it would find if the frames came one call at a time
-        p.k_append_dst = p.v_append_dst = nullptr;
-        const int row16 = s.n_kv_heads * kRowBytes / 16;
-        gather_carriers_kernel<<<n_frames, 64, 0, st>>>((const uint4*)kf, (const uint4*)vf, (uint4*)k_append_dst,
-                                                        (uint4*)v_append_dst, n_tokens, row16);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
     if (pl.merge_inside && counters) {
         int dev = 0;
         (void)hipGetDevice(&dev);
