@@ -70,6 +70,8 @@ struct ShiftParams {
 
 __global__ __launch_bounds__(kShiftThreads) void bank_shift_kernel(ShiftParams p) {
     __shared__ int s_victim;
+    __shared__ double s_cos[kShiftThreads / 64];
+    __shared__ int s_idx[kShiftThreads / 64];
     const int tid = threadIdx.x;
     const int64_t col = (int64_t)blockIdx.x * 1024 + (tid & 63) * 16;  // this thread's 16 bytes of a row
     const int lr = tid >> 6;
@@ -85,17 +87,40 @@ __global__ __launch_bounds__(kShiftThreads) void bank_shift_kernel(ShiftParams p
     }
     int victim;
     if (p.cosines) {
-        // largest cosine, of equal ones the smallest index: every thread scans the same M values
-        if (tid == 0) {
-            int best = 0;
-            double best_cos = p.cosines[0];
-            for (int i = 1; i < p.M; ++i) {
-                const double c = p.cosines[i];
-                if (c > best_cos) {
-                    best = i;
-                    best_cos = c;
-                }
+        // largest cosine, of equal ones the smallest index: thread t looks at cosines t, t + 256, ..,
+        // the candidates of a wavefront meet by lane exchanges, those of the wavefronts in LDS
+        double best_cos = 0.0;
+        int best = 0x7fffffff;  // (none yet)
+        for (int i = tid; i < p.M; i += kShiftThreads) {
+            const double c = p.cosines[i];
+            if (best == 0x7fffffff || c > best_cos) {
+                best = i;
+                best_cos = c;
             }
+        }
+        auto better = [](double c_b, int i_b, double c_a, int i_a) {  // does candidate b beat candidate a?
+            return i_b != 0x7fffffff && (i_a == 0x7fffffff || c_b > c_a || (c_b == c_a && i_b < i_a));
+        };
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const double c_o = __shfl_xor(best_cos, off);
+            const int i_o = __shfl_xor(best, off);
+            if (better(c_o, i_o, best_cos, best)) {
+                best_cos = c_o;
+                best = i_o;
+            }
+        }
+        if ((tid & 63) == 0) {
+            s_cos[tid >> 6] = best_cos;
+            s_idx[tid >> 6] = best;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w2 = 1; w2 < kShiftThreads / 64; ++w2)
+                if (better(s_cos[w2], s_idx[w2], best_cos, best)) {
+                    best_cos = s_cos[w2];
+                    best = s_idx[w2];
+                }
             s_victim = best;
         }
         __syncthreads();
